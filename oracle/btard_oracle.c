@@ -1,0 +1,323 @@
+/*
+ * fp64 CPU oracle for the robust-aggregation hot path of Byzantine-tolerant
+ * all-reduce ("Secure Distributed Training at Scale", arXiv 2106.11257).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow,
+ * step-by-step transcription of what the paper defines, used only by the
+ * tests, the smoke check and the CPU-baseline leg of the benchmark.  It shares
+ * no code, table or constant generator with the HIP library and neither side
+ * includes the other.
+ *
+ * What is computed, and where the paper defines it:
+ *   - Split:            App. D.1 ("Basic building blocks"), item Split(v, n)
+ *   - CenteredClip:     App. D.2, eq. (CenteredClip), run per partition as in
+ *                       Alg. 2 (ButterflyClip) line 5; stopping rule from
+ *                       Sec. 4.1 ("to convergence with eps = 1e-6") and the
+ *                       iteration cap M of App. I.1
+ *   - Delta, norm, w, s: Alg. 1 lines 8-9; Alg. 6 (BTARD) lines 8-12; eq. (2)
+ *   - column check:     Alg. 1 line 16; Alg. 6 Verification 2
+ *   - GetRandomVector:  Alg. 6 line 6 and the paragraph after it (a unit vector,
+ *                       uniform on the sphere, derived from the scalar seed r by
+ *                       "any standard" generator) -- the concrete generator is
+ *                       this build's z-spec: Philox4x32-10 (Salmon et al., SC'11)
+ *                       feeding Box-Muller; a normalised Gaussian vector is
+ *                       uniform on the sphere.
+ *
+ * Arithmetic: inputs are fp32 (the gradients), widened to fp64 on load; every
+ * state variable, reduction and output is fp64.  The paper does not state a
+ * precision.
+ *
+ * Loops over coordinates carry "#pragma omp parallel for" so that the large
+ * workloads finish; this changes only the order of fp64 additions.
+ *
+ * Pins (tests/test_oracle_*.py): Split closed form; tau=inf => mean; identical
+ * peers; n=1; collinear inputs => scalar clamp recursion; hand-worked n=3,d=8
+ * case (tests/golden); fixed point == minimiser of the summed Huber potential
+ * found by an independent optimiser; monotone decrease of that potential;
+ * |step| <= tau; translation/rotation/permutation equivariance; partition
+ * independence; column-sum identity n<z,next step>; Philox known-answer
+ * vectors; |z| = 1, normality (KS) and Box-Muller inversion of z-hat.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------------ */
+/* Split(v, n): App. D.1.  The first (d mod parts) parts have ceil(d/parts)   */
+/* entries, the others floor(d/parts).  off has parts+1 entries.             */
+/* ------------------------------------------------------------------------ */
+int oracle_split(int64_t d, int32_t parts, int64_t *off)
+{
+    if (d < 0 || parts <= 0 || !off) return -1;
+    int64_t q = d / parts, r = d % parts;
+    off[0] = 0;
+    for (int32_t j = 0; j < parts; ++j)
+        off[j + 1] = off[j] + q + (j < r ? 1 : 0);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* CenteredClip on ONE partition: columns [lo, hi) of the n x ld row-major   */
+/* fp32 matrix G (row i = peer i's gradient g_i).                             */
+/*                                                                          */
+/*   v^{l+1} = v^l + (1/n) sum_i (g_i - v^l) min{1, tau/||g_i - v^l||_2}      */
+/*                                                  (eq. CenteredClip)      */
+/*                                                                          */
+/* Readings where the paper is silent:                                       */
+/*   v^0     = caller's vector, else the coordinate-wise mean of the n rows   */
+/*   stop    = after applying update number it, if ||v^{it} - v^{it-1}||_2   */
+/*             < eps (strict), or when it == M                                */
+/*   weight  = 1 whenever the norm is <= tau (covers norm == 0)              */
+/*   n       = the number of rows passed in                                   */
+/* A partition whose residual norm is not finite gets iters = -1.            */
+/* trace (optional) receives ||step|| of every applied update, M per part.   */
+/* ------------------------------------------------------------------------ */
+static void centered_clip_partition(const float *G, int64_t ld, int32_t n,
+                                    int64_t lo, int64_t hi, double tau,
+                                    double eps, int32_t M, const double *v0,
+                                    double *v, int32_t *iters,
+                                    double *step_norm, double *trace)
+{
+    const int64_t dj = hi - lo;
+    double *step = (double *)malloc(sizeof(double) * (size_t)(dj > 0 ? dj : 1));
+    double *w = (double *)malloc(sizeof(double) * (size_t)n);
+
+    /* v^0 */
+    if (v0) {
+        for (int64_t x = lo; x < hi; ++x) v[x] = v0[x];
+    } else {
+#pragma omp parallel for schedule(static)
+        for (int64_t x = lo; x < hi; ++x) {
+            double sum = 0.0;
+            for (int32_t i = 0; i < n; ++i) sum += (double)G[i * ld + x];
+            v[x] = sum / (double)n;
+        }
+    }
+
+    int32_t it = 0;
+    double T = 0.0;
+    int bad = 0;
+    while (it < M) {
+        /* norms ||g_i - v^l|| and clip weights min{1, tau/norm} */
+        for (int32_t i = 0; i < n; ++i) {
+            const float *gi = G + i * ld;
+            double N2 = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : N2)
+            for (int64_t x = lo; x < hi; ++x) {
+                double r = (double)gi[x] - v[x];
+                N2 += r * r;
+            }
+            double N = sqrt(N2);
+            if (!isfinite(N)) bad = 1;
+            w[i] = (N <= tau) ? 1.0 : tau / N;
+        }
+        if (bad) break;
+
+        /* step = (1/n) sum_i w_i (g_i - v^l) ;  v^{l+1} = v^l + step */
+        double T2 = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : T2)
+        for (int64_t x = lo; x < hi; ++x) {
+            double sum = 0.0;
+            for (int32_t i = 0; i < n; ++i)
+                sum += w[i] * ((double)G[i * ld + x] - v[x]);
+            step[x - lo] = sum / (double)n;
+            T2 += step[x - lo] * step[x - lo];
+        }
+#pragma omp parallel for schedule(static)
+        for (int64_t x = lo; x < hi; ++x) v[x] += step[x - lo];
+
+        T = sqrt(T2);
+        if (trace) trace[it] = T;
+        ++it;
+        if (T < eps) break;
+    }
+    *iters = bad ? -1 : it;
+    if (step_norm) *step_norm = T;
+    free(step);
+    free(w);
+}
+
+/* All partitions, independently (Alg. 2: each aggregator runs its own
+ * CenteredClip on its own partition).  off[0..P] ascending, off[0] >= 0,
+ * off[P] <= ld.  v0 (fp64, indexed like v) may be NULL.  trace may be NULL or
+ * P*M doubles (row j = partition j).  Returns 0, or -1 on bad arguments. */
+int oracle_centered_clip(const float *G, int64_t ld, int32_t n,
+                         const int64_t *off, int32_t P, double tau, double eps,
+                         int32_t M, const double *v0, double *v,
+                         int32_t *iters, double *step_norm, double *trace)
+{
+    if (!G || n <= 0 || !off || P <= 0 || !v || !iters || M < 0 || !(tau > 0.0) ||
+        !(eps >= 0.0))
+        return -1;
+    for (int32_t j = 0; j < P; ++j)
+        if (off[j] > off[j + 1] || off[j] < 0 || off[j + 1] > ld) return -1;
+    for (int32_t j = 0; j < P; ++j) {
+        if (trace)
+            for (int32_t l = 0; l < M; ++l) trace[(int64_t)j * M + l] = -1.0;
+        centered_clip_partition(G, ld, n, off[j], off[j + 1], tau, eps, M, v0, v,
+                                &iters[j], step_norm ? &step_norm[j] : NULL,
+                                trace ? trace + (int64_t)j * M : NULL);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as    */
+/* easy as 1, 2, 3", SC'11).  Counter 4 x 32 bit, key 2 x 32 bit, 10 rounds. */
+/* ------------------------------------------------------------------------ */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2],
+                          uint32_t out[4])
+{
+    const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u; /* round multipliers */
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u; /* key increments    */
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = M0 * (uint64_t)c0;
+        uint64_t p1 = M1 * (uint64_t)c2;
+        uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += W0;
+        k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* ------------------------------------------------------------------------ */
+/* z-spec (this build's concrete GetRandomVector).  For global coordinate x, */
+/* q = floor(x/4): Philox counter (q lo, q hi, 0, 0), key (seed lo, seed hi) */
+/* gives words u0..u3.  a = ((u0>>8)+0.5)/2^24, b = ((u1>>8)+0.5)/2^24,       */
+/* rho = sqrt(-2 ln a): zhat[4q] = rho cos(2 pi b), zhat[4q+1] = rho sin(2 pi */
+/* b); the same with (u2,u3) for 4q+2, 4q+3.  z = zhat/||zhat||_2, the norm  */
+/* over ALL d coordinates of the gradient.                                   */
+/* ------------------------------------------------------------------------ */
+static const double TWO_PI = 6.283185307179586476925286766559;
+
+static void z_hat_block(uint64_t seed, int64_t q, double z4[4])
+{
+    uint32_t ctr[4] = {(uint32_t)((uint64_t)q & 0xFFFFFFFFu),
+                       (uint32_t)((uint64_t)q >> 32), 0u, 0u};
+    uint32_t key[2] = {(uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32)};
+    uint32_t u[4];
+    oracle_philox4x32_10(ctr, key, u);
+    for (int h = 0; h < 2; ++h) {
+        double a = ((double)(u[2 * h] >> 8) + 0.5) / 16777216.0;
+        double b = ((double)(u[2 * h + 1] >> 8) + 0.5) / 16777216.0;
+        double rho = sqrt(-2.0 * log(a));
+        z4[2 * h] = rho * cos(TWO_PI * b);
+        z4[2 * h + 1] = rho * sin(TWO_PI * b);
+    }
+}
+
+/* raw uniforms (a, b) on the 2^-24 grid, for the tests of the z-spec */
+void oracle_z_uniforms(uint64_t seed, int64_t x_begin, int64_t count, double *ab)
+{
+    for (int64_t t = 0; t < count; ++t) {
+        int64_t x = x_begin + t, q = x / 4;
+        uint32_t ctr[4] = {(uint32_t)((uint64_t)q & 0xFFFFFFFFu),
+                           (uint32_t)((uint64_t)q >> 32), 0u, 0u};
+        uint32_t key[2] = {(uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32)};
+        uint32_t u[4];
+        oracle_philox4x32_10(ctr, key, u);
+        ab[t] = ((double)(u[x % 4] >> 8) + 0.5) / 16777216.0;
+    }
+}
+
+/* un-normalised Gaussian coordinates zhat[x_begin .. x_begin+count) */
+void oracle_z_hat(uint64_t seed, int64_t x_begin, int64_t count, double *zhat)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < count; ++t) {
+        int64_t x = x_begin + t;
+        double z4[4];
+        z_hat_block(seed, x / 4, z4);
+        zhat[t] = z4[x % 4];
+    }
+}
+
+/* ||zhat||_2 over coordinates 0 .. d-1 */
+double oracle_z_norm(uint64_t seed, int64_t d)
+{
+    double Z2 = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : Z2)
+    for (int64_t q = 0; q < (d + 3) / 4; ++q) {
+        double z4[4];
+        z_hat_block(seed, q, z4);
+        for (int e = 0; e < 4; ++e)
+            if (4 * q + e < d) Z2 += z4[e] * z4[e];
+    }
+    return sqrt(Z2);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Verification quantities for the aggregate v (Alg. 6 lines 6-12):          */
+/*   norm_ij = ||g_i[j] - v[j]||_2                                            */
+/*   w_ij    = min{1, tau/norm_ij}   (1 when norm_ij <= tau)                  */
+/*   Delta_i^j = w_ij (g_i[j] - v[j])                                         */
+/*   s_i^j   = <z[j], Delta_i^j>                       (eq. 2)               */
+/*   colsum_j = sum_i s_i^j          (the quantity Verification 2 tests)     */
+/* Column x of G / v here is global coordinate x_base + x of the gradient    */
+/* (so that one partition can be checked on its own); z = zhat/znorm with    */
+/* znorm = oracle_z_norm(seed, d_total).  Outputs are row-major n x P;       */
+/* delta (optional) is n x ldd fp64.                                          */
+/* ------------------------------------------------------------------------ */
+int oracle_verify(const float *G, int64_t ld, int32_t n, const int64_t *off,
+                  int32_t P, const double *v, double tau, uint64_t seed,
+                  int64_t x_base, double znorm, double *norms, double *weights,
+                  double *proj, double *colsum, double *delta, int64_t ldd)
+{
+    if (!G || n <= 0 || !off || P <= 0 || !v || !(tau > 0.0) || !(znorm > 0.0) ||
+        !norms || !weights || !proj)
+        return -1;
+    for (int32_t j = 0; j < P; ++j) {
+        const int64_t lo = off[j], hi = off[j + 1];
+        if (lo > hi || lo < 0 || hi > ld) return -1;
+        /* zhat for this partition's coordinates, generated once */
+        double *zj = (double *)malloc(sizeof(double) * (size_t)(hi > lo ? hi - lo : 1));
+        oracle_z_hat(seed, x_base + lo, hi - lo, zj);
+        double cs = 0.0;
+        for (int32_t i = 0; i < n; ++i) {
+            const float *gi = G + i * ld;
+            double N2 = 0.0, R = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : N2, R)
+            for (int64_t x = lo; x < hi; ++x) {
+                double r = (double)gi[x] - v[x];
+                N2 += r * r;
+                R += zj[x - lo] * r;
+            }
+            double N = sqrt(N2);
+            double w = (N <= tau) ? 1.0 : tau / N;
+            norms[(int64_t)i * P + j] = N;
+            weights[(int64_t)i * P + j] = w;
+            proj[(int64_t)i * P + j] = w * R / znorm;
+            cs += proj[(int64_t)i * P + j];
+            if (delta) {
+                double *di = delta + i * ldd;
+#pragma omp parallel for schedule(static)
+                for (int64_t x = lo; x < hi; ++x)
+                    di[x] = w * ((double)gi[x] - v[x]);
+            }
+        }
+        free(zj);
+        if (colsum) colsum[j] = cs;
+    }
+    return 0;
+}

@@ -1,0 +1,160 @@
+"""ctypes/numpy front end of the plain-C fp64 oracle (``btard_oracle.c``).
+
+Test infrastructure only: argument marshalling, no arithmetic of the method.
+The shared object is compiled with gcc next to the source on first use.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "btard_oracle.c")
+_SO = os.path.join(_HERE, "libbtard_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP).  Returns the .so path."""
+    stale = (not os.path.exists(_SO)) or os.path.getmtime(_SO) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+             "-o", _SO, _SRC, "-lm"]
+        )
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = ctypes.CDLL(build())
+    c = ctypes
+    P = c.POINTER
+    lib.oracle_num_threads.restype = c.c_int
+    lib.oracle_split.argtypes = [c.c_int64, c.c_int32, P(c.c_int64)]
+    lib.oracle_split.restype = c.c_int
+    lib.oracle_centered_clip.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, P(c.c_int64), c.c_int32, c.c_double,
+        c.c_double, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p]
+    lib.oracle_centered_clip.restype = c.c_int
+    lib.oracle_philox4x32_10.argtypes = [P(c.c_uint32), P(c.c_uint32), P(c.c_uint32)]
+    lib.oracle_philox4x32_10.restype = None
+    lib.oracle_z_uniforms.argtypes = [c.c_uint64, c.c_int64, c.c_int64, c.c_void_p]
+    lib.oracle_z_uniforms.restype = None
+    lib.oracle_z_hat.argtypes = [c.c_uint64, c.c_int64, c.c_int64, c.c_void_p]
+    lib.oracle_z_hat.restype = None
+    lib.oracle_z_norm.argtypes = [c.c_uint64, c.c_int64]
+    lib.oracle_z_norm.restype = c.c_double
+    lib.oracle_verify.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, P(c.c_int64), c.c_int32, c.c_void_p,
+        c.c_double, c.c_uint64, c.c_int64, c.c_double, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64]
+    lib.oracle_verify.restype = c.c_int
+    _lib = lib
+    return lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _offsets(off: Sequence[int]):
+    arr = (ctypes.c_int64 * len(off))(*[int(o) for o in off])
+    return arr
+
+
+def _as_G(G) -> np.ndarray:
+    G = np.asarray(G)
+    if G.dtype != np.float32 or G.ndim != 2 or G.strides[1] != 4 or G.strides[0] % 4:
+        G = np.ascontiguousarray(G, dtype=np.float32)
+    return G
+
+
+def split(d: int, parts: int) -> np.ndarray:
+    off = (ctypes.c_int64 * (parts + 1))()
+    if _load().oracle_split(d, parts, off) != 0:
+        raise ValueError("oracle_split: bad arguments")
+    return np.array(off[:], dtype=np.int64)
+
+
+def centered_clip(G, off, tau: float, eps: float, max_iters: int,
+                  v0: Optional[np.ndarray] = None, want_trace: bool = False):
+    """Returns (v[fp64, ld], iters[int32, P], step_norm[fp64, P], trace|None)."""
+    G = _as_G(G)
+    n, _ = G.shape
+    ld = G.strides[0] // 4 if n > 1 else G.shape[1]
+    Pn = len(off) - 1
+    width = int(off[-1])
+    v = np.zeros(max(width, 1), dtype=np.float64)
+    iters = np.zeros(Pn, dtype=np.int32)
+    sn = np.zeros(Pn, dtype=np.float64)
+    trace = np.zeros((Pn, max(max_iters, 1)), dtype=np.float64) if want_trace else None
+    v0p = None
+    if v0 is not None:
+        v0 = np.ascontiguousarray(v0, dtype=np.float64)
+        assert v0.shape[0] >= width
+        v0p = v0.ctypes.data
+    rc = _load().oracle_centered_clip(
+        G.ctypes.data, ld, n, _offsets(off), Pn, float(tau), float(eps),
+        int(max_iters), v0p, v.ctypes.data, iters.ctypes.data, sn.ctypes.data,
+        trace.ctypes.data if want_trace else None)
+    if rc != 0:
+        raise ValueError("oracle_centered_clip: bad arguments")
+    return v[:width], iters, sn, trace
+
+
+def philox4x32_10(ctr: Sequence[int], key: Sequence[int]):
+    c = (ctypes.c_uint32 * 4)(*ctr)
+    k = (ctypes.c_uint32 * 2)(*key)
+    o = (ctypes.c_uint32 * 4)()
+    _load().oracle_philox4x32_10(c, k, o)
+    return [int(x) for x in o]
+
+
+def z_uniforms(seed: int, x_begin: int, count: int) -> np.ndarray:
+    out = np.zeros(count, dtype=np.float64)
+    _load().oracle_z_uniforms(seed, x_begin, count, out.ctypes.data)
+    return out
+
+
+def z_hat(seed: int, x_begin: int, count: int) -> np.ndarray:
+    out = np.zeros(count, dtype=np.float64)
+    _load().oracle_z_hat(seed, x_begin, count, out.ctypes.data)
+    return out
+
+
+def z_norm(seed: int, d: int) -> float:
+    return float(_load().oracle_z_norm(seed, d))
+
+
+def verify(G, off, v, tau: float, seed: int, x_base: int = 0,
+           znorm: Optional[float] = None, want_delta: bool = False):
+    """Returns dict(norms, weights, proj [n,P], colsum [P], delta [n,width]|None)."""
+    G = _as_G(G)
+    n, _ = G.shape
+    ld = G.strides[0] // 4 if n > 1 else G.shape[1]
+    Pn = len(off) - 1
+    width = int(off[-1])
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    assert v.shape[0] >= width
+    if znorm is None:
+        znorm = z_norm(seed, x_base + width)
+    norms = np.zeros((n, Pn)); weights = np.zeros((n, Pn)); proj = np.zeros((n, Pn))
+    colsum = np.zeros(Pn)
+    delta = np.zeros((n, max(width, 1))) if want_delta else None
+    rc = _load().oracle_verify(
+        G.ctypes.data, ld, n, _offsets(off), Pn, v.ctypes.data, float(tau),
+        int(seed), int(x_base), float(znorm), norms.ctypes.data,
+        weights.ctypes.data, proj.ctypes.data, colsum.ctypes.data,
+        delta.ctypes.data if want_delta else None, max(width, 1))
+    if rc != 0:
+        raise ValueError("oracle_verify: bad arguments")
+    return dict(norms=norms, weights=weights, proj=proj, colsum=colsum,
+                delta=delta[:, :width] if want_delta else None, znorm=znorm)
