@@ -1,0 +1,187 @@
+/*
+ * btard.h -- C ABI of the MI355X (gfx950) library for the robust-aggregation
+ * hot path of Byzantine-tolerant all-reduce ("Secure Distributed Training at
+ * Scale", arXiv 2106.11257).
+ *
+ * One process on one GPU plays all n aggregators of ButterflyClip (Alg. 2):
+ * the n peers' gradients are the rows of one matrix, the partitions are column
+ * ranges of it, and every partition is aggregated independently.
+ *
+ * Conventions for every entry point
+ *   - "DEVICE" pointers are HIP device memory, "HOST" pointers ordinary host
+ *     memory.  Every buffer is owned by the caller; the library allocates no
+ *     device memory and never frees or keeps a pointer after the call returns.
+ *   - g is fp32, row-major, n rows of leading dimension ldg >= d; row i is peer
+ *     i's whole gradient g_i.  Partition j is columns
+ *     [offsets_host[j], offsets_host[j+1]).  g is never written.
+ *   - Work is enqueued on `stream` (a hipStream_t; NULL = the default stream)
+ *     and the call returns without synchronising.  Outputs are valid once the
+ *     caller has synchronised the stream.  offsets_host is consumed before the
+ *     call returns.
+ *   - Return value: BTARD_OK or a negative btard_status.  Argument errors are
+ *     detected on the host before anything is enqueued.  A partition whose
+ *     residual norms are not finite is reported through iters[j] = -1.
+ *   - Calls that share a workspace must be ordered on one stream.  Results are
+ *     bit-reproducible from run to run on the same device (no floating-point
+ *     atomics; fixed reduction order).
+ *   - Limits: 1 <= n <= 255, 1 <= parts <= 65535, 0 <= d <= ldg.
+ */
+#ifndef BTARD_H_
+#define BTARD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum btard_status {
+    BTARD_OK = 0,
+    BTARD_ERR_INVALID_ARG = -1, /* null pointer, bad size, bad offsets, tau <= 0 ... */
+    BTARD_ERR_WORKSPACE = -2,   /* workspace missing, misaligned (256 B) or too small */
+    BTARD_ERR_DEVICE = -3       /* a HIP runtime call or kernel launch failed        */
+} btard_status;
+
+#define BTARD_FLAG_NONE 0u
+
+/* Human-readable name of a status code (static storage). */
+const char *btard_status_string(int status);
+
+/*
+ * Split(v, parts) of App. D.1: the first (d mod parts) partitions get
+ * ceil(d/parts) coordinates, the others floor(d/parts).
+ * offsets_host: HOST, parts + 1 entries, written.  Pure host function.
+ */
+int btard_split_offsets(int64_t d, int32_t parts, int64_t *offsets_host);
+
+/*
+ * Bytes of DEVICE workspace (256-byte aligned) that btard_centered_clip,
+ * the btard_cc_* calls and btard_verify_projections need for n peers and
+ * `parts` partitions.  Pure host arithmetic; 0 if the arguments are out of
+ * range.  Independent of d.
+ */
+size_t btard_workspace_bytes(int32_t n, int32_t parts);
+
+/*
+ * CenteredClip (App. D.2, eq. (CenteredClip)) on every partition, as in
+ * Alg. 2 line 5:
+ *
+ *     v^{l+1}[j] = v^l[j] + (1/n) sum_i (g_i[j] - v^l[j]) min{1, tau / ||g_i[j] - v^l[j]||_2}
+ *
+ * started from v0 (or, if v0 is NULL, from the coordinate-wise mean of the n
+ * rows) and stopped, per partition, after the first update whose L2 norm is
+ * < eps (Sec. 4.1: "to convergence with eps = 1e-6") or after max_iters
+ * updates (App. I.1).  The weight is 1 whenever the norm is <= tau.
+ *
+ *   g, ldg, n, d        DEVICE matrix as described above
+ *   offsets_host, parts HOST, parts + 1 ascending entries, first 0, last d
+ *   tau                 > 0; +INF allowed (every weight 1: one step to the mean)
+ *   eps                 >= 0; 0 disables the convergence test
+ *   max_iters           >= 0; 0 returns v = v0 (or the mean)
+ *   v0                  DEVICE [d] fp32 or NULL; must not overlap v
+ *   v                   DEVICE [d] fp32, written: the aggregate g-hat
+ *   iters               DEVICE [parts] int32, written: updates applied to
+ *                       partition j, or -1 if a residual norm was not finite
+ *   last_step_norm      DEVICE [parts] fp64 or NULL, written: L2 norm of the
+ *                       last applied update (0 if none was applied)
+ *   workspace(_bytes)   DEVICE scratch of >= btard_workspace_bytes(n, parts)
+ *   flags               BTARD_FLAG_NONE
+ *
+ * Arithmetic: fp32 inputs are widened to fp64; the iterate is carried as fp64
+ * coefficients of the rows (v^l = c_0 v0 + sum_i c_i g_i), every reduction is
+ * fp64 in a fixed order; v is rounded to fp32 once, when it is written.
+ */
+int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
+                        const int64_t *offsets_host, int32_t parts,
+                        float tau, float eps, int32_t max_iters,
+                        const float *v0, float *v, int32_t *iters,
+                        double *last_step_norm, void *workspace,
+                        size_t workspace_bytes, void *stream, uint32_t flags);
+
+/*
+ * The same computation in three phases, for callers that drive the iteration
+ * themselves (timing one pass, interleaving other work, custom stopping):
+ *
+ *   btard_cc_begin    validates, uploads the offsets, sets v^0 (state lives in
+ *                     the workspace)
+ *   btard_cc_iterate  enqueues `count` iterations of eq. (CenteredClip) on
+ *                     every partition that has not stopped yet (one pass over
+ *                     the n x d matrix each); partitions that stopped are
+ *                     skipped on the device, without host involvement
+ *   btard_cc_finish   writes v, iters and last_step_norm (one more pass)
+ *
+ * btard_centered_clip == begin; iterate(max_iters); finish.  The problem
+ * description must be identical in the three calls.
+ */
+typedef struct btard_cc_problem {
+    const float *g;              /* DEVICE */
+    int64_t ldg;
+    int32_t n;
+    int64_t d;
+    const int64_t *offsets_host; /* HOST */
+    int32_t parts;
+    float tau;
+    float eps;
+    int32_t max_iters;
+    const float *v0;             /* DEVICE or NULL */
+    void *workspace;             /* DEVICE */
+    size_t workspace_bytes;
+    void *stream;
+    uint32_t flags;
+} btard_cc_problem;
+
+int btard_cc_begin(const btard_cc_problem *p);
+int btard_cc_iterate(const btard_cc_problem *p, int32_t count);
+int btard_cc_finish(const btard_cc_problem *p, float *v, int32_t *iters,
+                    double *last_step_norm);
+
+/*
+ * Verification quantities of BTARD (Alg. 6 lines 6-12; Alg. 1 lines 5-9;
+ * eq. (2)) for an aggregate v:
+ *
+ *     norm_ij  = ||g_i[j] - v[j]||_2
+ *     w_ij     = min{1, tau / norm_ij}                  (1 when norm_ij <= tau)
+ *     Delta_i^j = w_ij (g_i[j] - v[j])
+ *     s_i^j    = <z[j], Delta_i^j>
+ *     colsum_j = sum_i s_i^j        (the sum Verification 2 compares with 0)
+ *
+ * z = GetRandomVector(seed): a unit vector of R^d, uniform on the sphere,
+ * generated inside the kernel and never stored.  Its definition: for
+ * coordinate x, the Philox4x32-10 block with counter (floor(x/4), 0) and key
+ * (seed low word, seed high word) yields u0..u3; a = ((u0 >> 9) + 1/2) 2^-23,
+ * b = ((u1 >> 9) + 1/2) 2^-23, rho = sqrt(-2 ln a), zhat[4q] = rho cos(2 pi b),
+ * zhat[4q+1] = rho sin(2 pi b), and (u2, u3) give zhat[4q+2], zhat[4q+3] the
+ * same way; z = zhat / ||zhat||_2 with the norm taken over all d coordinates.
+ *
+ *   v         DEVICE [d] fp32: the aggregate being verified (read only)
+ *   seed      the MPRNG output r of Alg. 6 line 5
+ *   norms, weights, proj   DEVICE [n * parts] fp64, written, entry (i, j) at
+ *             index i * parts + j
+ *   colsum    DEVICE [parts] fp64 or NULL, written
+ *   delta, ldd  DEVICE n x ldd fp32 (ldd >= d) or NULL: if given, Delta_i^j is
+ *             written to row i, columns of partition j (one more pass); must
+ *             not overlap g or v
+ *
+ * Arithmetic: residuals and reductions in fp64; zhat in fp32.
+ */
+int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
+                             const int64_t *offsets_host, int32_t parts,
+                             const float *v, float tau, uint64_t seed,
+                             double *norms, double *weights, double *proj,
+                             double *colsum, float *delta, int64_t ldd,
+                             void *workspace, size_t workspace_bytes,
+                             void *stream, uint32_t flags);
+
+/*
+ * Test hook for the z-spec: writes zhat[x_begin .. x_begin + count) (fp32,
+ * not normalised) to DEVICE out, with the same device code the verification
+ * kernel uses.
+ */
+int btard_debug_zhat(uint64_t seed, int64_t x_begin, int64_t count, float *out,
+                     void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BTARD_H_ */

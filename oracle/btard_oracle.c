@@ -204,7 +204,8 @@ void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2],
 /* ------------------------------------------------------------------------ */
 /* z-spec (this build's concrete GetRandomVector).  For global coordinate x, */
 /* q = floor(x/4): Philox counter (q lo, q hi, 0, 0), key (seed lo, seed hi) */
-/* gives words u0..u3.  a = ((u0>>8)+0.5)/2^24, b = ((u1>>8)+0.5)/2^24,       */
+/* gives words u0..u3.  a = ((u0>>9)+0.5)/2^23, b = ((u1>>9)+0.5)/2^23 (a     */
+/* grid whose points are exact in fp32 as well as fp64),                      */
 /* rho = sqrt(-2 ln a): zhat[4q] = rho cos(2 pi b), zhat[4q+1] = rho sin(2 pi */
 /* b); the same with (u2,u3) for 4q+2, 4q+3.  z = zhat/||zhat||_2, the norm  */
 /* over ALL d coordinates of the gradient.                                   */
@@ -219,15 +220,15 @@ static void z_hat_block(uint64_t seed, int64_t q, double z4[4])
     uint32_t u[4];
     oracle_philox4x32_10(ctr, key, u);
     for (int h = 0; h < 2; ++h) {
-        double a = ((double)(u[2 * h] >> 8) + 0.5) / 16777216.0;
-        double b = ((double)(u[2 * h + 1] >> 8) + 0.5) / 16777216.0;
+        double a = ((double)(u[2 * h] >> 9) + 0.5) / 8388608.0;
+        double b = ((double)(u[2 * h + 1] >> 9) + 0.5) / 8388608.0;
         double rho = sqrt(-2.0 * log(a));
         z4[2 * h] = rho * cos(TWO_PI * b);
         z4[2 * h + 1] = rho * sin(TWO_PI * b);
     }
 }
 
-/* raw uniforms (a, b) on the 2^-24 grid, for the tests of the z-spec */
+/* raw uniforms (a, b) on the 2^-23 grid, for the tests of the z-spec */
 void oracle_z_uniforms(uint64_t seed, int64_t x_begin, int64_t count, double *ab)
 {
     for (int64_t t = 0; t < count; ++t) {
@@ -237,7 +238,7 @@ void oracle_z_uniforms(uint64_t seed, int64_t x_begin, int64_t count, double *ab
         uint32_t key[2] = {(uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32)};
         uint32_t u[4];
         oracle_philox4x32_10(ctr, key, u);
-        ab[t] = ((double)(u[x % 4] >> 8) + 0.5) / 16777216.0;
+        ab[t] = ((double)(u[x % 4] >> 9) + 0.5) / 8388608.0;
     }
 }
 

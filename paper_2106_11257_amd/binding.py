@@ -1,0 +1,249 @@
+"""ctypes binding of the C ABI in ``include/btard.h``.
+
+Argument marshalling only: every step of the computation runs in the HIP
+library.  Device buffers are torch tensors (``data_ptr()``), the stream is
+torch's current stream.  There is no CPU fallback: if ``libbtard.so`` is not
+built the import of the library fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libbtard.so")
+_lib = None
+
+BTARD_OK = 0
+BTARD_FLAG_NONE = 0
+
+
+class BtardError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        name = load_library().btard_status_string(status).decode()
+        super().__init__(f"{where}: {name} ({status})")
+
+
+class _Problem(ctypes.Structure):
+    _fields_ = [
+        ("g", ctypes.c_void_p), ("ldg", ctypes.c_int64), ("n", ctypes.c_int32),
+        ("d", ctypes.c_int64), ("offsets_host", ctypes.POINTER(ctypes.c_int64)),
+        ("parts", ctypes.c_int32), ("tau", ctypes.c_float), ("eps", ctypes.c_float),
+        ("max_iters", ctypes.c_int32), ("v0", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("stream", ctypes.c_void_p), ("flags", ctypes.c_uint32),
+    ]
+
+
+def status_string(status: int) -> str:
+    return load_library().btard_status_string(int(status)).decode()
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """dlopen libbtard.so (built beforehand by ``build.py``); build it if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _build
+        _build.build(force=True)
+    lib = ctypes.CDLL(_LIB_PATH)
+    c = ctypes
+    lib.btard_status_string.argtypes = [c.c_int]
+    lib.btard_status_string.restype = c.c_char_p
+    lib.btard_split_offsets.argtypes = [c.c_int64, c.c_int32, c.POINTER(c.c_int64)]
+    lib.btard_split_offsets.restype = c.c_int
+    lib.btard_workspace_bytes.argtypes = [c.c_int32, c.c_int32]
+    lib.btard_workspace_bytes.restype = c.c_size_t
+    lib.btard_centered_clip.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.POINTER(c.c_int64), c.c_int32,
+        c.c_float, c.c_float, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_size_t, c.c_void_p, c.c_uint32]
+    lib.btard_centered_clip.restype = c.c_int
+    lib.btard_cc_begin.argtypes = [c.POINTER(_Problem)]
+    lib.btard_cc_begin.restype = c.c_int
+    lib.btard_cc_iterate.argtypes = [c.POINTER(_Problem), c.c_int32]
+    lib.btard_cc_iterate.restype = c.c_int
+    lib.btard_cc_finish.argtypes = [c.POINTER(_Problem), c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.btard_cc_finish.restype = c.c_int
+    lib.btard_verify_projections.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.POINTER(c.c_int64), c.c_int32,
+        c.c_void_p, c.c_float, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_int64, c.c_void_p, c.c_size_t, c.c_void_p, c.c_uint32]
+    lib.btard_verify_projections.restype = c.c_int
+    lib.btard_debug_zhat.argtypes = [c.c_uint64, c.c_int64, c.c_int64, c.c_void_p, c.c_void_p]
+    lib.btard_debug_zhat.restype = c.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != BTARD_OK:
+        raise BtardError(rc, where)
+
+
+def _stream_ptr(device) -> int:
+    return int(torch.cuda.current_stream(device).cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _off_array(offsets: Sequence[int]):
+    return (ctypes.c_int64 * len(offsets))(*[int(o) for o in offsets])
+
+
+def _row_stride(g: torch.Tensor) -> int:
+    assert g.dim() == 2 and g.dtype == torch.float32
+    assert g.shape[1] == 0 or g.stride(1) == 1, "rows of g must be contiguous"
+    return int(g.stride(0)) if g.shape[0] > 1 else int(max(g.shape[1], g.stride(0)))
+
+
+def split_offsets(d: int, parts: int) -> list:
+    """Split(v, parts) of App. D.1 -> parts + 1 offsets."""
+    out = (ctypes.c_int64 * (parts + 1))()
+    _check(load_library().btard_split_offsets(int(d), int(parts), out), "btard_split_offsets")
+    return list(out)
+
+
+def workspace_bytes(n: int, parts: int) -> int:
+    return int(load_library().btard_workspace_bytes(int(n), int(parts)))
+
+
+def alloc_workspace(n: int, parts: int, device) -> torch.Tensor:
+    nbytes = workspace_bytes(n, parts)
+    if nbytes == 0:
+        raise BtardError(-1, "btard_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def centered_clip(g: torch.Tensor, offsets: Sequence[int], tau: float, eps: float,
+                  max_iters: int, v0: Optional[torch.Tensor] = None,
+                  v: Optional[torch.Tensor] = None, iters: Optional[torch.Tensor] = None,
+                  last_step_norm: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None):
+    """btard_centered_clip.  Returns (v fp32 [d], iters int32 [P], last_step_norm fp64 [P]).
+
+    Work is enqueued on torch's current stream; the outputs are valid after it
+    is synchronised.
+    """
+    n, d = int(g.shape[0]), int(g.shape[1])
+    P = len(offsets) - 1
+    dev = g.device
+    if v is None:
+        v = torch.empty(d, dtype=torch.float32, device=dev)
+    if iters is None:
+        iters = torch.empty(P, dtype=torch.int32, device=dev)
+    if last_step_norm is None:
+        last_step_norm = torch.empty(P, dtype=torch.float64, device=dev)
+    if workspace is None:
+        workspace = alloc_workspace(n, P, dev)
+    rc = load_library().btard_centered_clip(
+        _ptr(g), _row_stride(g), n, d, _off_array(offsets), P, float(tau), float(eps),
+        int(max_iters), _ptr(v0), _ptr(v), _ptr(iters), _ptr(last_step_norm),
+        _ptr(workspace), workspace.numel(), _stream_ptr(dev), BTARD_FLAG_NONE)
+    _check(rc, "btard_centered_clip")
+    return v, iters, last_step_norm
+
+
+class Problem:
+    """Keeps the ctypes problem description (and what it points to) alive."""
+
+    def __init__(self, g, offsets, tau, eps, max_iters, v0, workspace):
+        self.g, self.v0, self.workspace = g, v0, workspace
+        self.offsets = _off_array(offsets)
+        self.parts = len(offsets) - 1
+        self.c = _Problem(
+            _ptr(g), _row_stride(g), int(g.shape[0]), int(g.shape[1]), self.offsets,
+            self.parts, float(tau), float(eps), int(max_iters), _ptr(v0), _ptr(workspace),
+            workspace.numel(), _stream_ptr(g.device), BTARD_FLAG_NONE)
+
+
+def make_problem(g: torch.Tensor, offsets: Sequence[int], tau: float, eps: float,
+                 max_iters: int, v0: Optional[torch.Tensor] = None,
+                 workspace: Optional[torch.Tensor] = None) -> Problem:
+    if workspace is None:
+        workspace = alloc_workspace(int(g.shape[0]), len(offsets) - 1, g.device)
+    return Problem(g, offsets, tau, eps, max_iters, v0, workspace)
+
+
+def cc_begin(p: Problem) -> None:
+    _check(load_library().btard_cc_begin(ctypes.byref(p.c)), "btard_cc_begin")
+
+
+def cc_iterate(p: Problem, count: int) -> None:
+    _check(load_library().btard_cc_iterate(ctypes.byref(p.c), int(count)), "btard_cc_iterate")
+
+
+def cc_finish(p: Problem, v: Optional[torch.Tensor] = None,
+              iters: Optional[torch.Tensor] = None,
+              last_step_norm: Optional[torch.Tensor] = None):
+    dev = p.g.device
+    if v is None:
+        v = torch.empty(int(p.g.shape[1]), dtype=torch.float32, device=dev)
+    if iters is None:
+        iters = torch.empty(p.parts, dtype=torch.int32, device=dev)
+    if last_step_norm is None:
+        last_step_norm = torch.empty(p.parts, dtype=torch.float64, device=dev)
+    _check(load_library().btard_cc_finish(ctypes.byref(p.c), _ptr(v), _ptr(iters),
+                                          _ptr(last_step_norm)), "btard_cc_finish")
+    return v, iters, last_step_norm
+
+
+def verify_projections(g: torch.Tensor, offsets: Sequence[int], v: torch.Tensor, tau: float,
+                       seed: int, want_delta: bool = False,
+                       workspace: Optional[torch.Tensor] = None,
+                       out: Optional[dict] = None) -> dict:
+    """btard_verify_projections.  Returns dict(norms, weights, proj [n,P], colsum [P], delta)."""
+    n, d = int(g.shape[0]), int(g.shape[1])
+    P = len(offsets) - 1
+    dev = g.device
+    if out is None:
+        out = {}
+    for key in ("norms", "weights", "proj"):
+        if key not in out:
+            out[key] = torch.empty((n, P), dtype=torch.float64, device=dev)
+    if "colsum" not in out:
+        out["colsum"] = torch.empty(P, dtype=torch.float64, device=dev)
+    if want_delta and out.get("delta") is None:
+        out["delta"] = torch.empty((n, d), dtype=torch.float32, device=dev)
+    delta = out.get("delta") if want_delta else None
+    if workspace is None:
+        workspace = alloc_workspace(n, P, dev)
+    rc = load_library().btard_verify_projections(
+        _ptr(g), _row_stride(g), n, d, _off_array(offsets), P, _ptr(v), float(tau),
+        int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(out["norms"]), _ptr(out["weights"]),
+        _ptr(out["proj"]), _ptr(out["colsum"]), _ptr(delta),
+        _row_stride(delta) if delta is not None else 0, _ptr(workspace), workspace.numel(),
+        _stream_ptr(dev), BTARD_FLAG_NONE)
+    _check(rc, "btard_verify_projections")
+    return out
+
+
+def debug_zhat(seed: int, x_begin: int, count: int, device) -> torch.Tensor:
+    out = torch.empty(count, dtype=torch.float32, device=device)
+    rc = load_library().btard_debug_zhat(int(seed) & 0xFFFFFFFFFFFFFFFF, int(x_begin),
+                                         int(count), _ptr(out), _stream_ptr(device))
+    _check(rc, "btard_debug_zhat")
+    return out
+
+
+# names as in include/btard.h
+btard_status_string = status_string
+btard_split_offsets = split_offsets
+btard_workspace_bytes = workspace_bytes
+btard_centered_clip = centered_clip
+btard_cc_begin = cc_begin
+btard_cc_iterate = cc_iterate
+btard_cc_finish = cc_finish
+btard_verify_projections = verify_projections
+btard_debug_zhat = debug_zhat

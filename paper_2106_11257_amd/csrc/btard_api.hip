@@ -1,0 +1,370 @@
+// Host side of the C ABI declared in include/btard.h: argument validation,
+// workspace carving, grid sizing and kernel launches.  Nothing here allocates
+// device memory or synchronises the stream.
+#include "../../include/btard.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <mutex>
+
+#include "cc_kernels.h"
+#include "verify_kernels.h"
+
+namespace btard {
+namespace {
+
+constexpr int kMaxPeers = 255;
+constexpr int kMaxParts = 65535;
+constexpr int kMaxBlocks = 4096;      // workgroups per launch the partial-sum area is sized for
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct WsLayout {
+    size_t off, coef, delta, counter, iters, done, partial, total;
+};
+
+WsLayout ws_layout(int32_t n, int32_t P)
+{
+    WsLayout L{};
+    const size_t R = (size_t)n + 1, S = 2 * (size_t)n + 2;
+    size_t p = kAlign;                                    // 256-byte header, reserved
+    L.off = p;      p = align_up(p + sizeof(int64_t) * ((size_t)P + 1));
+    L.coef = p;     p = align_up(p + sizeof(double) * P * R);
+    L.delta = p;    p = align_up(p + sizeof(double) * P * R);
+    L.counter = p;  p = align_up(p + sizeof(unsigned int) * P);
+    L.iters = p;    p = align_up(p + sizeof(int32_t) * P);
+    L.done = p;     p = align_up(p + sizeof(int32_t) * P);
+    const size_t blocks = (size_t)(P > kMaxBlocks ? P : kMaxBlocks);
+    L.partial = p;  p = align_up(p + sizeof(double) * blocks * S);
+    L.total = p;
+    return L;
+}
+
+bool basic_args_ok(const float *g, int64_t ldg, int32_t n, int64_t d, const int64_t *off,
+                   int32_t P)
+{
+    if (!g || !off) return false;
+    if (n < 1 || n > kMaxPeers || P < 1 || P > kMaxParts) return false;
+    if (d < 0 || ldg < d) return false;
+    if (off[0] != 0 || off[P] != d) return false;
+    for (int32_t j = 0; j < P; ++j)
+        if (off[j] > off[j + 1]) return false;
+    return true;
+}
+
+int check_workspace(const void *ws, size_t bytes, int32_t n, int32_t P)
+{
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return BTARD_ERR_WORKSPACE;
+    if (bytes < ws_layout(n, P).total) return BTARD_ERR_WORKSPACE;
+    return BTARD_OK;
+}
+
+CcState carve_cc(void *ws, int32_t n, int32_t P)
+{
+    const WsLayout L = ws_layout(n, P);
+    char *b = static_cast<char *>(ws);
+    CcState st;
+    st.off = reinterpret_cast<const int64_t *>(b + L.off);
+    st.coef = reinterpret_cast<double *>(b + L.coef);
+    st.delta = reinterpret_cast<double *>(b + L.delta);
+    st.partial = reinterpret_cast<double *>(b + L.partial);
+    st.counter = reinterpret_cast<unsigned int *>(b + L.counter);
+    st.iters = reinterpret_cast<int32_t *>(b + L.iters);
+    st.done = reinterpret_cast<int32_t *>(b + L.done);
+    st.R = n + 1;
+    return st;
+}
+
+// ---- kernel variants: peers per lane group (NP) x lane groups per wavefront (LG)
+enum Variant { V4x1, V8x1, V16x1, V16x2, V16x4, V16x8, V16x16, kVariants };
+
+Variant pick_variant(int32_t n)
+{
+    if (n <= 4) return V4x1;
+    if (n <= 8) return V8x1;
+    if (n <= 16) return V16x1;
+    if (n <= 32) return V16x2;
+    if (n <= 64) return V16x4;
+    if (n <= 128) return V16x8;
+    return V16x16;
+}
+
+int variant_tile_width(Variant v)
+{
+    switch (v) {
+        case V16x2: return Geo<16, 2>::kW;
+        case V16x4: return Geo<16, 4>::kW;
+        case V16x8: return Geo<16, 8>::kW;
+        case V16x16: return Geo<16, 16>::kW;
+        default: return Geo<16, 1>::kW;
+    }
+}
+
+typedef void (*CcPassFn)(CcArgs);
+typedef void (*CcFinishFn)(CcFinishArgs);
+typedef void (*VerifyFn)(VerifyArgs);
+
+const CcPassFn kCcPass[kVariants] = {
+    cc_pass_kernel<4, 1>, cc_pass_kernel<8, 1>, cc_pass_kernel<16, 1>, cc_pass_kernel<16, 2>,
+    cc_pass_kernel<16, 4>, cc_pass_kernel<16, 8>, cc_pass_kernel<16, 16>};
+const CcFinishFn kCcFinish[kVariants] = {
+    cc_finish_kernel<4, 1>, cc_finish_kernel<8, 1>, cc_finish_kernel<16, 1>,
+    cc_finish_kernel<16, 2>, cc_finish_kernel<16, 4>, cc_finish_kernel<16, 8>,
+    cc_finish_kernel<16, 16>};
+const VerifyFn kVerify[kVariants] = {
+    verify_pass_kernel<4, 1>, verify_pass_kernel<8, 1>, verify_pass_kernel<16, 1>,
+    verify_pass_kernel<16, 2>, verify_pass_kernel<16, 4>, verify_pass_kernel<16, 8>,
+    verify_pass_kernel<16, 16>};
+
+// Workgroups that are resident at once for a kernel on the current device
+// (compute units x occupancy), cached per (device, kernel).
+struct ResidentCache {
+    std::mutex mu;
+    int value[16][3][kVariants] = {};
+};
+ResidentCache g_resident;
+
+int resident_blocks(int kind, Variant v, const void *fn)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (dev < 0 || dev >= 16) dev = 0;
+    std::lock_guard<std::mutex> lock(g_resident.mu);
+    int &slot = g_resident.value[dev][kind][v];
+    if (slot == 0) {
+        int cus = 0, occ = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, fn, kBlock, 0) != hipSuccess)
+            return 0;
+        if (occ < 1) occ = 1;
+        slot = cus * occ;
+    }
+    return slot;
+}
+
+// Workgroups per partition: fill the device once (all partitions run side by
+// side), but never more than the partial-sum area holds or the work needs.
+int blocks_per_partition(int resident, int32_t P, const int64_t *off, int tile_w)
+{
+    int64_t max_units = 1;
+    for (int32_t j = 0; j < P; ++j) {
+        const int64_t units = (off[j + 1] - off[j] + tile_w + 2) / tile_w + 1;
+        if (units > max_units) max_units = units;
+    }
+    int64_t B = resident / P;
+    const int64_t cap_ws = kMaxBlocks / P;
+    if (B > cap_ws) B = cap_ws;
+    const int64_t cap_work = (max_units + kWaves - 1) / kWaves;
+    if (B > cap_work) B = cap_work;
+    if (B < 1) B = 1;
+    return (int)B;
+}
+
+int upload_offsets(const int64_t *off_host, int32_t P, const int64_t *off_dev, hipStream_t s)
+{
+    int64_t *dst = const_cast<int64_t *>(off_dev);
+    for (int32_t first = 0; first < P + 1; first += kOffChunk) {
+        OffChunk chunk;
+        const int32_t count = (P + 1 - first < kOffChunk) ? (P + 1 - first) : kOffChunk;
+        for (int32_t t = 0; t < kOffChunk; ++t) chunk.v[t] = (t < count) ? off_host[first + t] : 0;
+        hipLaunchKernelGGL(upload_offsets_kernel, dim3(1), dim3(kOffChunk), 0, s, dst, first, count,
+                           chunk);
+    }
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+bool overlaps(const void *a, const void *b, int64_t elems)
+{
+    if (!a || !b || elems <= 0) return false;
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    const uintptr_t len = (uintptr_t)elems * sizeof(float);
+    return pa < pb + len && pb < pa + len;
+}
+
+int check_problem(const btard_cc_problem *p)
+{
+    if (!p) return BTARD_ERR_INVALID_ARG;
+    if (!basic_args_ok(p->g, p->ldg, p->n, p->d, p->offsets_host, p->parts))
+        return BTARD_ERR_INVALID_ARG;
+    if (!(p->tau > 0.0f) || !(p->eps >= 0.0f) || p->max_iters < 0) return BTARD_ERR_INVALID_ARG;
+    if (p->flags != BTARD_FLAG_NONE) return BTARD_ERR_INVALID_ARG;
+    return check_workspace(p->workspace, p->workspace_bytes, p->n, p->parts);
+}
+
+}  // namespace
+}  // namespace btard
+
+using namespace btard;
+
+extern "C" {
+
+const char *btard_status_string(int status)
+{
+    switch (status) {
+        case BTARD_OK: return "BTARD_OK";
+        case BTARD_ERR_INVALID_ARG: return "BTARD_ERR_INVALID_ARG";
+        case BTARD_ERR_WORKSPACE: return "BTARD_ERR_WORKSPACE";
+        case BTARD_ERR_DEVICE: return "BTARD_ERR_DEVICE";
+        default: return "BTARD_ERR_UNKNOWN";
+    }
+}
+
+int btard_split_offsets(int64_t d, int32_t parts, int64_t *offsets_host)
+{
+    if (d < 0 || parts < 1 || !offsets_host) return BTARD_ERR_INVALID_ARG;
+    const int64_t small = d / parts, big_count = d % parts;
+    int64_t at = 0;
+    for (int32_t j = 0; j < parts; ++j) {
+        offsets_host[j] = at;
+        at += small + (j < big_count ? 1 : 0);
+    }
+    offsets_host[parts] = at;
+    return BTARD_OK;
+}
+
+size_t btard_workspace_bytes(int32_t n, int32_t parts)
+{
+    if (n < 1 || n > kMaxPeers || parts < 1 || parts > kMaxParts) return 0;
+    return ws_layout(n, parts).total;
+}
+
+int btard_cc_begin(const btard_cc_problem *p)
+{
+    const int rc = check_problem(p);
+    if (rc != BTARD_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(p->stream);
+    CcState st = carve_cc(p->workspace, p->n, p->parts);
+    const int up = upload_offsets(p->offsets_host, p->parts, st.off, s);
+    if (up != BTARD_OK) return up;
+    hipLaunchKernelGGL(cc_init_kernel, dim3(p->parts), dim3(64), 0, s, st, p->n, p->parts,
+                       p->v0 ? 1 : 0, p->max_iters);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+int btard_cc_iterate(const btard_cc_problem *p, int32_t count)
+{
+    const int rc = check_problem(p);
+    if (rc != BTARD_OK) return rc;
+    if (count < 0) return BTARD_ERR_INVALID_ARG;
+    if (count == 0) return BTARD_OK;
+    hipStream_t s = static_cast<hipStream_t>(p->stream);
+    const Variant var = pick_variant(p->n);
+    const int resident = resident_blocks(0, var, reinterpret_cast<const void *>(kCcPass[var]));
+    if (resident <= 0) return BTARD_ERR_DEVICE;
+    const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
+    CcArgs a;
+    a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = p->v0;
+    a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
+    a.st = carve_cc(p->workspace, p->n, p->parts);
+    for (int32_t l = 0; l < count; ++l)
+        hipLaunchKernelGGL(kCcPass[var], dim3(B, p->parts), dim3(kBlock), 0, s, a);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+int btard_cc_finish(const btard_cc_problem *p, float *v, int32_t *iters, double *last_step_norm)
+{
+    const int rc = check_problem(p);
+    if (rc != BTARD_OK) return rc;
+    if (!v || !iters) return BTARD_ERR_INVALID_ARG;
+    if (overlaps(v, p->v0, p->d)) return BTARD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(p->stream);
+    const Variant var = pick_variant(p->n);
+    const int resident = resident_blocks(1, var, reinterpret_cast<const void *>(kCcFinish[var]));
+    if (resident <= 0) return BTARD_ERR_DEVICE;
+    const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
+    CcFinishArgs a;
+    a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = p->v0; a.v = v;
+    a.iters_out = iters; a.step_norm_out = last_step_norm;
+    a.st = carve_cc(p->workspace, p->n, p->parts);
+    hipLaunchKernelGGL(kCcFinish[var], dim3(B, p->parts), dim3(kBlock), 0, s, a);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
+                        const int64_t *offsets_host, int32_t parts, float tau, float eps,
+                        int32_t max_iters, const float *v0, float *v, int32_t *iters,
+                        double *last_step_norm, void *workspace, size_t workspace_bytes,
+                        void *stream, uint32_t flags)
+{
+    btard_cc_problem p;
+    p.g = g; p.ldg = ldg; p.n = n; p.d = d; p.offsets_host = offsets_host; p.parts = parts;
+    p.tau = tau; p.eps = eps; p.max_iters = max_iters; p.v0 = v0;
+    p.workspace = workspace; p.workspace_bytes = workspace_bytes; p.stream = stream;
+    p.flags = flags;
+    int rc = check_problem(&p);
+    if (rc != BTARD_OK) return rc;
+    if (!v || !iters || overlaps(v, v0, d)) return BTARD_ERR_INVALID_ARG;
+    rc = btard_cc_begin(&p);
+    if (rc != BTARD_OK) return rc;
+    rc = btard_cc_iterate(&p, max_iters);
+    if (rc != BTARD_OK) return rc;
+    return btard_cc_finish(&p, v, iters, last_step_norm);
+}
+
+int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
+                             const int64_t *offsets_host, int32_t parts, const float *v,
+                             float tau, uint64_t seed, double *norms, double *weights,
+                             double *proj, double *colsum, float *delta, int64_t ldd,
+                             void *workspace, size_t workspace_bytes, void *stream,
+                             uint32_t flags)
+{
+    if (!basic_args_ok(g, ldg, n, d, offsets_host, parts)) return BTARD_ERR_INVALID_ARG;
+    if (!v || !norms || !weights || !proj || !(tau > 0.0f) || flags != BTARD_FLAG_NONE)
+        return BTARD_ERR_INVALID_ARG;
+    if (delta && (ldd < d || overlaps(delta, v, d))) return BTARD_ERR_INVALID_ARG;
+    const int wrc = check_workspace(workspace, workspace_bytes, n, parts);
+    if (wrc != BTARD_OK) return wrc;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    CcState st = carve_cc(workspace, n, parts);
+    const int up = upload_offsets(offsets_host, parts, st.off, s);
+    if (up != BTARD_OK) return up;
+
+    const Variant var = pick_variant(n);
+    const int resident = resident_blocks(2, var, reinterpret_cast<const void *>(kVerify[var]));
+    if (resident <= 0) return BTARD_ERR_DEVICE;
+    const int B = blocks_per_partition(resident, parts, offsets_host, variant_tile_width(var));
+
+    VerifyArgs a;
+    a.g = g; a.ld = ldg; a.n = n; a.v = v; a.seed = seed; a.off = st.off;
+    a.partial = st.partial; a.S = 2 * n + 1;
+    hipLaunchKernelGGL(kVerify[var], dim3(B, parts), dim3(kBlock), 0, s, a);
+
+    VerifyFinishArgs f;
+    f.partial = st.partial; f.n = n; f.P = parts; f.B = B; f.S = a.S; f.tau = (double)tau;
+    f.norms = norms; f.weights = weights; f.proj = proj; f.colsum = colsum;
+    hipLaunchKernelGGL(verify_finish_kernel, dim3(parts), dim3(kBlock), 0, s, f);
+
+    if (delta) {
+        DeltaArgs da;
+        da.g = g; da.ld = ldg; da.n = n; da.P = parts; da.v = v; da.off = st.off;
+        da.weights = weights; da.delta = delta; da.ldd = ldd;
+        int64_t max_len = 1;
+        for (int32_t j = 0; j < parts; ++j)
+            if (offsets_host[j + 1] - offsets_host[j] > max_len)
+                max_len = offsets_host[j + 1] - offsets_host[j];
+        int64_t bx = (max_len / kVec + 2 + kBlock - 1) / kBlock;
+        const int64_t cap = (kMaxBlocks * 4) / parts > 0 ? (kMaxBlocks * 4) / parts : 1;
+        if (bx > cap) bx = cap;
+        hipLaunchKernelGGL(delta_kernel, dim3((unsigned)bx, parts), dim3(kBlock), 0, s, da);
+    }
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+int btard_debug_zhat(uint64_t seed, int64_t x_begin, int64_t count, float *out, void *stream)
+{
+    if (x_begin < 0 || count < 0 || (!out && count > 0)) return BTARD_ERR_INVALID_ARG;
+    if (count == 0) return BTARD_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int64_t blocks = (count / 4 + 2 + kBlock - 1) / kBlock;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(zhat_debug_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, s, seed, x_begin,
+                       count, out);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+}  // extern "C"

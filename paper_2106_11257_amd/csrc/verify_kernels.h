@@ -1,0 +1,265 @@
+// Verification kernels: norms, clip weights, projections onto the random unit
+// direction z and (optionally) the clipped residuals Delta (Alg. 6 lines 6-12,
+// eq. (2)).  z is generated in registers from the seed (Philox4x32-10 + Box-
+// Muller) and never touches memory.
+#pragma once
+
+#include "kernels_common.h"
+
+namespace btard {
+
+// Philox4x32 with 10 rounds (Salmon et al., SC'11): counter (c0..c3), key (k0,k1).
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+    constexpr uint32_t kMulA = 0xD2511F53u, kMulB = 0xCD9E8D57u;
+    constexpr uint32_t kWeylA = 0x9E3779B9u, kWeylB = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hiA = __umulhi(kMulA, c0), loA = kMulA * c0;
+        const uint32_t hiB = __umulhi(kMulB, c2), loB = kMulB * c2;
+        c0 = hiB ^ c1 ^ k0;
+        c1 = loB;
+        c2 = hiA ^ c3 ^ k1;
+        c3 = loA;
+        k0 += kWeylA;
+        k1 += kWeylB;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// The four un-normalised Gaussian coordinates 4q .. 4q+3 of zhat.
+__device__ __forceinline__ void zhat_block(uint64_t seed, int64_t q, float (&z)[4])
+{
+    uint32_t u[4];
+    philox4x32_10((uint32_t)((uint64_t)q & 0xFFFFFFFFull), (uint32_t)((uint64_t)q >> 32), 0u, 0u,
+                  (uint32_t)(seed & 0xFFFFFFFFull), (uint32_t)(seed >> 32), u);
+    constexpr float kScale = 1.0f / 8388608.0f;   // 2^-23
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        // (u >> 9) + 1/2 has at most 24 significant bits: exact in fp32
+        const float a = ((float)(u[2 * h] >> 9) + 0.5f) * kScale;
+        const float b = ((float)(u[2 * h + 1] >> 9) + 0.5f) * kScale;
+        const float rho = sqrtf(-2.0f * logf(a));
+        float s, c;
+        sincospif(2.0f * b, &s, &c);
+        z[2 * h] = rho * c;
+        z[2 * h + 1] = rho * s;
+    }
+}
+
+__global__ void zhat_debug_kernel(uint64_t seed, int64_t x_begin, int64_t count, float *out)
+{
+    const int64_t q0 = x_begin / 4;
+    const int64_t nq = (x_begin + count + 3) / 4 - q0;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < nq;
+         t += (int64_t)gridDim.x * blockDim.x) {
+        float z[4];
+        zhat_block(seed, q0 + t, z);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int64_t x = 4 * (q0 + t) + e;
+            if (x >= x_begin && x < x_begin + count) out[x - x_begin] = z[e];
+        }
+    }
+}
+
+struct VerifyArgs {
+    const float *g;
+    int64_t ld;
+    int32_t n;
+    const float *v;
+    uint64_t seed;
+    const int64_t *off;      // [P+1] device copy
+    double *partial;         // [P][B][S], S = 2n + 1: n norms^2, n <zhat, r_i>, |zhat|^2
+    int32_t S;
+};
+
+template <int NP, int LG>
+__global__ __launch_bounds__(kBlock) void verify_pass_kernel(VerifyArgs a)
+{
+    using G = Geo<NP, LG>;
+    const int j = blockIdx.y;
+    const int n = a.n, S = a.S;
+    const int64_t lo = a.off[j], hi = a.off[j + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lg = lane / G::kLanes, sub = lane % G::kLanes;
+
+    const float *rp[NP];
+    bool have[NP];
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const int i = lg * NP + k;
+        have[k] = i < n;
+        rp[k] = a.g + (int64_t)(have[k] ? i : 0) * a.ld;
+    }
+    double accN[NP], accR[NP];
+#pragma unroll
+    for (int k = 0; k < NP; ++k) { accN[k] = 0.0; accR[k] = 0.0; }
+    double z2 = 0.0;
+
+    const int64_t xa = tile_origin(lo);
+    const int64_t units = (hi > lo) ? (hi - xa + G::kW - 1) / G::kW : 0;
+    const int64_t stride = (int64_t)gridDim.x * kWaves;
+    for (int64_t u = (int64_t)blockIdx.x * kWaves + wave; u < units; u += stride) {
+        const int64_t x0 = xa + u * G::kW + (int64_t)sub * kVec;
+        const bool full = (x0 >= lo) && (x0 + kVec <= hi);
+        float val[NP][4];
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            if (have[k]) load_row4(rp[k], x0, lo, hi, full, val[k]);
+            else { val[k][0] = val[k][1] = val[k][2] = val[k][3] = 0.0f; }
+        }
+        float vf[4];
+        load_row4(a.v, x0, lo, hi, full, vf);
+
+        float zf[4];
+        zhat_block(a.seed, x0 >> 2, zf);            // x0 is a multiple of 4
+        double z[4], vv[4];
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            const int64_t x = x0 + e;
+            z[e] = (x >= lo && x < hi) ? (double)zf[e] : 0.0;
+            vv[e] = (double)vf[e];
+        }
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) {
+                const double r = (double)val[k][e] - vv[e];
+                accN[k] = fma(r, r, accN[k]);
+                accR[k] = fma(z[e], r, accR[k]);
+            }
+        }
+        if (lg == 0) {
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) z2 = fma(z[e], z[e], z2);
+        }
+    }
+
+    __shared__ double sh[kWaves][2 * G::kPeers + 1];
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const double sN = sum_within_group<G::kLanes>(accN[k]);
+        const double sR = sum_within_group<G::kLanes>(accR[k]);
+        if (sub == 0) {
+            sh[wave][lg * NP + k] = sN;
+            sh[wave][G::kPeers + lg * NP + k] = sR;
+        }
+    }
+    {
+        const double s = sum_within_group<G::kLanes>(z2);
+        if (lane == 0) sh[wave][2 * G::kPeers] = s;
+    }
+    __syncthreads();
+    const int B = gridDim.x;
+    double *__restrict__ pb = a.partial + ((int64_t)j * B + blockIdx.x) * S;
+    for (int q = threadIdx.x; q < S; q += kBlock) {
+        int src;
+        if (q < n) src = q;
+        else if (q < 2 * n) src = G::kPeers + (q - n);
+        else src = 2 * G::kPeers;
+        double s = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) s += sh[w][src];
+        pb[q] = s;
+    }
+}
+
+struct VerifyFinishArgs {
+    const double *partial;
+    int32_t n, P, B, S;
+    double tau;
+    double *norms, *weights, *proj, *colsum;   // colsum may be null
+};
+
+// One workgroup per partition.  |zhat|^2 is summed over every partition's
+// partial sums in a fixed order (each workgroup repeats that small sum).
+__global__ __launch_bounds__(kBlock) void verify_finish_kernel(VerifyFinishArgs a)
+{
+    const int j = blockIdx.x;
+    const int n = a.n, P = a.P, B = a.B, S = a.S;
+    const int t = threadIdx.x;
+    __shared__ double s_red[kBlock];
+    __shared__ double s_proj[kBlock];
+    double zz = 0.0;
+    for (int64_t e = t; e < (int64_t)P * B; e += kBlock) zz += a.partial[e * S + 2 * n];
+    s_red[t] = zz;
+    __syncthreads();
+    for (int h = kBlock / 2; h > 0; h >>= 1) {
+        if (t < h) s_red[t] += s_red[t + h];
+        __syncthreads();
+    }
+    const double Z = sqrt(s_red[0]);
+
+    if (t < n) {
+        double N2 = 0.0, Rr = 0.0;
+        const double *pj = a.partial + (int64_t)j * B * S;
+        for (int b = 0; b < B; ++b) {
+            N2 += pj[(int64_t)b * S + t];
+            Rr += pj[(int64_t)b * S + n + t];
+        }
+        const double N = sqrt(N2);
+        const double w = (N <= a.tau) ? 1.0 : a.tau / N;
+        const double s = (Z > 0.0) ? w * Rr / Z : 0.0;
+        a.norms[(int64_t)t * P + j] = N;
+        a.weights[(int64_t)t * P + j] = w;
+        a.proj[(int64_t)t * P + j] = s;
+        s_proj[t] = s;
+    }
+    __syncthreads();
+    if (t == 0 && a.colsum) {
+        double cs = 0.0;
+        for (int i = 0; i < n; ++i) cs += s_proj[i];
+        a.colsum[j] = cs;
+    }
+}
+
+struct DeltaArgs {
+    const float *g;
+    int64_t ld;
+    int32_t n, P;
+    const float *v;
+    const int64_t *off;
+    const double *weights;   // [n][P]
+    float *delta;
+    int64_t ldd;
+};
+
+// Delta_i^j = w_ij (g_i[j] - v[j]), one pass: read n + 1 rows, write n rows.
+__global__ __launch_bounds__(kBlock) void delta_kernel(DeltaArgs a)
+{
+    const int j = blockIdx.y;
+    const int64_t lo = a.off[j], hi = a.off[j + 1];
+    const int64_t xa = tile_origin(lo);
+    const int64_t units = (hi > lo) ? (hi - xa + kVec - 1) / kVec : 0;
+    for (int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x; u < units;
+         u += (int64_t)gridDim.x * kBlock) {
+        const int64_t x0 = xa + u * kVec;
+        const bool full = (x0 >= lo) && (x0 + kVec <= hi);
+        float vf[4];
+        load_row4(a.v, x0, lo, hi, full, vf);
+        for (int i = 0; i < a.n; ++i) {
+            const double w = a.weights[(int64_t)i * a.P + j];
+            float gv[4];
+            load_row4(a.g + (int64_t)i * a.ld, x0, lo, hi, full, gv);
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) o[e] = (float)(w * ((double)gv[e] - (double)vf[e]));
+            float *dst = a.delta + (int64_t)i * a.ldd;
+            if (full) {
+                f32x4_u t;
+                t.x = o[0]; t.y = o[1]; t.z = o[2]; t.w = o[3];
+                *reinterpret_cast<f32x4_u *>(dst + x0) = t;
+            } else {
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) {
+                    const int64_t x = x0 + e;
+                    if (x >= lo && x < hi) dst[x] = o[e];
+                }
+            }
+        }
+    }
+}
+
+}  // namespace btard

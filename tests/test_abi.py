@@ -1,0 +1,104 @@
+"""Host-side checks of the C ABI (no GPU needed): the library loads, exports every
+symbol the header declares, and its pure-host entry points behave."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2106_11257_amd as btard
+from paper_2106_11257_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "btard.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(btard_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = btard.load_library()
+    names = declared_functions()
+    assert {"btard_centered_clip", "btard_verify_projections", "btard_split_offsets",
+            "btard_workspace_bytes", "btard_cc_begin", "btard_cc_iterate",
+            "btard_cc_finish"} <= set(names)
+    for name in names:
+        assert getattr(lib, name) is not None
+        assert hasattr(btard, name), f"python binding lacks {name}"
+
+
+@pytest.mark.parametrize("d,parts", [(10, 3), (0, 4), (7, 8), (11173962, 16), (1315758080, 16),
+                                     (17683968, 64), (1000003, 7)])
+def test_split_offsets_follow_the_paper_rule(d, parts):
+    off = btard.split_offsets(d, parts)
+    assert off == list(oracle.split(d, parts))          # two independent implementations
+    sizes = np.diff(off)
+    assert (sizes[: d % parts] == -(-d // parts)).all() and (sizes[d % parts:] == d // parts).all()
+
+
+def test_split_offsets_rejects_bad_arguments():
+    lib = btard.load_library()
+    buf = (ctypes.c_int64 * 4)()
+    assert lib.btard_split_offsets(-1, 3, buf) == -1
+    assert lib.btard_split_offsets(5, 0, buf) == -1
+    assert lib.btard_split_offsets(5, 3, None) == -1
+
+
+def test_workspace_bytes():
+    assert btard.workspace_bytes(0, 4) == 0
+    assert btard.workspace_bytes(256, 4) == 0
+    assert btard.workspace_bytes(16, 0) == 0
+    a, b, c = (btard.workspace_bytes(16, 16), btard.workspace_bytes(64, 64),
+               btard.workspace_bytes(255, 65535))
+    assert 0 < a < b < c < (1 << 31)
+    assert a % 256 == 0 and b % 256 == 0
+
+
+def test_status_strings():
+    lib = btard.load_library()
+    assert lib.btard_status_string(0) == b"BTARD_OK"
+    assert lib.btard_status_string(-1) == b"BTARD_ERR_INVALID_ARG"
+    assert lib.btard_status_string(-2) == b"BTARD_ERR_WORKSPACE"
+    assert lib.btard_status_string(-3) == b"BTARD_ERR_DEVICE"
+
+
+def test_argument_errors_are_caught_on_the_host_before_any_gpu_call():
+    lib = btard.load_library()
+    off = (ctypes.c_int64 * 3)(0, 4, 8)
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    ws = ctypes.c_void_p(0x10000)
+    big = 1 << 30
+
+    def cc(g=fake, ld=8, n=2, d=8, o=off, parts=2, tau=1.0, eps=1e-6, m=5, v0=None, v=fake,
+           iters=fake, wsp=ws, wsb=big, flags=0):
+        return lib.btard_centered_clip(g, ld, n, d, o, parts, tau, eps, m, v0, v, iters, None,
+                                       wsp, wsb, None, flags)
+
+    assert cc(g=None) == -1
+    assert cc(n=0) == -1 and cc(n=256) == -1
+    assert cc(ld=7) == -1
+    assert cc(d=9) == -1                       # offsets must end at d
+    assert cc(parts=0) == -1
+    assert cc(o=(ctypes.c_int64 * 3)(0, 9, 8)) == -1
+    assert cc(o=(ctypes.c_int64 * 3)(1, 4, 8)) == -1
+    assert cc(tau=0.0) == -1 and cc(tau=float("nan")) == -1
+    assert cc(eps=-1.0) == -1 and cc(m=-1) == -1
+    assert cc(flags=7) == -1
+    assert cc(wsp=None) == -2
+    assert cc(wsp=ctypes.c_void_p(0x10001)) == -2      # misaligned
+    assert cc(wsb=16) == -2
+    assert cc(v=None) == -1 and cc(iters=None) == -1
+    assert cc(v0=fake, v=fake) == -1                   # v must not overlap v0
+
+    def vp(g=fake, v=fake, norms=fake, tau=1.0, delta=None, ldd=0, wsb=big):
+        return lib.btard_verify_projections(g, 8, 2, 8, off, 2, v, tau, 1, norms, fake, fake, None,
+                                            delta, ldd, ws, wsb, None, 0)
+
+    assert vp(g=None) == -1 and vp(v=None) == -1 and vp(norms=None) == -1
+    assert vp(tau=-1.0) == -1
+    assert vp(delta=ctypes.c_void_p(0x2000000), ldd=4) == -1
+    assert vp(wsb=8) == -2

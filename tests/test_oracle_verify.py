@@ -14,7 +14,7 @@ def rng(seed):
 
 
 # --------------------------------------------------------------------------
-# z-spec: Philox4x32-10 -> uniforms on the 2^-24 grid -> Box-Muller -> unit vector
+# z-spec: Philox4x32-10 -> uniforms on the 2^-23 grid -> Box-Muller -> unit vector
 # --------------------------------------------------------------------------
 def test_philox_known_answers(golden_dir):
     rows = 0
@@ -27,19 +27,20 @@ def test_philox_known_answers(golden_dir):
     assert rows == 3
 
 
-def test_uniforms_lie_on_the_open_24_bit_grid_and_follow_the_counter_layout():
+def test_uniforms_lie_on_the_open_23_bit_grid_and_follow_the_counter_layout():
     seed = 0x0123456789ABCDEF
     ab = oracle.z_uniforms(seed, 0, 4096)
-    k = ab * 2 ** 24 - 0.5
+    k = ab * 2 ** 23 - 0.5
     assert (k == np.round(k)).all() and (ab > 0).all() and (ab < 1).all()
+    assert (ab.astype(np.float32).astype(np.float64) == ab).all()      # exact in fp32 too
     # coordinate x uses word x mod 4 of Philox(counter = floor(x/4), key = seed halves)
     for x in (0, 1, 2, 3, 4, 4093, 4095):
         words = oracle.philox4x32_10([x // 4, 0, 0, 0], [seed & 0xFFFFFFFF, seed >> 32])
-        assert ab[x] == ((words[x % 4] >> 8) + 0.5) / 2 ** 24
+        assert ab[x] == ((words[x % 4] >> 9) + 0.5) / 2 ** 23
     # high half of the counter is used beyond 2^34 coordinates
     x = 4 * (2 ** 32 + 5) + 2
     words = oracle.philox4x32_10([5, 1, 0, 0], [seed & 0xFFFFFFFF, seed >> 32])
-    assert oracle.z_uniforms(seed, x, 1)[0] == ((words[2] >> 8) + 0.5) / 2 ** 24
+    assert oracle.z_uniforms(seed, x, 1)[0] == ((words[2] >> 9) + 0.5) / 2 ** 23
     # windows agree with each other
     np.testing.assert_array_equal(oracle.z_uniforms(seed, 1001, 50), ab[1001:1051])
 
