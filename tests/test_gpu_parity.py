@@ -60,7 +60,7 @@ def check_cc(G, off, tau, eps, M, v0=None, parts_to_check=None, label=""):
             lo, hi = off[j], off[j + 1]
             assert rel_l2(v_h[lo:hi], vo[lo:hi]) <= V_TOL, f"partition {j}"
         assert rel_l2(v_h, vo) <= V_TOL
-        np.testing.assert_allclose(sn_h, sno, rtol=SCALAR_TOL, atol=1e-13)
+        np.testing.assert_allclose(sn_h, sno, rtol=SCALAR_TOL, atol=1e-11)
     else:
         for j in todo:
             lo, hi = off[j], off[j + 1]
@@ -69,7 +69,7 @@ def check_cc(G, off, tau, eps, M, v0=None, parts_to_check=None, label=""):
             vo, ito, sno, _ = oracle.centered_clip(sub, [0, hi - lo], tau, eps, M, v0=v0h)
             assert it_h[j] == ito[0], f"partition {j}: iters {it_h[j]} vs oracle {ito[0]}"
             assert rel_l2(v_h[lo:hi], vo) <= V_TOL, f"partition {j}"
-            assert sn_h[j] == pytest.approx(sno[0], rel=SCALAR_TOL, abs=1e-13)
+            assert sn_h[j] == pytest.approx(sno[0], rel=SCALAR_TOL, abs=1e-11)
             say(f"    partition {j}: iters={ito[0]} ok")
     return v, iters, sn
 
@@ -106,7 +106,7 @@ def check_verify(G, off, v, tau, seed, want_delta=False, parts_to_check=None, la
         np.testing.assert_allclose(got["weights"][:, j], r["weights"][:, c], rtol=SCALAR_TOL)
         scale = np.abs(r["proj"][:, c]).sum()
         assert abs(got["colsum"][j] - r["colsum"][c]) <= PROJ_TOL * scale + 1e-300
-        assert got["colsum"][j] == pytest.approx(got["proj"][:, j].sum(), rel=1e-9, abs=1e-300)
+        assert abs(got["colsum"][j] - got["proj"][:, j].sum()) <= 1e-12 * scale + 1e-300
         if want_delta:
             lo, hi = off[j], off[j + 1]
             dref = r["delta"][:, lo:hi] if parts_to_check is None else r["delta"]
