@@ -22,8 +22,8 @@
  *     detected on the host before anything is enqueued.  A partition whose
  *     residual norms are not finite is reported through iters[j] = -1.
  *   - Calls that share a workspace must be ordered on one stream.  Results are
- *     bit-reproducible from run to run on the same device (no floating-point
- *     atomics; fixed reduction order).
+ *     bit-reproducible from run to run on the same device (no atomics; every
+ *     reduction in a fixed order).
  *   - Limits: 1 <= n <= 255, 1 <= parts <= 65535, 0 <= d <= ldg.
  */
 #ifndef BTARD_H_
@@ -101,18 +101,22 @@ int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
 
 /*
  * The same computation in three phases, for callers that drive the iteration
- * themselves (timing one pass, interleaving other work, custom stopping):
+ * themselves (timing one pass, interleaving other work, stopping earlier):
  *
- *   btard_cc_begin    validates, uploads the offsets, sets v^0 (state lives in
- *                     the workspace)
- *   btard_cc_iterate  enqueues `count` iterations of eq. (CenteredClip) on
- *                     every partition that has not stopped yet (one pass over
- *                     the n x d matrix each); partitions that stopped are
- *                     skipped on the device, without host involvement
- *   btard_cc_finish   writes v, iters and last_step_norm (one more pass)
+ *   btard_cc_begin    validates, uploads the offsets, sets v^0 (the state lives
+ *                     in the workspace)
+ *   btard_cc_iterate  enqueues iterations first_iteration .. first_iteration +
+ *                     count - 1 of eq. (CenteredClip) (one pass over the n x d
+ *                     matrix each) on every partition that has not stopped;
+ *                     stopped partitions are skipped on the device, without
+ *                     host involvement.  Iterations must be enqueued in order,
+ *                     starting at 0, without gaps: the caller keeps the count.
+ *   btard_cc_finish   `iterations` = how many were enqueued in total; applies
+ *                     the last update and writes v, iters and last_step_norm
+ *                     (one more pass)
  *
- * btard_centered_clip == begin; iterate(max_iters); finish.  The problem
- * description must be identical in the three calls.
+ * btard_centered_clip == begin; iterate(0, max_iters); finish(max_iters).  The
+ * problem description must be identical in all calls of one run.
  */
 typedef struct btard_cc_problem {
     const float *g;              /* DEVICE */
@@ -132,8 +136,8 @@ typedef struct btard_cc_problem {
 } btard_cc_problem;
 
 int btard_cc_begin(const btard_cc_problem *p);
-int btard_cc_iterate(const btard_cc_problem *p, int32_t count);
-int btard_cc_finish(const btard_cc_problem *p, float *v, int32_t *iters,
+int btard_cc_iterate(const btard_cc_problem *p, int32_t first_iteration, int32_t count);
+int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int32_t *iters,
                     double *last_step_norm);
 
 /*

@@ -70,9 +70,10 @@ def load_library():
     lib.btard_centered_clip.restype = c.c_int
     lib.btard_cc_begin.argtypes = [c.POINTER(_Problem)]
     lib.btard_cc_begin.restype = c.c_int
-    lib.btard_cc_iterate.argtypes = [c.POINTER(_Problem), c.c_int32]
+    lib.btard_cc_iterate.argtypes = [c.POINTER(_Problem), c.c_int32, c.c_int32]
     lib.btard_cc_iterate.restype = c.c_int
-    lib.btard_cc_finish.argtypes = [c.POINTER(_Problem), c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.btard_cc_finish.argtypes = [c.POINTER(_Problem), c.c_int32, c.c_void_p, c.c_void_p,
+                                    c.c_void_p]
     lib.btard_cc_finish.restype = c.c_int
     lib.btard_verify_projections.argtypes = [
         c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.POINTER(c.c_int64), c.c_int32,
@@ -180,11 +181,12 @@ def cc_begin(p: Problem) -> None:
     _check(load_library().btard_cc_begin(ctypes.byref(p.c)), "btard_cc_begin")
 
 
-def cc_iterate(p: Problem, count: int) -> None:
-    _check(load_library().btard_cc_iterate(ctypes.byref(p.c), int(count)), "btard_cc_iterate")
+def cc_iterate(p: Problem, first_iteration: int, count: int) -> None:
+    _check(load_library().btard_cc_iterate(ctypes.byref(p.c), int(first_iteration), int(count)),
+           "btard_cc_iterate")
 
 
-def cc_finish(p: Problem, v: Optional[torch.Tensor] = None,
+def cc_finish(p: Problem, iterations: int, v: Optional[torch.Tensor] = None,
               iters: Optional[torch.Tensor] = None,
               last_step_norm: Optional[torch.Tensor] = None):
     dev = p.g.device
@@ -194,8 +196,8 @@ def cc_finish(p: Problem, v: Optional[torch.Tensor] = None,
         iters = torch.empty(p.parts, dtype=torch.int32, device=dev)
     if last_step_norm is None:
         last_step_norm = torch.empty(p.parts, dtype=torch.float64, device=dev)
-    _check(load_library().btard_cc_finish(ctypes.byref(p.c), _ptr(v), _ptr(iters),
-                                          _ptr(last_step_norm)), "btard_cc_finish")
+    _check(load_library().btard_cc_finish(ctypes.byref(p.c), int(iterations), _ptr(v),
+                                          _ptr(iters), _ptr(last_step_norm)), "btard_cc_finish")
     return v, iters, last_step_norm
 
 

@@ -23,22 +23,23 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-    size_t off, coef, delta, counter, iters, done, partial, total;
+    size_t off, coef, delta, iters, done, partial, partial_stride_doubles, total;
 };
 
+// State and partial sums exist twice (double-buffered by pass parity).
 WsLayout ws_layout(int32_t n, int32_t P)
 {
     WsLayout L{};
     const size_t R = (size_t)n + 1, S = 2 * (size_t)n + 2;
     size_t p = kAlign;                                    // 256-byte header, reserved
     L.off = p;      p = align_up(p + sizeof(int64_t) * ((size_t)P + 1));
-    L.coef = p;     p = align_up(p + sizeof(double) * P * R);
-    L.delta = p;    p = align_up(p + sizeof(double) * P * R);
-    L.counter = p;  p = align_up(p + sizeof(unsigned int) * P);
-    L.iters = p;    p = align_up(p + sizeof(int32_t) * P);
-    L.done = p;     p = align_up(p + sizeof(int32_t) * P);
+    L.coef = p;     p = align_up(p + 2 * sizeof(double) * P * R);
+    L.delta = p;    p = align_up(p + 2 * sizeof(double) * P * R);
+    L.iters = p;    p = align_up(p + 2 * sizeof(int32_t) * P);
+    L.done = p;     p = align_up(p + 2 * sizeof(int32_t) * P);
     const size_t blocks = (size_t)(P > kMaxBlocks ? P : kMaxBlocks);
-    L.partial = p;  p = align_up(p + sizeof(double) * blocks * S);
+    L.partial_stride_doubles = align_up(sizeof(double) * blocks * S) / sizeof(double);
+    L.partial = p;  p = align_up(p + 2 * sizeof(double) * L.partial_stride_doubles);
     L.total = p;
     return L;
 }
@@ -71,10 +72,11 @@ CcState carve_cc(void *ws, int32_t n, int32_t P)
     st.coef = reinterpret_cast<double *>(b + L.coef);
     st.delta = reinterpret_cast<double *>(b + L.delta);
     st.partial = reinterpret_cast<double *>(b + L.partial);
-    st.counter = reinterpret_cast<unsigned int *>(b + L.counter);
     st.iters = reinterpret_cast<int32_t *>(b + L.iters);
     st.done = reinterpret_cast<int32_t *>(b + L.done);
+    st.partial_stride = (int64_t)L.partial_stride_doubles;
     st.R = n + 1;
+    st.P = P;
     return st;
 }
 
@@ -107,33 +109,48 @@ typedef void (*CcPassFn)(CcArgs);
 typedef void (*CcFinishFn)(CcFinishArgs);
 typedef void (*VerifyFn)(VerifyArgs);
 
-const CcPassFn kCcPass[kVariants] = {
-    cc_pass_kernel<4, 1>, cc_pass_kernel<8, 1>, cc_pass_kernel<16, 1>, cc_pass_kernel<16, 2>,
-    cc_pass_kernel<16, 4>, cc_pass_kernel<16, 8>, cc_pass_kernel<16, 16>};
-const CcFinishFn kCcFinish[kVariants] = {
-    cc_finish_kernel<4, 1>, cc_finish_kernel<8, 1>, cc_finish_kernel<16, 1>,
-    cc_finish_kernel<16, 2>, cc_finish_kernel<16, 4>, cc_finish_kernel<16, 8>,
-    cc_finish_kernel<16, 16>};
-const VerifyFn kVerify[kVariants] = {
-    verify_pass_kernel<4, 1>, verify_pass_kernel<8, 1>, verify_pass_kernel<16, 1>,
-    verify_pass_kernel<16, 2>, verify_pass_kernel<16, 4>, verify_pass_kernel<16, 8>,
-    verify_pass_kernel<16, 16>};
+// [variant][ragged: n < NP*LG][has v0]
+#define BTARD_CC_ROW(K, NP, LG)                                                   \
+    {{K<NP, LG, false, false>, K<NP, LG, false, true>},                           \
+     {K<NP, LG, true, false>, K<NP, LG, true, true>}}
+const CcPassFn kCcPass[kVariants][2][2] = {
+    BTARD_CC_ROW(cc_pass_kernel, 4, 1),  BTARD_CC_ROW(cc_pass_kernel, 8, 1),
+    BTARD_CC_ROW(cc_pass_kernel, 16, 1), BTARD_CC_ROW(cc_pass_kernel, 16, 2),
+    BTARD_CC_ROW(cc_pass_kernel, 16, 4), BTARD_CC_ROW(cc_pass_kernel, 16, 8),
+    BTARD_CC_ROW(cc_pass_kernel, 16, 16)};
+const CcFinishFn kCcFinish[kVariants][2][2] = {
+    BTARD_CC_ROW(cc_finish_kernel, 4, 1),  BTARD_CC_ROW(cc_finish_kernel, 8, 1),
+    BTARD_CC_ROW(cc_finish_kernel, 16, 1), BTARD_CC_ROW(cc_finish_kernel, 16, 2),
+    BTARD_CC_ROW(cc_finish_kernel, 16, 4), BTARD_CC_ROW(cc_finish_kernel, 16, 8),
+    BTARD_CC_ROW(cc_finish_kernel, 16, 16)};
+#undef BTARD_CC_ROW
+#define BTARD_V_ROW(NP, LG) {verify_pass_kernel<NP, LG, false>, verify_pass_kernel<NP, LG, true>}
+const VerifyFn kVerify[kVariants][2] = {BTARD_V_ROW(4, 1),  BTARD_V_ROW(8, 1),  BTARD_V_ROW(16, 1),
+                                        BTARD_V_ROW(16, 2), BTARD_V_ROW(16, 4), BTARD_V_ROW(16, 8),
+                                        BTARD_V_ROW(16, 16)};
+#undef BTARD_V_ROW
+
+int variant_peers(Variant v)
+{
+    static const int peers[kVariants] = {4, 8, 16, 32, 64, 128, 256};
+    return peers[v];
+}
 
 // Workgroups that are resident at once for a kernel on the current device
 // (compute units x occupancy), cached per (device, kernel).
 struct ResidentCache {
     std::mutex mu;
-    int value[16][3][kVariants] = {};
+    int value[16][3][kVariants][4] = {};
 };
 ResidentCache g_resident;
 
-int resident_blocks(int kind, Variant v, const void *fn)
+int resident_blocks(int kind, Variant v, int sub, const void *fn)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (dev < 0 || dev >= 16) dev = 0;
     std::lock_guard<std::mutex> lock(g_resident.mu);
-    int &slot = g_resident.value[dev][kind][v];
+    int &slot = g_resident.value[dev][kind][v][sub];
     if (slot == 0) {
         int cus = 0, occ = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
@@ -240,47 +257,70 @@ int btard_cc_begin(const btard_cc_problem *p)
     CcState st = carve_cc(p->workspace, p->n, p->parts);
     const int up = upload_offsets(p->offsets_host, p->parts, st.off, s);
     if (up != BTARD_OK) return up;
-    hipLaunchKernelGGL(cc_init_kernel, dim3(p->parts), dim3(64), 0, s, st, p->n, p->parts,
-                       p->v0 ? 1 : 0, p->max_iters);
+    hipLaunchKernelGGL(cc_init_kernel, dim3(p->parts), dim3(64), 0, s, st, p->n, p->v0 ? 1 : 0,
+                       p->max_iters);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
-int btard_cc_iterate(const btard_cc_problem *p, int32_t count)
+// Workgroups per partition of the pass kernel for this problem (the same in every pass).
+static int pass_blocks(const btard_cc_problem *p, Variant var, int ragged, int based)
+{
+    const CcPassFn fn = kCcPass[var][ragged][based];
+    const int resident = resident_blocks(0, var, ragged * 2 + based, reinterpret_cast<const void *>(fn));
+    if (resident <= 0) return 0;
+    return blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
+}
+
+int btard_cc_iterate(const btard_cc_problem *p, int32_t first_iteration, int32_t count)
 {
     const int rc = check_problem(p);
     if (rc != BTARD_OK) return rc;
-    if (count < 0) return BTARD_ERR_INVALID_ARG;
+    if (count < 0 || first_iteration < 0) return BTARD_ERR_INVALID_ARG;
     if (count == 0) return BTARD_OK;
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     const Variant var = pick_variant(p->n);
-    const int resident = resident_blocks(0, var, reinterpret_cast<const void *>(kCcPass[var]));
-    if (resident <= 0) return BTARD_ERR_DEVICE;
-    const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
+    const int ragged = p->n < variant_peers(var) ? 1 : 0, based = p->v0 ? 1 : 0;
+    const CcPassFn fn = kCcPass[var][ragged][based];
+    const int B = pass_blocks(p, var, ragged, based);
+    if (B <= 0) return BTARD_ERR_DEVICE;
     CcArgs a;
     a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = p->v0;
     a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
+    a.prev_blocks = B;
     a.st = carve_cc(p->workspace, p->n, p->parts);
-    for (int32_t l = 0; l < count; ++l)
-        hipLaunchKernelGGL(kCcPass[var], dim3(B, p->parts), dim3(kBlock), 0, s, a);
+    for (int32_t l = 0; l < count; ++l) {
+        a.pass = first_iteration + l;
+        hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
+    }
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
-int btard_cc_finish(const btard_cc_problem *p, float *v, int32_t *iters, double *last_step_norm)
+int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int32_t *iters,
+                    double *last_step_norm)
 {
     const int rc = check_problem(p);
     if (rc != BTARD_OK) return rc;
-    if (!v || !iters) return BTARD_ERR_INVALID_ARG;
+    if (!v || !iters || iterations < 0) return BTARD_ERR_INVALID_ARG;
     if (overlaps(v, p->v0, p->d)) return BTARD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     const Variant var = pick_variant(p->n);
-    const int resident = resident_blocks(1, var, reinterpret_cast<const void *>(kCcFinish[var]));
+    const int ragged = p->n < variant_peers(var) ? 1 : 0, based = p->v0 ? 1 : 0;
+    const CcFinishFn fn = kCcFinish[var][ragged][based];
+    const int resident = resident_blocks(1, var, ragged * 2 + based, reinterpret_cast<const void *>(fn));
     if (resident <= 0) return BTARD_ERR_DEVICE;
     const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
+    const int Bpass = pass_blocks(p, var, ragged, based);
+    if (Bpass <= 0) return BTARD_ERR_DEVICE;
     CcFinishArgs a;
     a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = p->v0; a.v = v;
-    a.iters_out = iters; a.step_norm_out = last_step_norm;
+    a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
+    a.pass = iterations; a.prev_blocks = Bpass;
     a.st = carve_cc(p->workspace, p->n, p->parts);
-    hipLaunchKernelGGL(kCcFinish[var], dim3(B, p->parts), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
+    CcReportArgs r;
+    r.st = a.st; r.pass = iterations; r.blocks = B; r.iters_out = iters;
+    r.step_norm_out = last_step_norm;
+    hipLaunchKernelGGL(cc_report_kernel, dim3(p->parts), dim3(kBlock), 0, s, r);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
@@ -300,9 +340,9 @@ int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
     if (!v || !iters || overlaps(v, v0, d)) return BTARD_ERR_INVALID_ARG;
     rc = btard_cc_begin(&p);
     if (rc != BTARD_OK) return rc;
-    rc = btard_cc_iterate(&p, max_iters);
+    rc = btard_cc_iterate(&p, 0, max_iters);
     if (rc != BTARD_OK) return rc;
-    return btard_cc_finish(&p, v, iters, last_step_norm);
+    return btard_cc_finish(&p, max_iters, v, iters, last_step_norm);
 }
 
 int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
@@ -325,19 +365,21 @@ int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
     if (up != BTARD_OK) return up;
 
     const Variant var = pick_variant(n);
-    const int resident = resident_blocks(2, var, reinterpret_cast<const void *>(kVerify[var]));
+    const int ragged = n < variant_peers(var) ? 1 : 0;
+    const VerifyFn vfn = kVerify[var][ragged];
+    const int resident = resident_blocks(2, var, ragged, reinterpret_cast<const void *>(vfn));
     if (resident <= 0) return BTARD_ERR_DEVICE;
     const int B = blocks_per_partition(resident, parts, offsets_host, variant_tile_width(var));
 
     VerifyArgs a;
     a.g = g; a.ld = ldg; a.n = n; a.v = v; a.seed = seed; a.off = st.off;
     a.partial = st.partial; a.S = 2 * n + 1;
-    hipLaunchKernelGGL(kVerify[var], dim3(B, parts), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL(vfn, dim3(B, parts), dim3(kBlock), 0, s, a);
 
     VerifyFinishArgs f;
     f.partial = st.partial; f.n = n; f.P = parts; f.B = B; f.S = a.S; f.tau = (double)tau;
     f.norms = norms; f.weights = weights; f.proj = proj; f.colsum = colsum;
-    hipLaunchKernelGGL(verify_finish_kernel, dim3(parts), dim3(kBlock), 0, s, f);
+    hipLaunchKernelGGL(verify_finish_kernel, dim3(parts), dim3(kFinishThreads), 0, s, f);
 
     if (delta) {
         DeltaArgs da;

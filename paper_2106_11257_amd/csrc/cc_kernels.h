@@ -11,9 +11,17 @@
 // ONE pass over the n x d_j slab: recompute v^l[x] from the n values of
 // coordinate x that are in registers anyway, accumulate ||g_i - v^l||^2 for
 // every peer, and ||sum_i a_i g_i||^2 = ||v^l - v^{l-1}||^2 for the stopping
-// rule.  The last workgroup of a partition to finish reduces the partial sums
-// in a fixed order and advances the coefficients, so the host never
-// synchronises inside the iteration.
+// rule; each workgroup stores its partial sums.
+//
+// The scalar work between two passes (fixed-order reduction of the partial
+// sums, weights, coefficient update, stopping rule: "the control step") is done
+// at the START of the next kernel by every workgroup of the partition, each for
+// itself, from the previous pass's partial sums: all of them execute the same
+// instructions on the same data and so reach the same coefficients and the same
+// decision.  That needs no atomics, no device-wide fences and no extra launch;
+// the kernel boundary makes the partial sums visible.  State and partial sums
+// are double-buffered by pass parity, so a workgroup that is still reading
+// pass l-1's results is never overtaken by one that already stores pass l's.
 #pragma once
 
 #include "kernels_common.h"
@@ -22,13 +30,14 @@ namespace btard {
 
 struct CcState {
     const int64_t *off;      // [P+1] partition offsets (device copy)
-    double *coef;            // [P][R]  c_i, i < n; entry n = coefficient of v0
-    double *delta;           // [P][R]  a_i of the last applied update
-    double *partial;         // [P][B][R] per-workgroup partial sums (n norms^2, step^2)
-    unsigned int *counter;   // [P] workgroups finished in the current pass
-    int32_t *iters;          // [P] updates applied so far (-1: non-finite norm)
-    int32_t *done;           // [P] partition stopped
+    double *coef;            // [2][P][R]  c_i, i < n; entry n = coefficient of v0
+    double *delta;           // [2][P][R]  a_i of the last applied update
+    double *partial;         // [2][P*B*R] per-workgroup partial sums (n norms^2, step^2)
+    int32_t *iters;          // [2][P] updates applied so far (-1: non-finite norm)
+    int32_t *done;           // [2][P] partition stopped
+    int64_t partial_stride;  // doubles between the two partial-sum buffers
     int32_t R;               // n + 1
+    int32_t P;
 };
 
 struct CcArgs {
@@ -38,6 +47,8 @@ struct CcArgs {
     const float *v0;         // may be null
     double tau, eps;
     int32_t max_iters;
+    int32_t pass;            // index l of this pass (0-based)
+    int32_t prev_blocks;     // workgroups per partition of the previous pass
     CcState st;
 };
 
@@ -55,10 +66,10 @@ __global__ void upload_offsets_kernel(int64_t *off, int32_t first, int32_t count
     if (t < count) off[first + t] = chunk.v[t];
 }
 
-__global__ void cc_init_kernel(CcState st, int32_t n, int32_t P, int32_t has_v0, int32_t max_iters)
+__global__ void cc_init_kernel(CcState st, int32_t n, int32_t has_v0, int32_t max_iters)
 {
     const int j = blockIdx.x;
-    if (j >= P) return;
+    if (j >= st.P) return;
     for (int q = threadIdx.x; q < st.R; q += blockDim.x) {
         double c;
         if (has_v0) c = (q == n) ? 1.0 : 0.0;
@@ -67,87 +78,199 @@ __global__ void cc_init_kernel(CcState st, int32_t n, int32_t P, int32_t has_v0,
         st.delta[(int64_t)j * st.R + q] = 0.0;
     }
     if (threadIdx.x == 0) {
-        st.counter[j] = 0u;
         st.iters[j] = 0;
         st.done[j] = (max_iters <= 0) ? 1 : 0;
     }
 }
 
 // ---------------------------------------------------------------------------
-// one iteration: S2 (norms) + S3 (weights) + S4 (update, in coefficients) + S5
+// control step: weights, update in coefficients, stopping rule
 // ---------------------------------------------------------------------------
-template <int NP, int LG>
-__global__ __launch_bounds__(kBlock) void cc_pass_kernel(CcArgs a)
+// Brings partition j's state from "after pass-1" to "ready for pass `pass`": every thread
+// of the workgroup takes part.  On return s_c / s_a hold c^pass / a^pass (R entries), and
+// the function value is true if the partition has stopped.  Workgroup 0 of the partition
+// also records the new state in buffer (pass & 1).
+__device__ __forceinline__ bool control_step(const CcState &st, int j, int n, double tau,
+                                             double eps, int max_iters, int pass, int prev_blocks,
+                                             double *s_c, double *s_a, double *s_red,
+                                             int *s_flags, int *iters_out)
 {
-    using G = Geo<NP, LG>;
-    const int j = blockIdx.y;
-    if (a.st.done[j]) return;                       // uniform: whole partition skipped
+    const int R = st.R, P = st.P;
+    const int t = threadIdx.x;
+    if (pass == 0) {
+        // state buffer 0 as set by cc_init_kernel; nothing to advance
+        if (t < R) {
+            s_c[t] = st.coef[(int64_t)j * R + t];
+            s_a[t] = st.delta[(int64_t)j * R + t];
+        }
+        __syncthreads();
+        *iters_out = st.iters[j];
+        return st.done[j] != 0;
+    }
+    const int prev = (pass - 1) & 1, cur = pass & 1;
+    const double *cp = st.coef + ((int64_t)prev * P + j) * R;
+    const double *ap = st.delta + ((int64_t)prev * P + j) * R;
+    double cq = 0.0, aq = 0.0;
+    if (t < R) { cq = cp[t]; aq = ap[t]; }
+    int it = st.iters[prev * P + j];
+    int dn = st.done[prev * P + j];
 
-    const int n = a.n, R = a.st.R;
-    const int64_t lo = a.st.off[j], hi = a.st.off[j + 1];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int lg = lane / G::kLanes, sub = lane % G::kLanes;
+    if (!dn) {                                               // uniform over the workgroup
+        const double *pj = st.partial + prev * st.partial_stride + (int64_t)j * prev_blocks * R;
+        const double tot = reduce_partials<kBlock>(pj, prev_blocks, R, R, s_red);
+        if (t == 0) { s_flags[0] = 0; s_flags[1] = 0; }
+        __syncthreads();
+        // quantity n is ||v^it - v^{it-1}||^2: did update number `it` already converge?
+        if (t == n && it >= 1 && sqrt(tot) < eps) s_flags[0] = 1;
+        double w = 0.0;
+        if (t < n) {
+            const double N = sqrt(tot);
+            if (!isfinite(N)) s_flags[1] = 1;
+            w = (N <= tau) ? 1.0 : tau / N;
+        }
+        __syncthreads();
+        s_red[t] = w;
+        __syncthreads();
+        if (s_flags[0]) {
+            dn = 1;                                          // v^it is final; c, a unchanged
+        } else if (s_flags[1]) {
+            dn = 1; it = -1;
+        } else {
+            double W = 0.0;
+            for (int i = 0; i < n; ++i) W += s_red[i];
+            if (t < R) {
+                aq = ((t < n ? w : 0.0) - W * cq) / (double)n;
+                cq = cq + aq;
+            }
+            it = it + 1;
+            if (it >= max_iters) dn = 1;
+        }
+    }
+    if (t < R) { s_c[t] = cq; s_a[t] = aq; }
+    if (blockIdx.x == 0) {
+        if (t < R) {
+            st.coef[((int64_t)cur * P + j) * R + t] = cq;
+            st.delta[((int64_t)cur * P + j) * R + t] = aq;
+        }
+        if (t == 0) { st.iters[cur * P + j] = it; st.done[cur * P + j] = dn; }
+    }
+    __syncthreads();
+    *iters_out = it;
+    return dn != 0;
+}
 
-    const double *__restrict__ cj = a.st.coef + (int64_t)j * R;
-    const double *__restrict__ dj = a.st.delta + (int64_t)j * R;
-    double c[NP], dl[NP];
-    const float *rp[NP];
-    bool have[NP];
+// A workgroup-uniform double held in LDS -> scalar registers.
+__device__ __forceinline__ double uniform_double(double x)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+// This lane group's coefficients out of LDS.
+template <int NP, int LG, bool RAGGED>
+__device__ __forceinline__ void fetch_coefficients(const double *s_c, const double *s_a, int n, int lg,
+                                                   double (&c)[NP], double (&dl)[NP], double &cb,
+                                                   double &db)
+{
 #pragma unroll
     for (int k = 0; k < NP; ++k) {
         const int i = lg * NP + k;
-        have[k] = i < n;
-        c[k] = have[k] ? cj[i] : 0.0;
-        dl[k] = have[k] ? dj[i] : 0.0;
-        rp[k] = a.g + (int64_t)(have[k] ? i : 0) * a.ld;
+        const bool have = !RAGGED || i < n;
+        double ck = have ? s_c[have ? i : 0] : 0.0;
+        double ak = have ? s_a[have ? i : 0] : 0.0;
+        if (LG == 1) { ck = uniform_double(ck); ak = uniform_double(ak); }
+        c[k] = ck;
+        dl[k] = ak;
     }
-    const bool has_v0 = a.v0 != nullptr;
-    const double cb = cj[n], db = dj[n];
+    cb = uniform_double(s_c[n]);
+    db = uniform_double(s_a[n]);
+}
+
+// Per tile: v^l[x] = c_0 v0[x] + sum_i c_i g_i[x] and u[x] = a_0 v0[x] + sum_i a_i g_i[x]
+// (= (v^l - v^{l-1})[x]) for the lane's 4 coordinates, from the peers' values held in
+// registers.  With several lane groups the per-group partial sums are combined by a
+// butterfly over the groups.
+template <int NP, int LG, bool HAS_BASE>
+__device__ __forceinline__ void combine_rows(const float (&val)[NP][4], const float (&base)[4],
+                                             const double (&c)[NP], const double (&dl)[NP],
+                                             double cb, double db, double (&vv)[4], double (&ss)[4])
+{
+    using G = Geo<NP, LG>;
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) { vv[e] = 0.0; ss[e] = 0.0; }
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            const double gd = (double)val[k][e];
+            vv[e] = fma(c[k], gd, vv[e]);
+            ss[e] = fma(dl[k], gd, ss[e]);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+        vv[e] = sum_across_groups<G::kLanes>(vv[e]);
+        ss[e] = sum_across_groups<G::kLanes>(ss[e]);
+        if (HAS_BASE) {
+            vv[e] = fma(cb, (double)base[e], vv[e]);
+            ss[e] = fma(db, (double)base[e], ss[e]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// one iteration: control step for the previous pass, then norms at v^l
+// ---------------------------------------------------------------------------
+template <int NP, int LG, bool RAGGED, bool HAS_BASE>
+__global__ __launch_bounds__(kBlock) void cc_pass_kernel(CcArgs a)
+{
+    using G = Geo<NP, LG>;
+    __shared__ double s_c[kBlock], s_a[kBlock], s_red[kBlock];
+    __shared__ int s_flags[2];
+    __shared__ double sh[kWaves][G::kPeers + 1];
+
+    const int j = blockIdx.y;
+    const int n = a.n, R = a.st.R;
+    int iters_now;
+    if (control_step(a.st, j, n, a.tau, a.eps, a.max_iters, a.pass, a.prev_blocks, s_c, s_a, s_red,
+                     s_flags, &iters_now))
+        return;                                     // uniform: this partition has stopped
+
+    const int64_t lo = a.st.off[j], hi = a.st.off[j + 1];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lg = lane / G::kLanes, sub = lane % G::kLanes;
+
+    double c[NP], dl[NP], cb, db;
+    fetch_coefficients<NP, LG, RAGGED>(s_c, s_a, n, lg, c, dl, cb, db);
 
     double acc[NP];
 #pragma unroll
     for (int k = 0; k < NP; ++k) acc[k] = 0.0;
     double t2 = 0.0;
 
-    const int64_t xa = tile_origin(lo);
-    const int64_t units = (hi > lo) ? (hi - xa + G::kW - 1) / G::kW : 0;
-    const int64_t stride = (int64_t)gridDim.x * kWaves;
-    for (int64_t u = (int64_t)blockIdx.x * kWaves + wave; u < units; u += stride) {
-        const int64_t x0 = xa + u * G::kW + (int64_t)sub * kVec;
-        const bool full = (x0 >= lo) && (x0 + kVec <= hi);
+    const TileRange tr = tile_range<G::kW>(lo, hi);
+    for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
+        const int64_t xu = tr.xa + u * G::kW;
+        const bool interior = (xu >= lo) && (xu + G::kW <= hi);   // wavefront-uniform
         float val[NP][4];
-#pragma unroll
-        for (int k = 0; k < NP; ++k) {
-            if (have[k]) load_row4(rp[k], x0, lo, hi, full, val[k]);
-            else { val[k][0] = val[k][1] = val[k][2] = val[k][3] = 0.0f; }
-        }
+        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
         float base[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (has_v0) load_row4(a.v0, x0, lo, hi, full, base);
-
-        // v^l[x] and (v^l - v^{l-1})[x] from this lane group's peers ...
-        double vv[4] = {0.0, 0.0, 0.0, 0.0}, ss[4] = {0.0, 0.0, 0.0, 0.0};
+        if (HAS_BASE) {
+            const int64_t x0 = xu + (int64_t)sub * kVec;
+            if (interior) load_row4_vec(a.v0 + x0, base);
+            else load_row4_guarded(a.v0, x0, lo, hi, base);
+        }
+        double vv[4], ss[4];
+        combine_rows<NP, LG, HAS_BASE>(val, base, c, dl, cb, db, vv, ss);
+        // residual norms ||g_i - v^l||^2 (masked coordinates hold zeros in every row)
 #pragma unroll
         for (int k = 0; k < NP; ++k) {
 #pragma unroll
             for (int e = 0; e < kVec; ++e) {
-                const double gd = (double)val[k][e];
-                vv[e] = fma(c[k], gd, vv[e]);
-                ss[e] = fma(dl[k], gd, ss[e]);
-            }
-        }
-        // ... then over all peers, and the v0 term
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) {
-            vv[e] = sum_across_groups<G::kLanes>(vv[e]);
-            ss[e] = sum_across_groups<G::kLanes>(ss[e]);
-            vv[e] = fma(cb, (double)base[e], vv[e]);
-            ss[e] = fma(db, (double)base[e], ss[e]);
-        }
-        // residual norms ||g_i - v^l||^2 (masked coordinates hold zeros everywhere)
-#pragma unroll
-        for (int k = 0; k < NP; ++k) {
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) {
+                forget(val[k][e]);
                 const double r = (double)val[k][e] - vv[e];
                 acc[k] = fma(r, r, acc[k]);
             }
@@ -159,19 +282,17 @@ __global__ __launch_bounds__(kBlock) void cc_pass_kernel(CcArgs a)
     }
 
     // workgroup partial sums: lanes -> wavefront -> LDS -> one value per quantity
-    __shared__ double sh[kWaves][G::kPeers + 1];
+    sum_within_group_all<G::kLanes, NP>(acc);
+    t2 = sum_within_group<G::kLanes>(t2);
+    if (sub == 0) {
 #pragma unroll
-    for (int k = 0; k < NP; ++k) {
-        const double s = sum_within_group<G::kLanes>(acc[k]);
-        if (sub == 0) sh[wave][lg * NP + k] = s;
+        for (int k = 0; k < NP; ++k) sh[wave][lg * NP + k] = acc[k];
     }
-    {
-        const double s = sum_within_group<G::kLanes>(t2);
-        if (lane == 0) sh[wave][G::kPeers] = s;
-    }
+    if (lane == 0) sh[wave][G::kPeers] = t2;
     __syncthreads();
     const int B = gridDim.x;
-    double *__restrict__ pj = a.st.partial + (int64_t)j * B * R;
+    double *__restrict__ pj =
+        a.st.partial + (a.pass & 1) * a.st.partial_stride + (int64_t)j * B * R;
     if ((int)threadIdx.x < R) {
         const int q = threadIdx.x;
         const int src = (q == n) ? G::kPeers : q;
@@ -180,59 +301,11 @@ __global__ __launch_bounds__(kBlock) void cc_pass_kernel(CcArgs a)
         for (int w = 0; w < kWaves; ++w) s += sh[w][src];
         pj[(int64_t)blockIdx.x * R + q] = s;
     }
-
-    if (!last_block_of_partition(&a.st.counter[j], (unsigned)B)) return;
-
-    // ---- control: fixed-order reduction, weights, coefficient update, stopping rule
-    __shared__ double s_w[kBlock];
-    __shared__ int s_bad;
-    __shared__ int s_stop;
-    const int q = threadIdx.x;
-    if (q == 0) { s_bad = 0; s_stop = 0; }
-    double tot = 0.0;
-    if (q < R)
-        for (int b = 0; b < B; ++b) tot += pj[(int64_t)b * R + q];
-    __syncthreads();
-    const int it = a.st.iters[j];
-    if (q == n) {
-        // tot = ||v^it - v^{it-1}||^2: did update number `it` already converge?
-        if (it >= 1 && sqrt(tot) < a.eps) s_stop = 1;
-    }
-    double w = 0.0;
-    if (q < n) {
-        const double N = sqrt(tot);
-        if (!isfinite(N)) s_bad = 1;
-        w = (N <= a.tau) ? 1.0 : a.tau / N;
-        s_w[q] = w;
-    }
-    __syncthreads();
-    if (s_stop) {
-        if (q == 0) { a.st.done[j] = 1; a.st.counter[j] = 0u; }
-        return;
-    }
-    if (s_bad) {
-        if (q == 0) { a.st.iters[j] = -1; a.st.done[j] = 1; a.st.counter[j] = 0u; }
-        return;
-    }
-    double W = 0.0;
-    for (int i = 0; i < n; ++i) W += s_w[i];
-    if (q < R) {
-        double *cw = a.st.coef + (int64_t)j * R;
-        double *dw = a.st.delta + (int64_t)j * R;
-        const double cq = cw[q];
-        const double aq = ((q < n ? w : 0.0) - W * cq) / (double)n;
-        dw[q] = aq;
-        cw[q] = cq + aq;
-    }
-    if (q == 0) {
-        a.st.iters[j] = it + 1;
-        if (it + 1 >= a.max_iters) a.st.done[j] = 1;
-        a.st.counter[j] = 0u;
-    }
 }
 
 // ---------------------------------------------------------------------------
-// finish: v = c_0 v0 + sum_i c_i g_i rounded to fp32, ||last update||, iters
+// finish: last control step, v = c_0 v0 + sum_i c_i g_i rounded to fp32,
+// partial sums of ||last update||^2
 // ---------------------------------------------------------------------------
 struct CcFinishArgs {
     const float *g;
@@ -240,71 +313,52 @@ struct CcFinishArgs {
     int32_t n;
     const float *v0;
     float *v;
-    int32_t *iters_out;
-    double *step_norm_out;   // may be null
+    double tau, eps;
+    int32_t max_iters;
+    int32_t pass;            // number of passes that were enqueued
+    int32_t prev_blocks;
     CcState st;
 };
 
-template <int NP, int LG>
+template <int NP, int LG, bool RAGGED, bool HAS_BASE>
 __global__ __launch_bounds__(kBlock) void cc_finish_kernel(CcFinishArgs a)
 {
     using G = Geo<NP, LG>;
+    __shared__ double s_c[kBlock], s_a[kBlock], s_red[kBlock];
+    __shared__ int s_flags[2];
+    __shared__ double sh[kWaves];
+
     const int j = blockIdx.y;
-    const int n = a.n, R = a.st.R;
+    const int n = a.n;
+    int iters_now;
+    control_step(a.st, j, n, a.tau, a.eps, a.max_iters, a.pass, a.prev_blocks, s_c, s_a, s_red,
+                 s_flags, &iters_now);
+
     const int64_t lo = a.st.off[j], hi = a.st.off[j + 1];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lg = lane / G::kLanes, sub = lane % G::kLanes;
 
-    const double *__restrict__ cj = a.st.coef + (int64_t)j * R;
-    const double *__restrict__ dj = a.st.delta + (int64_t)j * R;
-    double c[NP], dl[NP];
-    const float *rp[NP];
-    bool have[NP];
-#pragma unroll
-    for (int k = 0; k < NP; ++k) {
-        const int i = lg * NP + k;
-        have[k] = i < n;
-        c[k] = have[k] ? cj[i] : 0.0;
-        dl[k] = have[k] ? dj[i] : 0.0;
-        rp[k] = a.g + (int64_t)(have[k] ? i : 0) * a.ld;
-    }
-    const bool has_v0 = a.v0 != nullptr;
-    const double cb = cj[n], db = dj[n];
+    double c[NP], dl[NP], cb, db;
+    fetch_coefficients<NP, LG, RAGGED>(s_c, s_a, n, lg, c, dl, cb, db);
     double t2 = 0.0;
 
-    const int64_t xa = tile_origin(lo);
-    const int64_t units = (hi > lo) ? (hi - xa + G::kW - 1) / G::kW : 0;
-    const int64_t stride = (int64_t)gridDim.x * kWaves;
-    for (int64_t u = (int64_t)blockIdx.x * kWaves + wave; u < units; u += stride) {
-        const int64_t x0 = xa + u * G::kW + (int64_t)sub * kVec;
-        const bool full = (x0 >= lo) && (x0 + kVec <= hi);
-        double vv[4] = {0.0, 0.0, 0.0, 0.0}, ss[4] = {0.0, 0.0, 0.0, 0.0};
+    const TileRange tr = tile_range<G::kW>(lo, hi);
+    for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
+        const int64_t xu = tr.xa + u * G::kW;
+        const bool interior = (xu >= lo) && (xu + G::kW <= hi);
+        const int64_t x0 = xu + (int64_t)sub * kVec;
         float val[NP][4];
-#pragma unroll
-        for (int k = 0; k < NP; ++k) {
-            if (have[k]) load_row4(rp[k], x0, lo, hi, full, val[k]);
-            else { val[k][0] = val[k][1] = val[k][2] = val[k][3] = 0.0f; }
-        }
+        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
         float base[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (has_v0) load_row4(a.v0, x0, lo, hi, full, base);
-#pragma unroll
-        for (int k = 0; k < NP; ++k) {
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) {
-                const double gd = (double)val[k][e];
-                vv[e] = fma(c[k], gd, vv[e]);
-                ss[e] = fma(dl[k], gd, ss[e]);
-            }
+        if (HAS_BASE) {
+            if (interior) load_row4_vec(a.v0 + x0, base);
+            else load_row4_guarded(a.v0, x0, lo, hi, base);
         }
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) {
-            vv[e] = sum_across_groups<G::kLanes>(vv[e]);
-            ss[e] = sum_across_groups<G::kLanes>(ss[e]);
-            vv[e] = fma(cb, (double)base[e], vv[e]);
-            ss[e] = fma(db, (double)base[e], ss[e]);
-        }
+        double vv[4], ss[4];
+        combine_rows<NP, LG, HAS_BASE>(val, base, c, dl, cb, db, vv, ss);
         if (lg == 0) {
-            if (full) {
+            if (interior) {
                 f32x4_u o;
                 o.x = (float)vv[0]; o.y = (float)vv[1]; o.z = (float)vv[2]; o.w = (float)vv[3];
                 *reinterpret_cast<f32x4_u *>(a.v + x0) = o;
@@ -320,28 +374,37 @@ __global__ __launch_bounds__(kBlock) void cc_finish_kernel(CcFinishArgs a)
         }
     }
 
-    __shared__ double sh[kWaves];
-    {
-        const double s = sum_within_group<G::kLanes>(t2);
-        if (lane == 0) sh[wave] = s;
-    }
+    t2 = sum_within_group<G::kLanes>(t2);
+    if (lane == 0) sh[wave] = t2;
     __syncthreads();
-    const int B = gridDim.x;
-    double *__restrict__ pj = a.st.partial + (int64_t)j * B * R;
     if (threadIdx.x == 0) {
         double s = 0.0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) s += sh[w];
-        pj[blockIdx.x] = s;
+        // buffer (pass & 1) is free: what the earlier passes stored there has been consumed
+        a.st.partial[(a.pass & 1) * a.st.partial_stride + (int64_t)j * gridDim.x + blockIdx.x] = s;
     }
-    if (!last_block_of_partition(&a.st.counter[j], (unsigned)B)) return;
+}
+
+// iters and ||last applied update|| for the caller, one workgroup per partition
+struct CcReportArgs {
+    CcState st;
+    int32_t pass;            // as in cc_finish_kernel
+    int32_t blocks;          // workgroups per partition of cc_finish_kernel
+    int32_t *iters_out;
+    double *step_norm_out;   // may be null
+};
+
+__global__ __launch_bounds__(kBlock) void cc_report_kernel(CcReportArgs a)
+{
+    __shared__ double s_red[kBlock];
+    const int j = blockIdx.x;
+    const double *pj = a.st.partial + (a.pass & 1) * a.st.partial_stride + (int64_t)j * a.blocks;
+    const double tot = reduce_partials<kBlock>(pj, a.blocks, 1, 1, s_red);
     if (threadIdx.x == 0) {
-        double tot = 0.0;
-        for (int b = 0; b < B; ++b) tot += pj[b];
-        const int it = a.st.iters[j];
+        const int it = a.st.iters[(a.pass & 1) * a.st.P + j];
         a.iters_out[j] = it;
         if (a.step_norm_out) a.step_norm_out[j] = (it > 0) ? sqrt(tot) : 0.0;
-        a.st.counter[j] = 0u;
     }
 }
 

@@ -11,11 +11,17 @@ constexpr int kBlock = 256;          // threads per workgroup = 4 wavefronts of 
 constexpr int kWaves = kBlock / 64;
 constexpr int kVec = 4;              // coordinates per lane per tile: one 128-bit load per row
 
-// A 128-bit load that only promises dword alignment: rows of g start at
+// A 128-bit access that only promises dword alignment: rows of g start at
 // arbitrary multiples of 4 bytes (ldg and the partition offsets are not
 // multiples of 4 elements in general), and gfx950 serves dword-aligned
 // global_load_dwordx4 directly.
 typedef float f32x4_u __attribute__((ext_vector_type(4), aligned(4)));
+
+// Explicit global-address-space pointer types (the address space survives an empty
+// asm statement, which a generic pointer's inferred one does not).
+typedef const float __attribute__((address_space(1))) *global_f32;
+typedef const char __attribute__((address_space(1))) *global_bytes;
+typedef const f32x4_u __attribute__((address_space(1))) *global_f32x4;
 
 // Geometry of one wavefront tile.  A wavefront is cut into LG lane groups of
 // LANES = 64/LG lanes.  Lane group lg owns peers [lg*NP, lg*NP + NP); lane
@@ -38,20 +44,106 @@ struct Geo {
 // Philox block (floor(x/4)); coordinates outside [lo, hi) are masked.
 __device__ __forceinline__ int64_t tile_origin(int64_t lo) { return lo & ~int64_t(kVec - 1); }
 
-__device__ __forceinline__ void load_row4(const float *__restrict__ row, int64_t x0,
-                                          int64_t lo, int64_t hi, bool full, float (&out)[4])
+// Which tiles of partition [lo, hi) a wavefront visits.
+struct TileRange {
+    int64_t xa;        // coordinate of tile 0, lane 0
+    int64_t units;     // number of tiles
+    int64_t first;     // first tile of this wavefront
+    int64_t stride;    // distance to its next tile
+};
+
+template <int W>
+__device__ __forceinline__ TileRange tile_range(int64_t lo, int64_t hi)
 {
-    if (full) {
-        f32x4_u t = *reinterpret_cast<const f32x4_u *>(row + x0);
-        out[0] = t.x; out[1] = t.y; out[2] = t.z; out[3] = t.w;
-    } else {
+    TileRange t;
+    t.xa = tile_origin(lo);
+    t.units = (hi > lo) ? (hi - t.xa + W - 1) / W : 0;
+    t.first = (int64_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    t.stride = (int64_t)gridDim.x * kWaves;
+    return t;
+}
+
+// One row, 4 coordinates starting at x0, each guarded against [lo, hi).
+__device__ __forceinline__ void load_row4_guarded(const float *__restrict__ row, int64_t x0,
+                                                  int64_t lo, int64_t hi, float (&out)[4])
+{
 #pragma unroll
-        for (int e = 0; e < kVec; ++e) {
-            const int64_t x = x0 + e;
-            out[e] = (x >= lo && x < hi) ? row[x] : 0.0f;
+    for (int e = 0; e < kVec; ++e) {
+        const int64_t x = x0 + e;
+        out[e] = (x >= lo && x < hi) ? row[x] : 0.0f;
+    }
+}
+
+__device__ __forceinline__ void load_row4_vec(const float *__restrict__ p, float (&out)[4])
+{
+    const f32x4_u t = *reinterpret_cast<const f32x4_u *>(p);
+    out[0] = t.x; out[1] = t.y; out[2] = t.z; out[3] = t.w;
+}
+
+// Loads the 4 coordinates [x0, x0+4) of this lane group's NP peers.
+//   interior (wavefront-uniform): the whole tile lies inside [lo, hi): straight-line
+//   128-bit loads, all issued before anything waits on them.
+//   Rows beyond n (RAGGED only) re-read the last valid row; their coefficients are
+//   zero and their accumulators are ignored.
+template <int NP, int LG, bool RAGGED>
+__device__ __forceinline__ void load_tile(const float *__restrict__ g, int64_t ld, int n, int lg,
+                                          int sub, int64_t xu, int64_t lo, int64_t hi,
+                                          bool interior, float (&val)[NP][4])
+{
+    if (interior) {
+        // uniform 64-bit row base (SGPRs) + 32-bit per-lane byte offset: the saddr form
+        // of global_load_dwordx4, no per-row address registers
+        const uint32_t lane_bytes = (uint32_t)sub * (kVec * sizeof(float));
+        if constexpr (LG == 1) {
+            // The row base walks from peer to peer in scalar registers (row += ld); the
+            // empty asm pins it there, so no per-row address is kept in vector registers.
+            global_f32 row = (global_f32)(g + xu);
+#pragma unroll
+            for (int k = 0; k < NP; ++k) {
+                asm volatile("" : "+s"(row));
+                const f32x4_u t = *(global_f32x4)((global_bytes)row + lane_bytes);
+                val[k][0] = t.x; val[k][1] = t.y; val[k][2] = t.z; val[k][3] = t.w;
+                if (!RAGGED || k + 1 < n) row += ld;
+            }
+        } else {
+            // lane group lg starts at its own first peer; the walk from peer to peer is
+            // the same uniform stride
+            int i0 = lg * NP;
+            if (RAGGED) i0 = i0 < n ? i0 : n - 1;
+            global_bytes row = (global_bytes)(g + xu) + ((int64_t)i0 * ld * 4 + lane_bytes);
+#pragma unroll
+            for (int k = 0; k < NP; ++k) {
+                asm volatile("" : "+v"(row));
+                const f32x4_u t = *(global_f32x4)row;
+                val[k][0] = t.x; val[k][1] = t.y; val[k][2] = t.z; val[k][3] = t.w;
+                if (!RAGGED) row += ld * 4;
+                else row += (lg * NP + k + 1 < n) ? ld * 4 : 0;
+            }
+        }
+    } else {
+        // edge tile (first or last of a partition): every element guarded
+        const int64_t x0 = xu + (int64_t)sub * kVec;
+        int i0 = lg * NP;
+        if (RAGGED) i0 = i0 < n ? i0 : n - 1;
+        global_f32 row = (global_f32)g + (int64_t)i0 * ld;
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+            asm volatile("" : "+v"(row));
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) {
+                const int64_t x = x0 + e;
+                val[k][e] = (x >= lo && x < hi) ? row[x] : 0.0f;
+            }
+            if (!RAGGED) row += ld;
+            else row += (lg * NP + k + 1 < n) ? ld : 0;
         }
     }
 }
+
+// Makes the compiler forget what it knows about a register value (no instruction is
+// emitted).  Used between the two sweeps over a tile so that the fp32 values are
+// converted to fp64 again in the second sweep instead of keeping 2x the registers live.
+__device__ __forceinline__ void forget(float &x) { asm volatile("" : "+v"(x)); }
 
 // Sum over the lanes of one lane group (xor masks below LANES) ...
 template <int LANES>
@@ -60,6 +152,21 @@ __device__ __forceinline__ double sum_within_group(double a)
 #pragma unroll
     for (int m = 1; m < LANES; m <<= 1) a += __shfl_xor(a, m, 64);
     return a;
+}
+
+// The same for NP independent values at once, step by step, so that the NP shuffles of
+// one step are in flight together instead of NP dependent chains one after another.
+template <int LANES, int NP>
+__device__ __forceinline__ void sum_within_group_all(double (&a)[NP])
+{
+#pragma unroll
+    for (int m = 1; m < LANES; m <<= 1) {
+        double other[NP];
+#pragma unroll
+        for (int k = 0; k < NP; ++k) other[k] = __shfl_xor(a[k], m, 64);
+#pragma unroll
+        for (int k = 0; k < NP; ++k) a[k] += other[k];
+    }
 }
 
 // ... and over the lane groups of a wavefront (xor masks LANES .. 32).  Every
@@ -73,22 +180,31 @@ __device__ __forceinline__ double sum_across_groups(double a)
     return a;
 }
 
-// Device-wide "last workgroup of this partition" election.  Every workgroup
-// calls it after its partial results are stored; exactly one caller per round
-// gets true, after all the others' stores are visible to it.
-__device__ __forceinline__ bool last_block_of_partition(unsigned int *counter, unsigned int blocks)
+// Fixed-order sum of the B workgroups' partial results, pj[b * stride + q] over b, for
+// every quantity q < Q (Q <= NT), by all NT threads of the workgroup: the rows b are
+// dealt round-robin to `tpq` threads per quantity (independent loads, a few each), whose
+// sums are then added in order.  Thread q < Q returns the total of quantity q.  The order
+// depends only on (B, Q, NT): results are reproducible.  s_red has NT entries.
+template <int NT>
+__device__ __forceinline__ double reduce_partials(const double *__restrict__ pj, int B, int stride,
+                                                  int Q, double *s_red)
 {
-    __shared__ int s_last;
-    __threadfence();            // release this thread's partial results (agent scope)
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned int prev = atomicAdd(counter, 1u);
-        s_last = (prev == blocks - 1u);
+    int tpq = NT / Q;
+    if (tpq > 32) tpq = 32;
+    const int t = threadIdx.x;
+    const int s = t / Q, q = t - s * Q;
+    double acc = 0.0;
+    if (s < tpq) {
+#pragma unroll 4
+        for (int b = s; b < B; b += tpq) acc += pj[(int64_t)b * stride + q];
     }
     __syncthreads();
-    const bool last = s_last != 0;
-    if (last) __threadfence();  // acquire the other workgroups' partial results
-    return last;
+    s_red[t] = acc;
+    __syncthreads();
+    double tot = 0.0;
+    if (t < Q)
+        for (int k = 0; k < tpq; ++k) tot += s_red[k * Q + t];
+    return tot;
 }
 
 }  // namespace btard

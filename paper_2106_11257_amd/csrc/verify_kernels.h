@@ -75,51 +75,40 @@ struct VerifyArgs {
     int32_t S;
 };
 
-template <int NP, int LG>
+template <int NP, int LG, bool RAGGED>
 __global__ __launch_bounds__(kBlock) void verify_pass_kernel(VerifyArgs a)
 {
     using G = Geo<NP, LG>;
     const int j = blockIdx.y;
     const int n = a.n, S = a.S;
     const int64_t lo = a.off[j], hi = a.off[j + 1];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lg = lane / G::kLanes, sub = lane % G::kLanes;
 
-    const float *rp[NP];
-    bool have[NP];
-#pragma unroll
-    for (int k = 0; k < NP; ++k) {
-        const int i = lg * NP + k;
-        have[k] = i < n;
-        rp[k] = a.g + (int64_t)(have[k] ? i : 0) * a.ld;
-    }
     double accN[NP], accR[NP];
 #pragma unroll
     for (int k = 0; k < NP; ++k) { accN[k] = 0.0; accR[k] = 0.0; }
     double z2 = 0.0;
 
-    const int64_t xa = tile_origin(lo);
-    const int64_t units = (hi > lo) ? (hi - xa + G::kW - 1) / G::kW : 0;
-    const int64_t stride = (int64_t)gridDim.x * kWaves;
-    for (int64_t u = (int64_t)blockIdx.x * kWaves + wave; u < units; u += stride) {
-        const int64_t x0 = xa + u * G::kW + (int64_t)sub * kVec;
-        const bool full = (x0 >= lo) && (x0 + kVec <= hi);
+    const TileRange tr = tile_range<G::kW>(lo, hi);
+    for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
+        const int64_t xu = tr.xa + u * G::kW;
+        const bool interior = (xu >= lo) && (xu + G::kW <= hi);   // wavefront-uniform
+        const int64_t x0 = xu + (int64_t)sub * kVec;               // a multiple of 4
         float val[NP][4];
-#pragma unroll
-        for (int k = 0; k < NP; ++k) {
-            if (have[k]) load_row4(rp[k], x0, lo, hi, full, val[k]);
-            else { val[k][0] = val[k][1] = val[k][2] = val[k][3] = 0.0f; }
-        }
+        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
         float vf[4];
-        load_row4(a.v, x0, lo, hi, full, vf);
+        if (interior) load_row4_vec(a.v + x0, vf);
+        else load_row4_guarded(a.v, x0, lo, hi, vf);
 
         float zf[4];
-        zhat_block(a.seed, x0 >> 2, zf);            // x0 is a multiple of 4
+        zhat_block(a.seed, x0 >> 2, zf);
         double z[4], vv[4];
 #pragma unroll
         for (int e = 0; e < kVec; ++e) {
             const int64_t x = x0 + e;
-            z[e] = (x >= lo && x < hi) ? (double)zf[e] : 0.0;
+            z[e] = (interior || (x >= lo && x < hi)) ? (double)zf[e] : 0.0;
             vv[e] = (double)vf[e];
         }
 #pragma unroll
@@ -175,31 +164,34 @@ struct VerifyFinishArgs {
 
 // One workgroup per partition.  |zhat|^2 is summed over every partition's
 // partial sums in a fixed order (each workgroup repeats that small sum).
-__global__ __launch_bounds__(kBlock) void verify_finish_kernel(VerifyFinishArgs a)
+constexpr int kFinishThreads = 1024;
+
+__global__ __launch_bounds__(kFinishThreads) void verify_finish_kernel(VerifyFinishArgs a)
 {
     const int j = blockIdx.x;
     const int n = a.n, P = a.P, B = a.B, S = a.S;
     const int t = threadIdx.x;
-    __shared__ double s_red[kBlock];
-    __shared__ double s_proj[kBlock];
+    __shared__ double s_red[kFinishThreads];
+    __shared__ double s_proj[256];
     double zz = 0.0;
-    for (int64_t e = t; e < (int64_t)P * B; e += kBlock) zz += a.partial[e * S + 2 * n];
+    for (int64_t e = t; e < (int64_t)P * B; e += kFinishThreads) zz += a.partial[e * S + 2 * n];
     s_red[t] = zz;
     __syncthreads();
-    for (int h = kBlock / 2; h > 0; h >>= 1) {
+    for (int h = kFinishThreads / 2; h > 0; h >>= 1) {
         if (t < h) s_red[t] += s_red[t + h];
         __syncthreads();
     }
     const double Z = sqrt(s_red[0]);
 
+    // quantity q < n: norm^2 of peer q; n <= q < 2n: <zhat, r> of peer q - n
+    const double tot = reduce_partials<kFinishThreads>(a.partial + (int64_t)j * B * S, B, S, 2 * n,
+                                                       s_red);
+    __syncthreads();
+    if (t < 2 * n) s_red[t] = tot;
+    __syncthreads();
     if (t < n) {
-        double N2 = 0.0, Rr = 0.0;
-        const double *pj = a.partial + (int64_t)j * B * S;
-        for (int b = 0; b < B; ++b) {
-            N2 += pj[(int64_t)b * S + t];
-            Rr += pj[(int64_t)b * S + n + t];
-        }
-        const double N = sqrt(N2);
+        const double N = sqrt(s_red[t]);
+        const double Rr = s_red[n + t];
         const double w = (N <= a.tau) ? 1.0 : a.tau / N;
         const double s = (Z > 0.0) ? w * Rr / Z : 0.0;
         a.norms[(int64_t)t * P + j] = N;
@@ -238,11 +230,13 @@ __global__ __launch_bounds__(kBlock) void delta_kernel(DeltaArgs a)
         const int64_t x0 = xa + u * kVec;
         const bool full = (x0 >= lo) && (x0 + kVec <= hi);
         float vf[4];
-        load_row4(a.v, x0, lo, hi, full, vf);
+        if (full) load_row4_vec(a.v + x0, vf);
+        else load_row4_guarded(a.v, x0, lo, hi, vf);
         for (int i = 0; i < a.n; ++i) {
             const double w = a.weights[(int64_t)i * a.P + j];
             float gv[4];
-            load_row4(a.g + (int64_t)i * a.ld, x0, lo, hi, full, gv);
+            if (full) load_row4_vec(a.g + (int64_t)i * a.ld + x0, gv);
+            else load_row4_guarded(a.g + (int64_t)i * a.ld, x0, lo, hi, gv);
             float o[4];
 #pragma unroll
             for (int e = 0; e < kVec; ++e) o[e] = (float)(w * ((double)gv[e] - (double)vf[e]));

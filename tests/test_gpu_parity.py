@@ -216,9 +216,11 @@ def test_phased_api_matches_the_single_call(dev):
     ref = btard.centered_clip(G, off, 1.0, 1e-6, 9)
     p = btard.make_problem(G, off, 1.0, 1e-6, 9)
     btard.cc_begin(p)
+    done = 0
     for count in (1, 3, 0, 5, 4):          # more than max_iters in total: the extra passes are no-ops
-        btard.cc_iterate(p, count)
-    got = btard.cc_finish(p)
+        btard.cc_iterate(p, done, count)
+        done += count
+    got = btard.cc_finish(p, done)
     torch.cuda.synchronize()
     for x, y in zip(ref, got):
         assert torch.equal(x, y)
