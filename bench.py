@@ -26,6 +26,26 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E bandwidth
 
 
+def recorded_traffic(cfg: int):
+    """HBM bytes per launch of the CenteredClip pass as measured with rocprofv3 --pmc
+    (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); the summary of
+    those profiler runs is kept under profiles/.  None if no such run is recorded for
+    this configuration: a plain bench run cannot read hardware counters itself."""
+    import glob
+    import re
+    tag = re.compile(r"^traffic_bytes_per_launch cc_pass_kernel cfg%d:\s*([0-9.eE+]+)" % cfg)
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        try:
+            with open(path) as fh:
+                for line in fh:
+                    m = tag.match(line.strip())
+                    if m:
+                        return float(m.group(1))
+        except OSError:
+            pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -35,6 +55,9 @@ def main() -> int:
     ap.add_argument("--with-delta", action="store_true",
                     help="also materialise the clipped residuals (optional step S8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of known size (1 GiB read + 1 GiB written) "
+                         "so that HBM counters of a profiler run can be scaled")
     ap.add_argument("--cpu-sample-parts", type=int, default=0,
                     help="partitions the oracle is timed on (0 = pick for ~10-30 s)")
     args = ap.parse_args()
@@ -84,6 +107,14 @@ def main() -> int:
         if events is not None:
             events[4].record(stream)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -121,7 +152,7 @@ def main() -> int:
         "bound": "hbm", "kernel": "cc_pass_kernel",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4),
-        "traffic": None,
+        "traffic": recorded_traffic(args.config),
         "bytes_per_launch": pass_bytes_total / launches,
         "launches_per_step": launches,
         "avg_launch_us": round(t_iter_s / launches * 1e6, 2),
@@ -156,9 +187,14 @@ def main() -> int:
         lo, hi = off[0], off[k]
         sub = G[:, lo:hi].contiguous().cpu().numpy()
         sub_off = [o - lo for o in off[: k + 1]]
-        t0 = time.perf_counter()
-        _, ito, _, _ = oracle.centered_clip(sub, sub_off, wl.tau, wl.eps, wl.max_iters)
-        t_cpu = time.perf_counter() - t0
+        times = []
+        while True:                      # at least one run; repeat short ones (best of <= 5)
+            t0 = time.perf_counter()
+            _, ito, _, _ = oracle.centered_clip(sub, sub_off, wl.tau, wl.eps, wl.max_iters)
+            times.append(time.perf_counter() - t0)
+            if sum(times) > 10.0 or len(times) >= 5:
+                break
+        t_cpu = min(times)
         cpu_bytes = 4.0 * n * sum((sub_off[j + 1] - sub_off[j]) * max(int(ito[j]), 0)
                                   for j in range(k))
         out["cpu_baseline"] = {
@@ -166,7 +202,7 @@ def main() -> int:
             "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"CenteredClip on partitions 0..{k - 1} of {P} of the same workload "
                       f"({(hi - lo)} of {d} coordinates, all {n} peers, same tau/eps/max_iters), "
-                      f"{t_cpu:.2f} s",
+                      f"best of {len(times)} runs: {t_cpu:.2f} s",
         }
         assert [int(x) for x in ito] == it[:k], "oracle and GPU iteration counts differ"
         del np
