@@ -55,6 +55,11 @@ def main() -> int:
     ap.add_argument("--with-delta", action="store_true",
                     help="also materialise the clipped residuals (optional step S8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gram", action="store_true",
+                    help="time the step with BTARD_FLAG_GRAM (Gram-matrix iteration with "
+                         "streaming fallback) instead of one streaming pass per iteration")
+    ap.add_argument("--no-host-sync", action="store_true",
+                    help="with --gram: stay asynchronous and enqueue max_iters passes blindly")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of known size (1 GiB read + 1 GiB written) "
                          "so that HBM counters of a profiler run can be scaled")
@@ -87,19 +92,25 @@ def main() -> int:
     vout["colsum"] = torch.empty(P, dtype=torch.float64, device=dev)
     if args.with_delta:
         vout["delta"] = torch.empty((n, d), dtype=torch.float32, device=dev)
-    prob = btard.make_problem(G, off, wl.tau, wl.eps, wl.max_iters, workspace=ws)
+    flags = btard.BTARD_FLAG_GRAM if args.gram else btard.BTARD_FLAG_NONE
+    prob = btard.make_problem(G, off, wl.tau, wl.eps, wl.max_iters, workspace=ws, flags=flags)
     stream = torch.cuda.current_stream(dev)
 
     def step(events=None):
         if events is not None:
             events[0].record(stream)
         btard.cc_begin(prob)
+        passes = wl.max_iters
+        if args.gram:
+            btard.cc_gram(prob)
+            if not args.no_host_sync:
+                passes = btard.cc_remaining(prob)    # one stream synchronisation
         if events is not None:
             events[1].record(stream)
-        btard.cc_iterate(prob, 0, wl.max_iters)
+        btard.cc_iterate(prob, 0, passes)
         if events is not None:
             events[2].record(stream)
-        btard.cc_finish(prob, wl.max_iters, v, iters, step_norm)
+        btard.cc_finish(prob, passes, v, iters, step_norm)
         if events is not None:
             events[3].record(stream)
         btard.verify_projections(G, off, v, wl.tau, wl.seed_z, want_delta=args.with_delta,
@@ -167,7 +178,8 @@ def main() -> int:
                    "eps": wl.eps, "max_iters": wl.max_iters,
                    "iters_min": min(it), "iters_max": max(it),
                    "seed_inputs": wl.seed_inputs, "seed_z": wl.seed_z,
-                   "with_delta": bool(args.with_delta)},
+                   "with_delta": bool(args.with_delta),
+                   "mode": "gram + streaming fallback" if args.gram else "streaming"},
         "segments_ms": {"cc_begin": round(seg_ms[0], 4), "cc_iterate": round(seg_ms[1], 4),
                         "cc_finish": round(seg_ms[2], 4), "verify": round(seg_ms[3], 4)},
         "cc_only_GBps": round(cc_only, 1),

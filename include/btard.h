@@ -44,6 +44,16 @@ typedef enum btard_status {
 } btard_status;
 
 #define BTARD_FLAG_NONE 0u
+/* btard_centered_clip / btard_cc_*: run the iteration on the n x n Gram matrix of each
+ * partition (one pass over the data for all iterations) wherever that is accurate enough
+ * to reproduce the plain iteration, and fall back to one pass per iteration elsewhere.
+ * Takes effect for n <= 16 and v0 == NULL; ignored otherwise.  Same results contract. */
+#define BTARD_FLAG_GRAM 1u
+/* btard_centered_clip with BTARD_FLAG_GRAM: allow ONE synchronisation of the stream inside
+ * the call (after the Gram iteration), so that the per-iteration passes are only enqueued
+ * if some partition still needs them.  Without it the call stays asynchronous and enqueues
+ * max_iters passes that return at once for stopped partitions (about 2 us each). */
+#define BTARD_FLAG_HOST_SYNC 2u
 
 /* Human-readable name of a status code (static storage). */
 const char *btard_status_string(int status);
@@ -86,7 +96,7 @@ size_t btard_workspace_bytes(int32_t n, int32_t parts);
  *   last_step_norm      DEVICE [parts] fp64 or NULL, written: L2 norm of the
  *                       last applied update (0 if none was applied)
  *   workspace(_bytes)   DEVICE scratch of >= btard_workspace_bytes(n, parts)
- *   flags               BTARD_FLAG_NONE
+ *   flags               BTARD_FLAG_NONE, or BTARD_FLAG_GRAM [| BTARD_FLAG_HOST_SYNC]
  *
  * Arithmetic: fp32 inputs are widened to fp64; the iterate is carried as fp64
  * coefficients of the rows (v^l = c_0 v0 + sum_i c_i g_i), every reduction is
@@ -105,6 +115,14 @@ int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
  *
  *   btard_cc_begin    validates, uploads the offsets, sets v^0 (the state lives
  *                     in the workspace)
+ *   btard_cc_gram     (optional, right after begin; does something only with
+ *                     BTARD_FLAG_GRAM) one pass that forms each partition's Gram
+ *                     matrix and runs the iteration on it as far as its accuracy
+ *                     is guaranteed; partitions it could not finish are left
+ *                     in the state at which btard_cc_iterate must take over
+ *   btard_cc_remaining (optional) synchronises the stream and returns an upper
+ *                     bound on the iterations the partitions that have not
+ *                     stopped still need (0: btard_cc_iterate can be skipped)
  *   btard_cc_iterate  enqueues iterations first_iteration .. first_iteration +
  *                     count - 1 of eq. (CenteredClip) (one pass over the n x d
  *                     matrix each) on every partition that has not stopped;
@@ -115,8 +133,8 @@ int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
  *                     the last update and writes v, iters and last_step_norm
  *                     (one more pass)
  *
- * btard_centered_clip == begin; iterate(0, max_iters); finish(max_iters).  The
- * problem description must be identical in all calls of one run.
+ * btard_centered_clip == begin; gram; iterate(0, max_iters); finish(max_iters).
+ * The problem description must be identical in all calls of one run.
  */
 typedef struct btard_cc_problem {
     const float *g;              /* DEVICE */
@@ -136,6 +154,8 @@ typedef struct btard_cc_problem {
 } btard_cc_problem;
 
 int btard_cc_begin(const btard_cc_problem *p);
+int btard_cc_gram(const btard_cc_problem *p);
+int btard_cc_remaining(const btard_cc_problem *p, int32_t *remaining_host);
 int btard_cc_iterate(const btard_cc_problem *p, int32_t first_iteration, int32_t count);
 int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int32_t *iters,
                     double *last_step_norm);
@@ -184,6 +204,13 @@ int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
  */
 int btard_debug_zhat(uint64_t seed, int64_t x_begin, int64_t count, float *out,
                      void *stream);
+
+/*
+ * Test hook for the Gram formulation: writes the n x n Gram matrix G G^T of every
+ * partition (fp64, zero-padded to 16 x 16, row-major, parts * 256 entries) to DEVICE
+ * gram_out.  Needs n <= 16.  Uses the workspace of `p`.
+ */
+int btard_debug_gram(const btard_cc_problem *p, double *gram_out);
 
 #ifdef __cplusplus
 }

@@ -7,7 +7,16 @@ from .binding import (  # noqa: F401
     BtardError,
     alloc_workspace,
     btard_cc_begin,
+    BTARD_FLAG_GRAM,
+    BTARD_FLAG_HOST_SYNC,
+    btard_cc_remaining,
+    cc_remaining,
+    BTARD_FLAG_NONE,
     btard_cc_finish,
+    btard_cc_gram,
+    btard_debug_gram,
+    cc_gram,
+    debug_gram,
     btard_cc_iterate,
     btard_centered_clip,
     btard_debug_zhat,

@@ -19,6 +19,8 @@ _lib = None
 
 BTARD_OK = 0
 BTARD_FLAG_NONE = 0
+BTARD_FLAG_GRAM = 1
+BTARD_FLAG_HOST_SYNC = 2
 
 
 class BtardError(RuntimeError):
@@ -70,6 +72,12 @@ def load_library():
     lib.btard_centered_clip.restype = c.c_int
     lib.btard_cc_begin.argtypes = [c.POINTER(_Problem)]
     lib.btard_cc_begin.restype = c.c_int
+    lib.btard_cc_gram.argtypes = [c.POINTER(_Problem)]
+    lib.btard_cc_gram.restype = c.c_int
+    lib.btard_cc_remaining.argtypes = [c.POINTER(_Problem), c.POINTER(c.c_int32)]
+    lib.btard_cc_remaining.restype = c.c_int
+    lib.btard_debug_gram.argtypes = [c.POINTER(_Problem), c.c_void_p]
+    lib.btard_debug_gram.restype = c.c_int
     lib.btard_cc_iterate.argtypes = [c.POINTER(_Problem), c.c_int32, c.c_int32]
     lib.btard_cc_iterate.restype = c.c_int
     lib.btard_cc_finish.argtypes = [c.POINTER(_Problem), c.c_int32, c.c_void_p, c.c_void_p,
@@ -131,7 +139,7 @@ def centered_clip(g: torch.Tensor, offsets: Sequence[int], tau: float, eps: floa
                   max_iters: int, v0: Optional[torch.Tensor] = None,
                   v: Optional[torch.Tensor] = None, iters: Optional[torch.Tensor] = None,
                   last_step_norm: Optional[torch.Tensor] = None,
-                  workspace: Optional[torch.Tensor] = None):
+                  workspace: Optional[torch.Tensor] = None, flags: int = BTARD_FLAG_NONE):
     """btard_centered_clip.  Returns (v fp32 [d], iters int32 [P], last_step_norm fp64 [P]).
 
     Work is enqueued on torch's current stream; the outputs are valid after it
@@ -151,7 +159,7 @@ def centered_clip(g: torch.Tensor, offsets: Sequence[int], tau: float, eps: floa
     rc = load_library().btard_centered_clip(
         _ptr(g), _row_stride(g), n, d, _off_array(offsets), P, float(tau), float(eps),
         int(max_iters), _ptr(v0), _ptr(v), _ptr(iters), _ptr(last_step_norm),
-        _ptr(workspace), workspace.numel(), _stream_ptr(dev), BTARD_FLAG_NONE)
+        _ptr(workspace), workspace.numel(), _stream_ptr(dev), int(flags))
     _check(rc, "btard_centered_clip")
     return v, iters, last_step_norm
 
@@ -159,26 +167,44 @@ def centered_clip(g: torch.Tensor, offsets: Sequence[int], tau: float, eps: floa
 class Problem:
     """Keeps the ctypes problem description (and what it points to) alive."""
 
-    def __init__(self, g, offsets, tau, eps, max_iters, v0, workspace):
+    def __init__(self, g, offsets, tau, eps, max_iters, v0, workspace, flags=BTARD_FLAG_NONE):
         self.g, self.v0, self.workspace = g, v0, workspace
         self.offsets = _off_array(offsets)
         self.parts = len(offsets) - 1
         self.c = _Problem(
             _ptr(g), _row_stride(g), int(g.shape[0]), int(g.shape[1]), self.offsets,
             self.parts, float(tau), float(eps), int(max_iters), _ptr(v0), _ptr(workspace),
-            workspace.numel(), _stream_ptr(g.device), BTARD_FLAG_NONE)
+            workspace.numel(), _stream_ptr(g.device), int(flags))
 
 
 def make_problem(g: torch.Tensor, offsets: Sequence[int], tau: float, eps: float,
                  max_iters: int, v0: Optional[torch.Tensor] = None,
-                 workspace: Optional[torch.Tensor] = None) -> Problem:
+                 workspace: Optional[torch.Tensor] = None, flags: int = BTARD_FLAG_NONE) -> Problem:
     if workspace is None:
         workspace = alloc_workspace(int(g.shape[0]), len(offsets) - 1, g.device)
-    return Problem(g, offsets, tau, eps, max_iters, v0, workspace)
+    return Problem(g, offsets, tau, eps, max_iters, v0, workspace, flags)
 
 
 def cc_begin(p: Problem) -> None:
     _check(load_library().btard_cc_begin(ctypes.byref(p.c)), "btard_cc_begin")
+
+
+def cc_gram(p: Problem) -> None:
+    _check(load_library().btard_cc_gram(ctypes.byref(p.c)), "btard_cc_gram")
+
+
+def cc_remaining(p: Problem) -> int:
+    """Synchronises the stream; upper bound on the iterations still needed."""
+    out = ctypes.c_int32(0)
+    _check(load_library().btard_cc_remaining(ctypes.byref(p.c), ctypes.byref(out)),
+           "btard_cc_remaining")
+    return int(out.value)
+
+
+def debug_gram(p: Problem) -> torch.Tensor:
+    out = torch.empty((p.parts, 16, 16), dtype=torch.float64, device=p.g.device)
+    _check(load_library().btard_debug_gram(ctypes.byref(p.c), _ptr(out)), "btard_debug_gram")
+    return out
 
 
 def cc_iterate(p: Problem, first_iteration: int, count: int) -> None:
@@ -245,6 +271,9 @@ btard_split_offsets = split_offsets
 btard_workspace_bytes = workspace_bytes
 btard_centered_clip = centered_clip
 btard_cc_begin = cc_begin
+btard_cc_gram = cc_gram
+btard_cc_remaining = cc_remaining
+btard_debug_gram = debug_gram
 btard_cc_iterate = cc_iterate
 btard_cc_finish = cc_finish
 btard_verify_projections = verify_projections

@@ -8,8 +8,10 @@
 #include <cmath>
 #include <cstdint>
 #include <mutex>
+#include <vector>
 
 #include "cc_kernels.h"
+#include "gram_kernels.h"
 #include "verify_kernels.h"
 
 namespace btard {
@@ -23,7 +25,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-    size_t off, coef, delta, iters, done, partial, partial_stride_doubles, total;
+    size_t off, coef, delta, iters, done, aux, partial, partial_stride_doubles, gram, total;
 };
 
 // State and partial sums exist twice (double-buffered by pass parity).
@@ -36,10 +38,12 @@ WsLayout ws_layout(int32_t n, int32_t P)
     L.coef = p;     p = align_up(p + 2 * sizeof(double) * P * R);
     L.delta = p;    p = align_up(p + 2 * sizeof(double) * P * R);
     L.iters = p;    p = align_up(p + 2 * sizeof(int32_t) * P);
-    L.done = p;     p = align_up(p + 2 * sizeof(int32_t) * P);
+    L.done = p;     p = align_up(p + 2 * sizeof(int32_t) * P);      // done | final_buf
+    L.aux = p;      p = align_up(p + 2 * sizeof(int32_t) * P);      // report_buf | remaining
     const size_t blocks = (size_t)(P > kMaxBlocks ? P : kMaxBlocks);
     L.partial_stride_doubles = align_up(sizeof(double) * blocks * S) / sizeof(double);
     L.partial = p;  p = align_up(p + 2 * sizeof(double) * L.partial_stride_doubles);
+    L.gram = p;     p = align_up(p + sizeof(double) * blocks * kGramEntries);   // partial Gram matrices
     L.total = p;
     return L;
 }
@@ -74,6 +78,9 @@ CcState carve_cc(void *ws, int32_t n, int32_t P)
     st.partial = reinterpret_cast<double *>(b + L.partial);
     st.iters = reinterpret_cast<int32_t *>(b + L.iters);
     st.done = reinterpret_cast<int32_t *>(b + L.done);
+    st.final_buf = st.done + P;
+    st.report_buf = reinterpret_cast<int32_t *>(b + L.aux);
+    st.remaining = st.report_buf + P;
     st.partial_stride = (int64_t)L.partial_stride_doubles;
     st.R = n + 1;
     st.P = P;
@@ -140,7 +147,7 @@ int variant_peers(Variant v)
 // (compute units x occupancy), cached per (device, kernel).
 struct ResidentCache {
     std::mutex mu;
-    int value[16][3][kVariants][4] = {};
+    int value[16][4][kVariants][4] = {};
 };
 ResidentCache g_resident;
 
@@ -163,13 +170,15 @@ int resident_blocks(int kind, Variant v, int sub, const void *fn)
     return slot;
 }
 
-// Workgroups per partition: fill the device once (all partitions run side by
-// side), but never more than the partial-sum area holds or the work needs.
+// Workgroups per partition: fill the device once (all partitions run side by side; the
+// pass gains bandwidth up to full occupancy), but never more than the partial-sum area
+// holds or the work needs.
 int blocks_per_partition(int resident, int32_t P, const int64_t *off, int tile_w)
 {
     int64_t max_units = 1;
     for (int32_t j = 0; j < P; ++j) {
-        const int64_t units = (off[j + 1] - off[j] + tile_w + 2) / tile_w + 1;
+        const int64_t lo = off[j], hi = off[j + 1];
+        const int64_t units = hi > lo ? (hi - (lo & ~int64_t(kVec - 1)) + tile_w - 1) / tile_w : 0;
         if (units > max_units) max_units = units;
     }
     int64_t B = resident / P;
@@ -208,7 +217,8 @@ int check_problem(const btard_cc_problem *p)
     if (!basic_args_ok(p->g, p->ldg, p->n, p->d, p->offsets_host, p->parts))
         return BTARD_ERR_INVALID_ARG;
     if (!(p->tau > 0.0f) || !(p->eps >= 0.0f) || p->max_iters < 0) return BTARD_ERR_INVALID_ARG;
-    if (p->flags != BTARD_FLAG_NONE) return BTARD_ERR_INVALID_ARG;
+    if ((p->flags & ~(uint32_t)(BTARD_FLAG_GRAM | BTARD_FLAG_HOST_SYNC)) != 0)
+        return BTARD_ERR_INVALID_ARG;
     return check_workspace(p->workspace, p->workspace_bytes, p->n, p->parts);
 }
 
@@ -259,6 +269,82 @@ int btard_cc_begin(const btard_cc_problem *p)
     if (up != BTARD_OK) return up;
     hipLaunchKernelGGL(cc_init_kernel, dim3(p->parts), dim3(64), 0, s, st, p->n, p->v0 ? 1 : 0,
                        p->max_iters);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+// The Gram formulation is built for one 16 x 16 MFMA block and a start at the mean.
+static bool gram_applies(const btard_cc_problem *p)
+{
+    return (p->flags & BTARD_FLAG_GRAM) != 0 && p->n <= kGramPeers && p->v0 == nullptr &&
+           p->max_iters > 0;
+}
+
+static int gram_blocks(const btard_cc_problem *p)
+{
+    const int resident = resident_blocks(3, V16x1, 0, reinterpret_cast<const void *>(gram_pass_kernel));
+    if (resident <= 0) return 0;
+    return blocks_per_partition(resident, p->parts, p->offsets_host, 256);
+}
+
+int btard_cc_gram(const btard_cc_problem *p)
+{
+    const int rc = check_problem(p);
+    if (rc != BTARD_OK) return rc;
+    if (!gram_applies(p)) return BTARD_OK;               // nothing to do: streaming passes only
+    hipStream_t s = static_cast<hipStream_t>(p->stream);
+    const int B = gram_blocks(p);
+    if (B <= 0) return BTARD_ERR_DEVICE;
+    const WsLayout L = ws_layout(p->n, p->parts);
+    GramArgs ga;
+    ga.g = p->g; ga.ld = p->ldg; ga.n = p->n;
+    ga.gpart = reinterpret_cast<double *>(static_cast<char *>(p->workspace) + L.gram);
+    GramIterArgs gi;
+    gi.st = carve_cc(p->workspace, p->n, p->parts);
+    ga.off = gi.st.off;
+    gi.gpart = ga.gpart; gi.blocks = B; gi.n = p->n;
+    gi.tau = (double)p->tau; gi.eps = (double)p->eps; gi.max_iters = p->max_iters;
+    hipLaunchKernelGGL(gram_pass_kernel, dim3(B, p->parts), dim3(kBlock), 0, s, ga);
+    hipLaunchKernelGGL(gram_iterate_kernel, dim3(p->parts), dim3(kBlock), 0, s, gi);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+int btard_cc_remaining(const btard_cc_problem *p, int32_t *remaining_host)
+{
+    const int rc = check_problem(p);
+    if (rc != BTARD_OK) return rc;
+    if (!remaining_host) return BTARD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(p->stream);
+    const CcState st = carve_cc(p->workspace, p->n, p->parts);
+    std::vector<int32_t> host((size_t)p->parts);
+    if (hipMemcpyAsync(host.data(), st.remaining, sizeof(int32_t) * (size_t)p->parts,
+                       hipMemcpyDeviceToHost, s) != hipSuccess)
+        return BTARD_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return BTARD_ERR_DEVICE;
+    int32_t most = 0;
+    for (int32_t r : host)
+        if (r > most) most = r;
+    *remaining_host = most;
+    return BTARD_OK;
+}
+
+int btard_debug_gram(const btard_cc_problem *p, double *gram_out)
+{
+    const int rc = check_problem(p);
+    if (rc != BTARD_OK) return rc;
+    if (!gram_out || p->n > kGramPeers) return BTARD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(p->stream);
+    const int B = gram_blocks(p);
+    if (B <= 0) return BTARD_ERR_DEVICE;
+    const WsLayout L = ws_layout(p->n, p->parts);
+    CcState st = carve_cc(p->workspace, p->n, p->parts);
+    const int up = upload_offsets(p->offsets_host, p->parts, st.off, s);
+    if (up != BTARD_OK) return up;
+    GramArgs ga;
+    ga.g = p->g; ga.ld = p->ldg; ga.n = p->n; ga.off = st.off;
+    ga.gpart = reinterpret_cast<double *>(static_cast<char *>(p->workspace) + L.gram);
+    hipLaunchKernelGGL(gram_pass_kernel, dim3(B, p->parts), dim3(kBlock), 0, s, ga);
+    hipLaunchKernelGGL(gram_debug_kernel, dim3(p->parts), dim3(kGramEntries), 0, s, ga.gpart, B,
+                       gram_out);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
@@ -340,9 +426,18 @@ int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
     if (!v || !iters || overlaps(v, v0, d)) return BTARD_ERR_INVALID_ARG;
     rc = btard_cc_begin(&p);
     if (rc != BTARD_OK) return rc;
-    rc = btard_cc_iterate(&p, 0, max_iters);
+    rc = btard_cc_gram(&p);
     if (rc != BTARD_OK) return rc;
-    return btard_cc_finish(&p, max_iters, v, iters, last_step_norm);
+    int32_t passes = max_iters;
+    if ((flags & BTARD_FLAG_HOST_SYNC) != 0 && gram_applies(&p)) {
+        // one look at what the Gram iteration left undone saves the launches of passes
+        // that would find every partition stopped
+        rc = btard_cc_remaining(&p, &passes);
+        if (rc != BTARD_OK) return rc;
+    }
+    rc = btard_cc_iterate(&p, 0, passes);
+    if (rc != BTARD_OK) return rc;
+    return btard_cc_finish(&p, passes, v, iters, last_step_norm);
 }
 
 int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,

@@ -34,7 +34,11 @@ struct CcState {
     double *delta;           // [2][P][R]  a_i of the last applied update
     double *partial;         // [2][P*B*R] per-workgroup partial sums (n norms^2, step^2)
     int32_t *iters;          // [2][P] updates applied so far (-1: non-finite norm)
-    int32_t *done;           // [2][P] partition stopped
+    int32_t *done;           // [P] partition stopped (set once, by workgroup 0 of the pass
+                             //     that decides; later kernels skip the partition)
+    int32_t *final_buf;      // [P] state buffer that holds a stopped partition's final state
+    int32_t *report_buf;     // [P] state buffer the finish kernel left the reported state in
+    int32_t *remaining;      // [P] iterations still to run after the Gram iteration
     int64_t partial_stride;  // doubles between the two partial-sum buffers
     int32_t R;               // n + 1
     int32_t P;
@@ -80,6 +84,9 @@ __global__ void cc_init_kernel(CcState st, int32_t n, int32_t has_v0, int32_t ma
     if (threadIdx.x == 0) {
         st.iters[j] = 0;
         st.done[j] = (max_iters <= 0) ? 1 : 0;
+        st.final_buf[j] = 0;
+        st.report_buf[j] = 0;
+        st.remaining[j] = max_iters > 0 ? max_iters : 0;
     }
 }
 
@@ -87,25 +94,29 @@ __global__ void cc_init_kernel(CcState st, int32_t n, int32_t has_v0, int32_t ma
 // control step: weights, update in coefficients, stopping rule
 // ---------------------------------------------------------------------------
 // Brings partition j's state from "after pass-1" to "ready for pass `pass`": every thread
-// of the workgroup takes part.  On return s_c / s_a hold c^pass / a^pass (R entries), and
-// the function value is true if the partition has stopped.  Workgroup 0 of the partition
-// also records the new state in buffer (pass & 1).
+// of the workgroup takes part.  The partition must have been running when pass-1 ended (the
+// callers skip stopped partitions before they get here).  On return s_c / s_a hold
+// c^pass / a^pass (R entries), *iters_out the updates applied, and the function value is
+// true if the partition stops now.  Workgroup 0 of the partition records the new state in
+// buffer (pass & 1) and, with mark_done, publishes a stop in done / final_buf.  Other
+// workgroups may see that flag while they are still starting the same pass; all they do
+// with it is leave, which is what they would decide themselves.
 __device__ __forceinline__ bool control_step(const CcState &st, int j, int n, double tau,
                                              double eps, int max_iters, int pass, int prev_blocks,
-                                             double *s_c, double *s_a, double *s_red,
-                                             int *s_flags, int *iters_out)
+                                             bool mark_done, double *s_c, double *s_a,
+                                             double *s_red, int *s_flags, int *iters_out)
 {
     const int R = st.R, P = st.P;
     const int t = threadIdx.x;
     if (pass == 0) {
-        // state buffer 0 as set by cc_init_kernel; nothing to advance
+        // state buffer 0 as set by cc_init_kernel (or left by the Gram iteration)
         if (t < R) {
             s_c[t] = st.coef[(int64_t)j * R + t];
             s_a[t] = st.delta[(int64_t)j * R + t];
         }
         __syncthreads();
         *iters_out = st.iters[j];
-        return st.done[j] != 0;
+        return false;
     }
     const int prev = (pass - 1) & 1, cur = pass & 1;
     const double *cp = st.coef + ((int64_t)prev * P + j) * R;
@@ -113,38 +124,36 @@ __device__ __forceinline__ bool control_step(const CcState &st, int j, int n, do
     double cq = 0.0, aq = 0.0;
     if (t < R) { cq = cp[t]; aq = ap[t]; }
     int it = st.iters[prev * P + j];
-    int dn = st.done[prev * P + j];
+    int dn = 0;
 
-    if (!dn) {                                               // uniform over the workgroup
-        const double *pj = st.partial + prev * st.partial_stride + (int64_t)j * prev_blocks * R;
-        const double tot = reduce_partials<kBlock>(pj, prev_blocks, R, R, s_red);
-        if (t == 0) { s_flags[0] = 0; s_flags[1] = 0; }
-        __syncthreads();
-        // quantity n is ||v^it - v^{it-1}||^2: did update number `it` already converge?
-        if (t == n && it >= 1 && sqrt(tot) < eps) s_flags[0] = 1;
-        double w = 0.0;
-        if (t < n) {
-            const double N = sqrt(tot);
-            if (!isfinite(N)) s_flags[1] = 1;
-            w = (N <= tau) ? 1.0 : tau / N;
+    const double *pj = st.partial + prev * st.partial_stride + (int64_t)j * prev_blocks * R;
+    const double tot = reduce_partials<kBlock>(pj, prev_blocks, R, R, s_red);
+    if (t == 0) { s_flags[0] = 0; s_flags[1] = 0; }
+    __syncthreads();
+    // quantity n is ||v^it - v^{it-1}||^2: did update number `it` already converge?
+    if (t == n && it >= 1 && sqrt(tot) < eps) s_flags[0] = 1;
+    double w = 0.0;
+    if (t < n) {
+        const double N = sqrt(tot);
+        if (!isfinite(N)) s_flags[1] = 1;
+        w = (N <= tau) ? 1.0 : tau / N;
+    }
+    __syncthreads();
+    s_red[t] = w;
+    __syncthreads();
+    if (s_flags[0]) {
+        dn = 1;                                              // v^it is final; c, a unchanged
+    } else if (s_flags[1]) {
+        dn = 1; it = -1;
+    } else {
+        double W = 0.0;
+        for (int i = 0; i < n; ++i) W += s_red[i];
+        if (t < R) {
+            aq = ((t < n ? w : 0.0) - W * cq) / (double)n;
+            cq = cq + aq;
         }
-        __syncthreads();
-        s_red[t] = w;
-        __syncthreads();
-        if (s_flags[0]) {
-            dn = 1;                                          // v^it is final; c, a unchanged
-        } else if (s_flags[1]) {
-            dn = 1; it = -1;
-        } else {
-            double W = 0.0;
-            for (int i = 0; i < n; ++i) W += s_red[i];
-            if (t < R) {
-                aq = ((t < n ? w : 0.0) - W * cq) / (double)n;
-                cq = cq + aq;
-            }
-            it = it + 1;
-            if (it >= max_iters) dn = 1;
-        }
+        it = it + 1;
+        if (it >= max_iters) dn = 1;
     }
     if (t < R) { s_c[t] = cq; s_a[t] = aq; }
     if (blockIdx.x == 0) {
@@ -152,7 +161,10 @@ __device__ __forceinline__ bool control_step(const CcState &st, int j, int n, do
             st.coef[((int64_t)cur * P + j) * R + t] = cq;
             st.delta[((int64_t)cur * P + j) * R + t] = aq;
         }
-        if (t == 0) { st.iters[cur * P + j] = it; st.done[cur * P + j] = dn; }
+        if (t == 0) {
+            st.iters[cur * P + j] = it;
+            if (dn && mark_done) { st.final_buf[j] = cur; st.done[j] = 1; }
+        }
     }
     __syncthreads();
     *iters_out = it;
@@ -232,16 +244,36 @@ __global__ __launch_bounds__(kBlock) void cc_pass_kernel(CcArgs a)
     __shared__ double sh[kWaves][G::kPeers + 1];
 
     const int j = blockIdx.y;
-    const int n = a.n, R = a.st.R;
-    int iters_now;
-    if (control_step(a.st, j, n, a.tau, a.eps, a.max_iters, a.pass, a.prev_blocks, s_c, s_a, s_red,
-                     s_flags, &iters_now))
-        return;                                     // uniform: this partition has stopped
-
+    const int stopped = a.st.done[j];               // the three loads travel together
     const int64_t lo = a.st.off[j], hi = a.st.off[j + 1];
+    if (stopped) return;                            // stopped in an earlier kernel (uniform)
+    const int n = a.n, R = a.st.R;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lg = lane / G::kLanes, sub = lane % G::kLanes;
+    const TileRange tr = tile_range<G::kW>(lo, hi);
+
+    // The first tile's loads do not depend on the coefficients: they are issued before the
+    // control step and travel while it runs.
+    float val[NP][4];
+    float base[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    bool loaded = false;
+    if (tr.first < tr.units) {
+        const int64_t xu = tr.xa + tr.first * G::kW;
+        const bool interior = (xu >= lo) && (xu + G::kW <= hi);
+        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
+        if (HAS_BASE) {
+            const int64_t x0 = xu + (int64_t)sub * kVec;
+            if (interior) load_row4_vec(a.v0 + x0, base);
+            else load_row4_guarded(a.v0, x0, lo, hi, base);
+        }
+        loaded = true;
+    }
+
+    int iters_now;
+    if (control_step(a.st, j, n, a.tau, a.eps, a.max_iters, a.pass, a.prev_blocks, true, s_c, s_a,
+                     s_red, s_flags, &iters_now))
+        return;                                     // uniform: this partition stops now
 
     double c[NP], dl[NP], cb, db;
     fetch_coefficients<NP, LG, RAGGED>(s_c, s_a, n, lg, c, dl, cb, db);
@@ -251,18 +283,18 @@ __global__ __launch_bounds__(kBlock) void cc_pass_kernel(CcArgs a)
     for (int k = 0; k < NP; ++k) acc[k] = 0.0;
     double t2 = 0.0;
 
-    const TileRange tr = tile_range<G::kW>(lo, hi);
     for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
-        const int64_t xu = tr.xa + u * G::kW;
-        const bool interior = (xu >= lo) && (xu + G::kW <= hi);   // wavefront-uniform
-        float val[NP][4];
-        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
-        float base[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (HAS_BASE) {
-            const int64_t x0 = xu + (int64_t)sub * kVec;
-            if (interior) load_row4_vec(a.v0 + x0, base);
-            else load_row4_guarded(a.v0, x0, lo, hi, base);
+        if (!loaded) {
+            const int64_t xu = tr.xa + u * G::kW;
+            const bool interior = (xu >= lo) && (xu + G::kW <= hi);   // wavefront-uniform
+            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
+            if (HAS_BASE) {
+                const int64_t x0 = xu + (int64_t)sub * kVec;
+                if (interior) load_row4_vec(a.v0 + x0, base);
+                else load_row4_guarded(a.v0, x0, lo, hi, base);
+            }
         }
+        loaded = false;
         double vv[4], ss[4];
         combine_rows<NP, LG, HAS_BASE>(val, base, c, dl, cb, db, vv, ss);
         // residual norms ||g_i - v^l||^2 (masked coordinates hold zeros in every row)
@@ -331,8 +363,22 @@ __global__ __launch_bounds__(kBlock) void cc_finish_kernel(CcFinishArgs a)
     const int j = blockIdx.y;
     const int n = a.n;
     int iters_now;
-    control_step(a.st, j, n, a.tau, a.eps, a.max_iters, a.pass, a.prev_blocks, s_c, s_a, s_red,
-                 s_flags, &iters_now);
+    if (a.st.done[j]) {
+        // stopped earlier: its final state is where the deciding kernel left it
+        const int buf = a.st.final_buf[j];
+        if ((int)threadIdx.x < a.st.R) {
+            s_c[threadIdx.x] = a.st.coef[((int64_t)buf * a.st.P + j) * a.st.R + threadIdx.x];
+            s_a[threadIdx.x] = a.st.delta[((int64_t)buf * a.st.P + j) * a.st.R + threadIdx.x];
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0) a.st.report_buf[j] = buf;
+        __syncthreads();
+    } else {
+        // still running: apply the update the last pass prepared (this kernel does not
+        // publish a stop: nothing runs after it that would need to skip the partition)
+        control_step(a.st, j, n, a.tau, a.eps, a.max_iters, a.pass, a.prev_blocks, false, s_c, s_a,
+                     s_red, s_flags, &iters_now);
+        if (blockIdx.x == 0 && threadIdx.x == 0) a.st.report_buf[j] = a.pass & 1;
+    }
 
     const int64_t lo = a.st.off[j], hi = a.st.off[j + 1];
     const int lane = threadIdx.x & 63;
@@ -402,7 +448,7 @@ __global__ __launch_bounds__(kBlock) void cc_report_kernel(CcReportArgs a)
     const double *pj = a.st.partial + (a.pass & 1) * a.st.partial_stride + (int64_t)j * a.blocks;
     const double tot = reduce_partials<kBlock>(pj, a.blocks, 1, 1, s_red);
     if (threadIdx.x == 0) {
-        const int it = a.st.iters[(a.pass & 1) * a.st.P + j];
+        const int it = a.st.iters[a.st.report_buf[j] * a.st.P + j];
         a.iters_out[j] = it;
         if (a.step_norm_out) a.step_norm_out[j] = (it > 0) ? sqrt(tot) : 0.0;
     }

@@ -23,6 +23,21 @@ typedef const float __attribute__((address_space(1))) *global_f32;
 typedef const char __attribute__((address_space(1))) *global_bytes;
 typedef const f32x4_u __attribute__((address_space(1))) *global_f32x4;
 
+// The slab is read once per pass and is far larger than the caches: its loads are marked
+// non-temporal so that they do not displace other data (measured: +10 % bandwidth on the
+// 84 GB slab, +6 % on the 0.7 GB one).  BTARD_NT_LOADS=0 turns that off for experiments.
+#ifndef BTARD_NT_LOADS
+#define BTARD_NT_LOADS 1
+#endif
+__device__ __forceinline__ f32x4_u stream_load(global_f32x4 p)
+{
+#if BTARD_NT_LOADS
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+
 // Geometry of one wavefront tile.  A wavefront is cut into LG lane groups of
 // LANES = 64/LG lanes.  Lane group lg owns peers [lg*NP, lg*NP + NP); lane
 // `sub` of every group owns the same 4 consecutive coordinates, so a tile
@@ -101,7 +116,7 @@ __device__ __forceinline__ void load_tile(const float *__restrict__ g, int64_t l
 #pragma unroll
             for (int k = 0; k < NP; ++k) {
                 asm volatile("" : "+s"(row));
-                const f32x4_u t = *(global_f32x4)((global_bytes)row + lane_bytes);
+                const f32x4_u t = stream_load((global_f32x4)((global_bytes)row + lane_bytes));
                 val[k][0] = t.x; val[k][1] = t.y; val[k][2] = t.z; val[k][3] = t.w;
                 if (!RAGGED || k + 1 < n) row += ld;
             }
@@ -114,7 +129,7 @@ __device__ __forceinline__ void load_tile(const float *__restrict__ g, int64_t l
 #pragma unroll
             for (int k = 0; k < NP; ++k) {
                 asm volatile("" : "+v"(row));
-                const f32x4_u t = *(global_f32x4)row;
+                const f32x4_u t = stream_load((global_f32x4)row);
                 val[k][0] = t.x; val[k][1] = t.y; val[k][2] = t.z; val[k][3] = t.w;
                 if (!RAGGED) row += ld * 4;
                 else row += (lg * NP + k + 1 < n) ? ld * 4 : 0;
