@@ -154,7 +154,9 @@ typedef struct btard_cc_problem {
 } btard_cc_problem;
 
 int btard_cc_begin(const btard_cc_problem *p);
-int btard_cc_gram(const btard_cc_problem *p);
+int btard_cc_gram(const btard_cc_problem *p);          /* = gram_matrix; gram_iterate */
+int btard_cc_gram_matrix(const btard_cc_problem *p);   /* the pass that forms the Gram matrices */
+int btard_cc_gram_iterate(const btard_cc_problem *p);  /* the iteration on them */
 int btard_cc_remaining(const btard_cc_problem *p, int32_t *remaining_host);
 int btard_cc_iterate(const btard_cc_problem *p, int32_t first_iteration, int32_t count);
 int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int32_t *iters,
@@ -196,6 +198,27 @@ int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
                              double *colsum, float *delta, int64_t ldd,
                              void *workspace, size_t workspace_bytes,
                              void *stream, uint32_t flags);
+
+/*
+ * CenteredClip and the verification quantities of its own result in one call:
+ * what btard_centered_clip followed by btard_verify_projections(v = that result,
+ * delta = NULL) return, with the last pass of the one and the pass of the other
+ * merged into a single read of g (the projections are taken against v as it is
+ * written, rounded to fp32).  Arguments as in those two calls.
+ */
+int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d,
+                               const int64_t *offsets_host, int32_t parts,
+                               float tau, float eps, int32_t max_iters,
+                               const float *v0, float *v, int32_t *iters,
+                               double *last_step_norm, uint64_t seed,
+                               double *norms, double *weights, double *proj,
+                               double *colsum, void *workspace,
+                               size_t workspace_bytes, void *stream, uint32_t flags);
+
+/* The same for the phased interface: btard_cc_finish + btard_verify_projections. */
+int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float *v,
+                           int32_t *iters, double *last_step_norm, uint64_t seed,
+                           double *norms, double *weights, double *proj, double *colsum);
 
 /*
  * Test hook for the z-spec: writes zhat[x_begin .. x_begin + count) (fp32,

@@ -74,6 +74,9 @@ def load_library():
     lib.btard_cc_begin.restype = c.c_int
     lib.btard_cc_gram.argtypes = [c.POINTER(_Problem)]
     lib.btard_cc_gram.restype = c.c_int
+    for name in ("btard_cc_gram_matrix", "btard_cc_gram_iterate"):
+        getattr(lib, name).argtypes = [c.POINTER(_Problem)]
+        getattr(lib, name).restype = c.c_int
     lib.btard_cc_remaining.argtypes = [c.POINTER(_Problem), c.POINTER(c.c_int32)]
     lib.btard_cc_remaining.restype = c.c_int
     lib.btard_debug_gram.argtypes = [c.POINTER(_Problem), c.c_void_p]
@@ -83,6 +86,16 @@ def load_library():
     lib.btard_cc_finish.argtypes = [c.POINTER(_Problem), c.c_int32, c.c_void_p, c.c_void_p,
                                     c.c_void_p]
     lib.btard_cc_finish.restype = c.c_int
+    lib.btard_cc_finish_verify.argtypes = [
+        c.POINTER(_Problem), c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_uint64,
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.btard_cc_finish_verify.restype = c.c_int
+    lib.btard_centered_clip_verify.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.POINTER(c.c_int64), c.c_int32,
+        c.c_float, c.c_float, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t,
+        c.c_void_p, c.c_uint32]
+    lib.btard_centered_clip_verify.restype = c.c_int
     lib.btard_verify_projections.argtypes = [
         c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.POINTER(c.c_int64), c.c_int32,
         c.c_void_p, c.c_float, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
@@ -193,6 +206,14 @@ def cc_gram(p: Problem) -> None:
     _check(load_library().btard_cc_gram(ctypes.byref(p.c)), "btard_cc_gram")
 
 
+def cc_gram_matrix(p: Problem) -> None:
+    _check(load_library().btard_cc_gram_matrix(ctypes.byref(p.c)), "btard_cc_gram_matrix")
+
+
+def cc_gram_iterate(p: Problem) -> None:
+    _check(load_library().btard_cc_gram_iterate(ctypes.byref(p.c)), "btard_cc_gram_iterate")
+
+
 def cc_remaining(p: Problem) -> int:
     """Synchronises the stream; upper bound on the iterations still needed."""
     out = ctypes.c_int32(0)
@@ -225,6 +246,60 @@ def cc_finish(p: Problem, iterations: int, v: Optional[torch.Tensor] = None,
     _check(load_library().btard_cc_finish(ctypes.byref(p.c), int(iterations), _ptr(v),
                                           _ptr(iters), _ptr(last_step_norm)), "btard_cc_finish")
     return v, iters, last_step_norm
+
+
+def _verify_outputs(n: int, P: int, dev, out: Optional[dict]) -> dict:
+    if out is None:
+        out = {}
+    for key in ("norms", "weights", "proj"):
+        if key not in out:
+            out[key] = torch.empty((n, P), dtype=torch.float64, device=dev)
+    if "colsum" not in out:
+        out["colsum"] = torch.empty(P, dtype=torch.float64, device=dev)
+    return out
+
+
+def cc_finish_verify(p: Problem, iterations: int, seed: int, v: Optional[torch.Tensor] = None,
+                     iters: Optional[torch.Tensor] = None,
+                     last_step_norm: Optional[torch.Tensor] = None, out: Optional[dict] = None):
+    """btard_cc_finish_verify.  Returns (v, iters, last_step_norm, dict of verification outputs)."""
+    dev = p.g.device
+    n = int(p.g.shape[0])
+    if v is None:
+        v = torch.empty(int(p.g.shape[1]), dtype=torch.float32, device=dev)
+    if iters is None:
+        iters = torch.empty(p.parts, dtype=torch.int32, device=dev)
+    if last_step_norm is None:
+        last_step_norm = torch.empty(p.parts, dtype=torch.float64, device=dev)
+    out = _verify_outputs(n, p.parts, dev, out)
+    _check(load_library().btard_cc_finish_verify(
+        ctypes.byref(p.c), int(iterations), _ptr(v), _ptr(iters), _ptr(last_step_norm),
+        int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(out["norms"]), _ptr(out["weights"]),
+        _ptr(out["proj"]), _ptr(out["colsum"])), "btard_cc_finish_verify")
+    return v, iters, last_step_norm, out
+
+
+def centered_clip_verify(g: torch.Tensor, offsets: Sequence[int], tau: float, eps: float,
+                         max_iters: int, seed: int, v0: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, flags: int = BTARD_FLAG_NONE):
+    """btard_centered_clip_verify.  Returns (v, iters, last_step_norm, dict)."""
+    n, d = int(g.shape[0]), int(g.shape[1])
+    P = len(offsets) - 1
+    dev = g.device
+    v = torch.empty(d, dtype=torch.float32, device=dev)
+    iters = torch.empty(P, dtype=torch.int32, device=dev)
+    last_step_norm = torch.empty(P, dtype=torch.float64, device=dev)
+    out = _verify_outputs(n, P, dev, None)
+    if workspace is None:
+        workspace = alloc_workspace(n, P, dev)
+    rc = load_library().btard_centered_clip_verify(
+        _ptr(g), _row_stride(g), n, d, _off_array(offsets), P, float(tau), float(eps),
+        int(max_iters), _ptr(v0), _ptr(v), _ptr(iters), _ptr(last_step_norm),
+        int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(out["norms"]), _ptr(out["weights"]),
+        _ptr(out["proj"]), _ptr(out["colsum"]), _ptr(workspace), workspace.numel(),
+        _stream_ptr(dev), int(flags))
+    _check(rc, "btard_centered_clip_verify")
+    return v, iters, last_step_norm, out
 
 
 def verify_projections(g: torch.Tensor, offsets: Sequence[int], v: torch.Tensor, tau: float,
@@ -272,9 +347,13 @@ btard_workspace_bytes = workspace_bytes
 btard_centered_clip = centered_clip
 btard_cc_begin = cc_begin
 btard_cc_gram = cc_gram
+btard_cc_gram_matrix = cc_gram_matrix
+btard_cc_gram_iterate = cc_gram_iterate
 btard_cc_remaining = cc_remaining
 btard_debug_gram = debug_gram
 btard_cc_iterate = cc_iterate
 btard_cc_finish = cc_finish
 btard_verify_projections = verify_projections
+btard_cc_finish_verify = cc_finish_verify
+btard_centered_clip_verify = centered_clip_verify
 btard_debug_zhat = debug_zhat

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "cc_kernels.h"
+#include "fused_kernels.h"
 #include "gram_kernels.h"
 #include "verify_kernels.h"
 
@@ -115,6 +116,7 @@ int variant_tile_width(Variant v)
 typedef void (*CcPassFn)(CcArgs);
 typedef void (*CcFinishFn)(CcFinishArgs);
 typedef void (*VerifyFn)(VerifyArgs);
+typedef void (*FusedFn)(FusedArgs);
 
 // [variant][ragged: n < NP*LG][has v0]
 #define BTARD_CC_ROW(K, NP, LG)                                                   \
@@ -136,6 +138,11 @@ const VerifyFn kVerify[kVariants][2] = {BTARD_V_ROW(4, 1),  BTARD_V_ROW(8, 1),  
                                         BTARD_V_ROW(16, 2), BTARD_V_ROW(16, 4), BTARD_V_ROW(16, 8),
                                         BTARD_V_ROW(16, 16)};
 #undef BTARD_V_ROW
+#define BTARD_F_ROW(NP, LG) {cc_finish_verify_kernel<NP, LG, false>, cc_finish_verify_kernel<NP, LG, true>}
+const FusedFn kFused[kVariants][2] = {BTARD_F_ROW(4, 1),  BTARD_F_ROW(8, 1),  BTARD_F_ROW(16, 1),
+                                      BTARD_F_ROW(16, 2), BTARD_F_ROW(16, 4), BTARD_F_ROW(16, 8),
+                                      BTARD_F_ROW(16, 16)};
+#undef BTARD_F_ROW
 
 int variant_peers(Variant v)
 {
@@ -286,7 +293,7 @@ static int gram_blocks(const btard_cc_problem *p)
     return blocks_per_partition(resident, p->parts, p->offsets_host, 256);
 }
 
-int btard_cc_gram(const btard_cc_problem *p)
+int btard_cc_gram_matrix(const btard_cc_problem *p)
 {
     const int rc = check_problem(p);
     if (rc != BTARD_OK) return rc;
@@ -297,15 +304,35 @@ int btard_cc_gram(const btard_cc_problem *p)
     const WsLayout L = ws_layout(p->n, p->parts);
     GramArgs ga;
     ga.g = p->g; ga.ld = p->ldg; ga.n = p->n;
+    ga.off = carve_cc(p->workspace, p->n, p->parts).off;
     ga.gpart = reinterpret_cast<double *>(static_cast<char *>(p->workspace) + L.gram);
+    hipLaunchKernelGGL(gram_pass_kernel, dim3(B, p->parts), dim3(kBlock), 0, s, ga);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+int btard_cc_gram_iterate(const btard_cc_problem *p)
+{
+    const int rc = check_problem(p);
+    if (rc != BTARD_OK) return rc;
+    if (!gram_applies(p)) return BTARD_OK;
+    hipStream_t s = static_cast<hipStream_t>(p->stream);
+    const int B = gram_blocks(p);
+    if (B <= 0) return BTARD_ERR_DEVICE;
+    const WsLayout L = ws_layout(p->n, p->parts);
     GramIterArgs gi;
     gi.st = carve_cc(p->workspace, p->n, p->parts);
-    ga.off = gi.st.off;
-    gi.gpart = ga.gpart; gi.blocks = B; gi.n = p->n;
+    gi.gpart = reinterpret_cast<const double *>(static_cast<char *>(p->workspace) + L.gram);
+    gi.blocks = B; gi.n = p->n;
     gi.tau = (double)p->tau; gi.eps = (double)p->eps; gi.max_iters = p->max_iters;
-    hipLaunchKernelGGL(gram_pass_kernel, dim3(B, p->parts), dim3(kBlock), 0, s, ga);
     hipLaunchKernelGGL(gram_iterate_kernel, dim3(p->parts), dim3(kBlock), 0, s, gi);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+int btard_cc_gram(const btard_cc_problem *p)
+{
+    const int rc = btard_cc_gram_matrix(p);
+    if (rc != BTARD_OK) return rc;
+    return btard_cc_gram_iterate(p);
 }
 
 int btard_cc_remaining(const btard_cc_problem *p, int32_t *remaining_host)
@@ -438,6 +465,81 @@ int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
     rc = btard_cc_iterate(&p, 0, passes);
     if (rc != BTARD_OK) return rc;
     return btard_cc_finish(&p, passes, v, iters, last_step_norm);
+}
+
+int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float *v, int32_t *iters,
+                           double *last_step_norm, uint64_t seed, double *norms, double *weights,
+                           double *proj, double *colsum)
+{
+    const int rc = check_problem(p);
+    if (rc != BTARD_OK) return rc;
+    if (!v || !iters || iterations < 0 || !norms || !weights || !proj) return BTARD_ERR_INVALID_ARG;
+    if (p->v0) {
+        // with a caller-supplied start vector: the two separate passes
+        const int r1 = btard_cc_finish(p, iterations, v, iters, last_step_norm);
+        if (r1 != BTARD_OK) return r1;
+        return btard_verify_projections(p->g, p->ldg, p->n, p->d, p->offsets_host, p->parts, v,
+                                        p->tau, seed, norms, weights, proj, colsum, nullptr, 0,
+                                        p->workspace, p->workspace_bytes, p->stream,
+                                        BTARD_FLAG_NONE);
+    }
+    hipStream_t s = static_cast<hipStream_t>(p->stream);
+    const Variant var = pick_variant(p->n);
+    const int ragged = p->n < variant_peers(var) ? 1 : 0;
+    const FusedFn fn = kFused[var][ragged];
+    const int resident = resident_blocks(3, var, 1 + ragged, reinterpret_cast<const void *>(fn));
+    if (resident <= 0) return BTARD_ERR_DEVICE;
+    const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
+    const int Bpass = pass_blocks(p, var, ragged, 0);
+    if (Bpass <= 0) return BTARD_ERR_DEVICE;
+    FusedArgs a;
+    a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v = v;
+    a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
+    a.pass = iterations; a.prev_blocks = Bpass; a.seed = seed; a.S = 2 * p->n + 2;
+    a.st = carve_cc(p->workspace, p->n, p->parts);
+    hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
+
+    const double *part = a.st.partial + (iterations & 1) * a.st.partial_stride;
+    VerifyFinishArgs f;
+    f.partial = part; f.n = p->n; f.P = p->parts; f.B = B; f.S = a.S; f.tau = (double)p->tau;
+    f.norms = norms; f.weights = weights; f.proj = proj; f.colsum = colsum;
+    hipLaunchKernelGGL(verify_finish_kernel, dim3(p->parts), dim3(kFinishThreads), 0, s, f);
+    FusedReportArgs r;
+    r.st = a.st; r.partial = part; r.blocks = B; r.S = a.S; r.index = 2 * p->n + 1;
+    r.iters_out = iters; r.step_norm_out = last_step_norm;
+    hipLaunchKernelGGL(fused_report_kernel, dim3(p->parts), dim3(kBlock), 0, s, r);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d,
+                               const int64_t *offsets_host, int32_t parts, float tau, float eps,
+                               int32_t max_iters, const float *v0, float *v, int32_t *iters,
+                               double *last_step_norm, uint64_t seed, double *norms,
+                               double *weights, double *proj, double *colsum, void *workspace,
+                               size_t workspace_bytes, void *stream, uint32_t flags)
+{
+    btard_cc_problem p;
+    p.g = g; p.ldg = ldg; p.n = n; p.d = d; p.offsets_host = offsets_host; p.parts = parts;
+    p.tau = tau; p.eps = eps; p.max_iters = max_iters; p.v0 = v0;
+    p.workspace = workspace; p.workspace_bytes = workspace_bytes; p.stream = stream;
+    p.flags = flags;
+    int rc = check_problem(&p);
+    if (rc != BTARD_OK) return rc;
+    if (!v || !iters || overlaps(v, v0, d) || !norms || !weights || !proj)
+        return BTARD_ERR_INVALID_ARG;
+    rc = btard_cc_begin(&p);
+    if (rc != BTARD_OK) return rc;
+    rc = btard_cc_gram(&p);
+    if (rc != BTARD_OK) return rc;
+    int32_t passes = max_iters;
+    if ((flags & BTARD_FLAG_HOST_SYNC) != 0 && gram_applies(&p)) {
+        rc = btard_cc_remaining(&p, &passes);
+        if (rc != BTARD_OK) return rc;
+    }
+    rc = btard_cc_iterate(&p, 0, passes);
+    if (rc != BTARD_OK) return rc;
+    return btard_cc_finish_verify(&p, passes, v, iters, last_step_norm, seed, norms, weights, proj,
+                                  colsum);
 }
 
 int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,

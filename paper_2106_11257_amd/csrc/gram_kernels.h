@@ -45,7 +45,10 @@ __device__ __forceinline__ int gram_entry(int lane, int r) { return ((lane >> 4)
 // groups of 16; in group s the lane loads coordinates 16 s + 4 q .. + 3 (one 128-bit load)
 // and feeds them, one at a time, to v_mfma_f64_16x16x4_f64 as BOTH operands: in MFMA k-slot
 // q the 16 lanes that share q hold the 16 peers' values of one coordinate, which is what
-// A (16 x 4) and B (4 x 16) of Gamma += X_tile X_tile^T look like.
+// A (16 x 4) and B (4 x 16) of Gamma += X_tile X_tile^T look like.  (Loading row-wise and
+// transposing through LDS, and prefetching the next tile, were tried: the kernel stays at
+// the fp64 MFMA issue rate either way -- measured 105 cycles per instruction -- so the
+// simple form is kept.)
 __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
 {
     constexpr int kW = 256;
@@ -58,7 +61,10 @@ __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
     const bool have = p < n;
     global_f32 row = (global_f32)a.g + (int64_t)(have ? p : n - 1) * a.ld;
 
-    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+    // four independent accumulators: consecutive MFMAs do not wait for each other
+    f64x4 acc[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) acc[m] = f64x4{0.0, 0.0, 0.0, 0.0};
     const TileRange tr = tile_range<kW>(lo, hi);
     for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
         const int64_t xu = tr.xa + u * kW;
@@ -86,7 +92,7 @@ __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const double d = have ? (double)val[s][e] : 0.0;
-                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(d, d, acc, 0, 0, 0);
+                acc[e] = __builtin_amdgcn_mfma_f64_16x16x4f64(d, d, acc[e], 0, 0, 0);
             }
         }
     }
@@ -94,7 +100,8 @@ __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
     // workgroup partial: the 4 wavefronts' matrices added in order
     __shared__ double sh[kWaves][kGramEntries];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) sh[wave][gram_entry(lane, r)] = acc[r];
+    for (int r = 0; r < 4; ++r)
+        sh[wave][gram_entry(lane, r)] = (acc[0][r] + acc[1][r]) + (acc[2][r] + acc[3][r]);
     __syncthreads();
     const int t = threadIdx.x;
     double s = 0.0;
@@ -117,13 +124,52 @@ struct GramIterArgs {
 // hundred fused multiply-adds of exact products, the rest are short fixed-order sums).
 constexpr double kGramUnit = 1.4210854715202004e-14;
 
-// Sum over the 16 lanes of a row of the wavefront (every lane gets the total, in a
-// fixed order).
+// Value of lane `k` (a compile-time constant) for every lane: two v_readlane into scalar
+// registers, no LDS traffic.
+template <int K>
+__device__ __forceinline__ double lane_value(double x)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, K);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), K);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+// x of the lane CTRL positions to the left in the same row of 16 lanes (0 if there is none).
+template <int CTRL>
+__device__ __forceinline__ double row_shift_right(double x)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, 0xf, 0xf, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, 0xf, 0xf, true);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+// Sum over lanes 0..15 (row 0 of the wavefront; the other rows hold copies), in a fixed
+// order, returned to every lane: DPP row shifts by 1, 2, 4, 8 leave the total in lane 15.
 __device__ __forceinline__ double row_sum16(double x)
 {
-#pragma unroll
-    for (int m = 8; m >= 1; m >>= 1) x += __shfl_xor(x, m, 16);
-    return x;
+    x += row_shift_right<0x111>(x);
+    x += row_shift_right<0x112>(x);
+    x += row_shift_right<0x114>(x);
+    x += row_shift_right<0x118>(x);
+    return lane_value<15>(x);
+}
+
+// sum_k row[k] * (value of x in lane k)
+template <int N>
+__device__ __forceinline__ double row_dot(const double (&row)[N], double x)
+{
+    double y = 0.0;
+    y = fma(row[0], lane_value<0>(x), y);   y = fma(row[1], lane_value<1>(x), y);
+    y = fma(row[2], lane_value<2>(x), y);   y = fma(row[3], lane_value<3>(x), y);
+    y = fma(row[4], lane_value<4>(x), y);   y = fma(row[5], lane_value<5>(x), y);
+    y = fma(row[6], lane_value<6>(x), y);   y = fma(row[7], lane_value<7>(x), y);
+    y = fma(row[8], lane_value<8>(x), y);   y = fma(row[9], lane_value<9>(x), y);
+    y = fma(row[10], lane_value<10>(x), y); y = fma(row[11], lane_value<11>(x), y);
+    y = fma(row[12], lane_value<12>(x), y); y = fma(row[13], lane_value<13>(x), y);
+    y = fma(row[14], lane_value<14>(x), y); y = fma(row[15], lane_value<15>(x), y);
+    return y;
 }
 
 // One workgroup per partition: the whole iteration of eq. (CenteredClip) on the Gram
@@ -131,7 +177,7 @@ __device__ __forceinline__ double row_sum16(double x)
 // final state (done = 1) or the state at which the streaming passes must take over.
 // After the workgroup has summed the partial matrices, one wavefront runs the iteration
 // in registers: lane i (mod 16) owns peer i and row i of Gamma; the scalars every peer
-// needs travel by lane broadcasts and 16-lane butterflies, with no LDS and no barriers.
+// needs travel by v_readlane broadcasts and DPP row shifts, with no LDS and no barriers.
 __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
 {
     constexpr int N = kGramPeers;
@@ -166,9 +212,7 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
     double ev = 0.0;                          // bound on the error put into v so far
 
     while (!dn) {                             // wavefront-uniform
-        double y = 0.0;
-#pragma unroll
-        for (int k = 0; k < N; ++k) y = fma(row[k], __shfl(c, k, 16), y);
+        const double y = row_dot<N>(row, c);
         const double qv = row_sum16(c * y);
         const double Sc = row_sum16(fabs(c) * rt);
         // norms, weights and how wrong the weights may be
@@ -182,7 +226,9 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
             // a weight that is (or may be) tau/N inherits half the relative error of N^2;
             // its contribution to v is w * N <= tau
             if (N2 + eN2 > a.tau * a.tau) {
-                const double rel = (N2 > eN2) ? 0.5 * eN2 / N2 : 1.0;
+                // (error bars are bounds: hardware reciprocal / square-root estimates,
+                // rounded up by 1 %, instead of full divisions)
+                const double rel = (N2 > eN2) ? 0.505 * eN2 * __builtin_amdgcn_rcp(N2) : 1.0;
                 err_w = rel * fmin(Nn, a.tau) * inv_n;
             }
         }
@@ -190,16 +236,14 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         const double ev_new = ev + row_sum16(err_w);
         // the update this would apply, and its norm sqrt(a^T Gamma a)
         const double an = peer ? (w - W * c) / (double)n : 0.0;
-        double u = 0.0;
-#pragma unroll
-        for (int k = 0; k < N; ++k) u = fma(row[k], __shfl(an, k, 16), u);
+        const double u = row_dot<N>(row, an);
         const double Tn2 = row_sum16(an * u);
         const double Sa = row_sum16(fabs(an) * rt);
         const double T = sqrt(fmax(Tn2, 0.0));
         // error budget: the (generously bounded, never discounted) error put into v must
         // stay a small fraction of ||v|| and of the step itself (whose norm is compared
         // with eps below; the norm that is reported is recomputed from the data at the end)
-        const double budget = fmin(1e-8 * sqrt(fmax(qv, 0.0)), 1e-3 * T);
+        const double budget = fmin(0.99e-8 * __builtin_amdgcn_sqrt(fmax(qv, 0.0)), 1e-3 * T);
         if (ev_new > budget) break;                               // hand over before this update
         ev = ev_new;
         al = an;
@@ -209,7 +253,8 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         // stopping rule on the update just applied, with its error bar
         if (a.eps > 0.0) {
             const double eT2 = kGramUnit * Sa * Sa;
-            const double eT = (T * T > eT2) ? eT2 / T : sqrt(eT2);
+            const double eT = (T * T > eT2) ? 1.01 * eT2 * __builtin_amdgcn_rcp(T)
+                                            : 1.01 * __builtin_amdgcn_sqrt(eT2);
             // the plain iteration's step may differ from this one by the error in v as well
             const double band = eT + 2.0 * ev;
             if (T + band < a.eps) dn = 1;                         // certainly converged

@@ -305,6 +305,30 @@ def test_gram_path_configs_reduced_length(dev, cfg, d):
              flags=btard.BTARD_FLAG_GRAM)
 
 
+@pytest.mark.parametrize("n,d,P,pad,flags", [(3, 1031, 2, 0, 0), (9, 5000, 4, 2, 1), (16, 262147, 3, 5, 0),
+                                             (16, 70001, 16, 0, 3), (33, 2000, 3, 1, 0),
+                                             (64, 20000, 64, 0, 0), (130, 700, 2, 0, 0)])
+def test_fused_finish_and_verify_equals_the_two_calls(dev, n, d, P, pad, flags):
+    G, off = workloads.generic_case(n, d, P, seed=n + d, device=dev, ld=d + pad, spread=0.05,
+                                    outliers=max(1, n // 5))
+    tau, eps, M, seed = 1.0, 1e-6, 30, 0x1234ABCD5678
+    v, iters, sn = btard.centered_clip(G, off, tau, eps, M, flags=flags)
+    ref = btard.verify_projections(G, off, v, tau, seed)
+    v2, iters2, sn2, out = btard.centered_clip_verify(G, off, tau, eps, M, seed, flags=flags)
+    torch.cuda.synchronize()
+    assert torch.equal(v, v2) and torch.equal(iters, iters2)
+    np.testing.assert_allclose(sn2.cpu().numpy(), sn.cpu().numpy(), rtol=1e-12, atol=1e-300)
+    for k in ("norms", "weights", "proj", "colsum"):
+        a, b = out[k].cpu().numpy(), ref[k].cpu().numpy()
+        assert np.abs(a - b).max() <= 1e-12 * max(np.abs(b).max(), 1e-300), k
+    # and with a caller-supplied start vector (served by the two separate passes)
+    v0 = torch.zeros(d, device=dev)
+    a = btard.centered_clip(G, off, tau, eps, 5, v0=v0)
+    b = btard.centered_clip_verify(G, off, tau, eps, 5, seed, v0=v0)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
 # --------------------------------------------------------------------------
 # the five benchmark configurations: reduced length (whole oracle) and full size
 # --------------------------------------------------------------------------
@@ -334,9 +358,25 @@ def test_configs_full_size(dev, cfg, sample):
         pytest.skip(f"needs {need / 2**30:.0f} GiB of device memory")
     wl = workloads.make_workload(cfg, device=dev)
     say(f"[full] {wl.name}: slab {wl.slab_bytes / 2**30:.2f} GiB generated")
+    # the per-iteration path and the two separate calls ...
     v, iters, sn = check_cc(wl.G, wl.offsets, wl.tau, wl.eps, wl.max_iters, parts_to_check=sample,
                             label=wl.name)
     say(f"    iters = {iters.cpu().numpy().tolist()}")
-    check_verify(wl.G, wl.offsets, v, wl.tau, wl.seed_z, parts_to_check=sample, label=wl.name)
-    del wl, v
+    out = check_verify(wl.G, wl.offsets, v, wl.tau, wl.seed_z, parts_to_check=sample, label=wl.name)
+    # ... and the path the benchmark's headline times (Gram iteration where it applies, one
+    # host synchronisation, last pass fused with the verification pass) must agree with them
+    F = btard.BTARD_FLAG_GRAM | btard.BTARD_FLAG_HOST_SYNC
+    v2, iters2, sn2, out2 = btard.centered_clip_verify(wl.G, wl.offsets, wl.tau, wl.eps,
+                                                       wl.max_iters, wl.seed_z, flags=F)
+    torch.cuda.synchronize()
+    assert torch.equal(iters, iters2)
+    vh, v2h = v.cpu().numpy(), v2.cpu().numpy()
+    for j in range(wl.parts):
+        lo, hi = wl.offsets[j], wl.offsets[j + 1]
+        assert rel_l2(v2h[lo:hi], vh[lo:hi]) <= 1e-6, f"partition {j}"
+    np.testing.assert_allclose(sn2.cpu().numpy(), sn.cpu().numpy(), rtol=1e-4, atol=1e-11)
+    a, b = out2["proj"].cpu().numpy(), out["proj"].cpu().numpy()
+    assert rel_l2(a, b) <= 1e-5
+    np.testing.assert_allclose(out2["norms"].cpu().numpy(), out["norms"].cpu().numpy(), rtol=1e-6)
+    del wl, v, v2
     torch.cuda.empty_cache()
