@@ -7,7 +7,9 @@
 
 #include <cmath>
 #include <cstdint>
+#include <map>
 #include <mutex>
+#include <utility>
 #include <vector>
 
 #include "cc_kernels.h"
@@ -26,7 +28,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-    size_t off, coef, delta, iters, done, aux, partial, partial_stride_doubles, gram, total;
+    size_t off, coef, delta, iters, done, aux, gram_n2, partial, partial_stride_doubles, gram, total;
 };
 
 // State and partial sums exist twice (double-buffered by pass parity).
@@ -40,7 +42,8 @@ WsLayout ws_layout(int32_t n, int32_t P)
     L.delta = p;    p = align_up(p + 2 * sizeof(double) * P * R);
     L.iters = p;    p = align_up(p + 2 * sizeof(int32_t) * P);
     L.done = p;     p = align_up(p + 2 * sizeof(int32_t) * P);      // done | final_buf
-    L.aux = p;      p = align_up(p + 2 * sizeof(int32_t) * P);      // report_buf | remaining
+    L.aux = p;      p = align_up(p + 3 * sizeof(int32_t) * P);      // report_buf | remaining | gram_ok
+    L.gram_n2 = p;  p = align_up(p + sizeof(double) * P * (R + 1));  // gram_n2 [P][R] | gram_t2 [P]
     const size_t blocks = (size_t)(P > kMaxBlocks ? P : kMaxBlocks);
     L.partial_stride_doubles = align_up(sizeof(double) * blocks * S) / sizeof(double);
     L.partial = p;  p = align_up(p + 2 * sizeof(double) * L.partial_stride_doubles);
@@ -82,6 +85,9 @@ CcState carve_cc(void *ws, int32_t n, int32_t P)
     st.final_buf = st.done + P;
     st.report_buf = reinterpret_cast<int32_t *>(b + L.aux);
     st.remaining = st.report_buf + P;
+    st.gram_ok = st.report_buf + 2 * (size_t)P;
+    st.gram_n2 = reinterpret_cast<double *>(b + L.gram_n2);
+    st.gram_t2 = st.gram_n2 + (size_t)P * ((size_t)n + 1);
     st.partial_stride = (int64_t)L.partial_stride_doubles;
     st.R = n + 1;
     st.P = P;
@@ -143,6 +149,10 @@ const FusedFn kFused[kVariants][2] = {BTARD_F_ROW(4, 1),  BTARD_F_ROW(8, 1),  BT
                                       BTARD_F_ROW(16, 2), BTARD_F_ROW(16, 4), BTARD_F_ROW(16, 8),
                                       BTARD_F_ROW(16, 16)};
 #undef BTARD_F_ROW
+// the Gram formulation's last pass: n <= 16, one lane group  [variant][ragged]
+const FusedFn kProject[3][2] = {{cc_finish_project_kernel<4, false>, cc_finish_project_kernel<4, true>},
+                                {cc_finish_project_kernel<8, false>, cc_finish_project_kernel<8, true>},
+                                {cc_finish_project_kernel<16, false>, cc_finish_project_kernel<16, true>}};
 
 int variant_peers(Variant v)
 {
@@ -154,17 +164,16 @@ int variant_peers(Variant v)
 // (compute units x occupancy), cached per (device, kernel).
 struct ResidentCache {
     std::mutex mu;
-    int value[16][4][kVariants][4] = {};
+    std::map<std::pair<int, const void *>, int> value;
 };
 ResidentCache g_resident;
 
-int resident_blocks(int kind, Variant v, int sub, const void *fn)
+int resident_blocks(const void *fn)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (dev < 0 || dev >= 16) dev = 0;
     std::lock_guard<std::mutex> lock(g_resident.mu);
-    int &slot = g_resident.value[dev][kind][v][sub];
+    int &slot = g_resident.value[std::make_pair(dev, fn)];
     if (slot == 0) {
         int cus = 0, occ = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
@@ -288,7 +297,7 @@ static bool gram_applies(const btard_cc_problem *p)
 
 static int gram_blocks(const btard_cc_problem *p)
 {
-    const int resident = resident_blocks(3, V16x1, 0, reinterpret_cast<const void *>(gram_pass_kernel));
+    const int resident = resident_blocks(reinterpret_cast<const void *>(gram_pass_kernel));
     if (resident <= 0) return 0;
     return blocks_per_partition(resident, p->parts, p->offsets_host, 256);
 }
@@ -379,7 +388,7 @@ int btard_debug_gram(const btard_cc_problem *p, double *gram_out)
 static int pass_blocks(const btard_cc_problem *p, Variant var, int ragged, int based)
 {
     const CcPassFn fn = kCcPass[var][ragged][based];
-    const int resident = resident_blocks(0, var, ragged * 2 + based, reinterpret_cast<const void *>(fn));
+    const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
     if (resident <= 0) return 0;
     return blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
 }
@@ -419,7 +428,7 @@ int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int
     const Variant var = pick_variant(p->n);
     const int ragged = p->n < variant_peers(var) ? 1 : 0, based = p->v0 ? 1 : 0;
     const CcFinishFn fn = kCcFinish[var][ragged][based];
-    const int resident = resident_blocks(1, var, ragged * 2 + based, reinterpret_cast<const void *>(fn));
+    const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
     if (resident <= 0) return BTARD_ERR_DEVICE;
     const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
     const int Bpass = pass_blocks(p, var, ragged, based);
@@ -487,16 +496,30 @@ int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float 
     const Variant var = pick_variant(p->n);
     const int ragged = p->n < variant_peers(var) ? 1 : 0;
     const FusedFn fn = kFused[var][ragged];
-    const int resident = resident_blocks(3, var, 1 + ragged, reinterpret_cast<const void *>(fn));
+    const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
     if (resident <= 0) return BTARD_ERR_DEVICE;
-    const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
+    int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
     const int Bpass = pass_blocks(p, var, ragged, 0);
     if (Bpass <= 0) return BTARD_ERR_DEVICE;
+    // With the Gram formulation two kernels share the partitions (each leaves at once what
+    // is the other's): the light one takes those the Gram iteration finished and vouches
+    // for.  Both write the same partial-sum layout, so they use one grid width.
+    const bool split = gram_applies(p);
+    FusedFn light = nullptr;
+    if (split) {
+        light = kProject[var][ragged];
+        const int res_l = resident_blocks(reinterpret_cast<const void *>(light));
+        if (res_l <= 0) return BTARD_ERR_DEVICE;
+        const int Bl = blocks_per_partition(res_l, p->parts, p->offsets_host, variant_tile_width(var));
+        if (Bl < B) B = Bl;
+    }
     FusedArgs a;
     a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v = v;
     a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
     a.pass = iterations; a.prev_blocks = Bpass; a.seed = seed; a.S = 2 * p->n + 2;
+    a.skip_gram_ok = split ? 1 : 0;
     a.st = carve_cc(p->workspace, p->n, p->parts);
+    if (split) hipLaunchKernelGGL(light, dim3(B, p->parts), dim3(kBlock), 0, s, a);
     hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
 
     const double *part = a.st.partial + (iterations & 1) * a.st.partial_stride;
@@ -564,7 +587,7 @@ int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
     const Variant var = pick_variant(n);
     const int ragged = n < variant_peers(var) ? 1 : 0;
     const VerifyFn vfn = kVerify[var][ragged];
-    const int resident = resident_blocks(2, var, ragged, reinterpret_cast<const void *>(vfn));
+    const int resident = resident_blocks(reinterpret_cast<const void *>(vfn));
     if (resident <= 0) return BTARD_ERR_DEVICE;
     const int B = blocks_per_partition(resident, parts, offsets_host, variant_tile_width(var));
 

@@ -39,6 +39,10 @@ struct CcState {
     int32_t *final_buf;      // [P] state buffer that holds a stopped partition's final state
     int32_t *report_buf;     // [P] state buffer the finish kernel left the reported state in
     int32_t *remaining;      // [P] iterations still to run after the Gram iteration
+    int32_t *gram_ok;        // [P] the Gram iteration finished the partition AND vouches for
+                             //     the final norms and the last step norm it left below
+    double *gram_n2;         // [P][R] ||g_i - v||^2 at the final v, from the Gram matrix
+    double *gram_t2;         // [P]    ||last applied update||^2, from the Gram matrix
     int64_t partial_stride;  // doubles between the two partial-sum buffers
     int32_t R;               // n + 1
     int32_t P;
@@ -87,6 +91,7 @@ __global__ void cc_init_kernel(CcState st, int32_t n, int32_t has_v0, int32_t ma
         st.final_buf[j] = 0;
         st.report_buf[j] = 0;
         st.remaining[j] = max_iters > 0 ? max_iters : 0;
+        st.gram_ok[j] = 0;
     }
 }
 
@@ -236,7 +241,7 @@ __device__ __forceinline__ void combine_rows(const float (&val)[NP][4], const fl
 // one iteration: control step for the previous pass, then norms at v^l
 // ---------------------------------------------------------------------------
 template <int NP, int LG, bool RAGGED, bool HAS_BASE>
-__global__ __launch_bounds__(kBlock) void cc_pass_kernel(CcArgs a)
+__global__ __launch_bounds__(kBlock, (LG == 1 ? 4 : 2)) void cc_pass_kernel(CcArgs a)
 {
     using G = Geo<NP, LG>;
     __shared__ double s_c[kBlock], s_a[kBlock], s_red[kBlock];
@@ -352,8 +357,51 @@ struct CcFinishArgs {
     CcState st;
 };
 
+// One tile of the last pass: v = c_0 v0 + sum_i c_i g_i rounded to fp32 and written, and
+// the squared norm of the last applied update.  INTERIOR: the whole tile lies inside the
+// partition (wavefront-uniform): vector loads and store, no masks.
+template <int NP, int LG, bool RAGGED, bool HAS_BASE, bool INTERIOR>
+__device__ __forceinline__ void finish_tile(const float *__restrict__ g, int64_t ld, int n,
+                                            const float *__restrict__ v0, float *__restrict__ v,
+                                            int lg, int sub, int64_t xu, int64_t lo, int64_t hi,
+                                            const double (&c)[NP], const double (&dl)[NP],
+                                            double cb, double db, double &t2)
+{
+    const int64_t x0 = xu + (int64_t)sub * kVec;
+    float val[NP][4];
+    load_tile<NP, LG, RAGGED>(g, ld, n, lg, sub, xu, lo, hi, INTERIOR, val);
+    float base[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (HAS_BASE) {
+        if (INTERIOR) load_row4_vec(v0 + x0, base);
+        else load_row4_guarded(v0, x0, lo, hi, base);
+    }
+    // (converted one by one where they are used: few registers, many wavefronts)
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) forget(val[k][e]);
+    }
+    double vv[4], ss[4];
+    combine_rows<NP, LG, HAS_BASE>(val, base, c, dl, cb, db, vv, ss);
+    if (lg == 0) {
+        if (INTERIOR) {
+            f32x4_u o;
+            o.x = (float)vv[0]; o.y = (float)vv[1]; o.z = (float)vv[2]; o.w = (float)vv[3];
+            stream_store(v + x0, o);
+        } else {
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) {
+                const int64_t x = x0 + e;
+                if (x >= lo && x < hi) v[x] = (float)vv[e];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) t2 = fma(ss[e], ss[e], t2);
+    }
+}
+
 template <int NP, int LG, bool RAGGED, bool HAS_BASE>
-__global__ __launch_bounds__(kBlock) void cc_finish_kernel(CcFinishArgs a)
+__global__ __launch_bounds__(kBlock, 3) void cc_finish_kernel(CcFinishArgs a)
 {
     using G = Geo<NP, LG>;
     __shared__ double s_c[kBlock], s_a[kBlock], s_red[kBlock];
@@ -389,35 +437,22 @@ __global__ __launch_bounds__(kBlock) void cc_finish_kernel(CcFinishArgs a)
     fetch_coefficients<NP, LG, RAGGED>(s_c, s_a, n, lg, c, dl, cb, db);
     double t2 = 0.0;
 
+    // interior tiles, then the partition's first and last tile where they are not interior
+    // (by the wavefronts that own them): two bodies, so that the guarded one costs the
+    // common one no registers
     const TileRange tr = tile_range<G::kW>(lo, hi);
-    for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
+    const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
+    for (int64_t u = iw.begin; u < iw.end; u += tr.stride)
+        finish_tile<NP, LG, RAGGED, HAS_BASE, true>(a.g, a.ld, n, a.v0, a.v, lg, sub,
+                                                    tr.xa + u * G::kW, lo, hi, c, dl, cb, db, t2);
+#pragma unroll 1
+    for (int t = 0; t < 2; ++t) {
+        const int64_t u = (t == 0) ? 0 : tr.units - 1;
+        if ((t == 1 && tr.units < 2) || !owns_tile(tr, u)) continue;
         const int64_t xu = tr.xa + u * G::kW;
-        const bool interior = (xu >= lo) && (xu + G::kW <= hi);
-        const int64_t x0 = xu + (int64_t)sub * kVec;
-        float val[NP][4];
-        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
-        float base[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (HAS_BASE) {
-            if (interior) load_row4_vec(a.v0 + x0, base);
-            else load_row4_guarded(a.v0, x0, lo, hi, base);
-        }
-        double vv[4], ss[4];
-        combine_rows<NP, LG, HAS_BASE>(val, base, c, dl, cb, db, vv, ss);
-        if (lg == 0) {
-            if (interior) {
-                f32x4_u o;
-                o.x = (float)vv[0]; o.y = (float)vv[1]; o.z = (float)vv[2]; o.w = (float)vv[3];
-                *reinterpret_cast<f32x4_u *>(a.v + x0) = o;
-            } else {
-#pragma unroll
-                for (int e = 0; e < kVec; ++e) {
-                    const int64_t x = x0 + e;
-                    if (x >= lo && x < hi) a.v[x] = (float)vv[e];
-                }
-            }
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) t2 = fma(ss[e], ss[e], t2);
-        }
+        if (tile_is_interior<G::kW>(xu, lo, hi)) continue;
+        finish_tile<NP, LG, RAGGED, HAS_BASE, false>(a.g, a.ld, n, a.v0, a.v, lg, sub, xu, lo, hi, c,
+                                                     dl, cb, db, t2);
     }
 
     t2 = sum_within_group<G::kLanes>(t2);

@@ -21,8 +21,75 @@ struct FusedArgs {
     int32_t prev_blocks;
     uint64_t seed;
     int32_t S;               // 2n + 2: n norms^2, n <zhat, r_i>, |zhat|^2, |last update|^2
+    int32_t skip_gram_ok;    // leave partitions with gram_ok set to cc_finish_project_kernel
     CcState st;
 };
+
+// The arithmetic of one tile whose rows are in registers (val).  INTERIOR (the whole tile
+// lies inside the partition, a wavefront-uniform fact) selects a body with a vector store
+// and no masks; the other body guards every coordinate.
+template <int NP, int LG, bool INTERIOR>
+__device__ __forceinline__ void fused_rows(float *__restrict__ v, uint64_t seed, int lg, int sub,
+                                           int64_t xu, int64_t lo, int64_t hi, float (&val)[NP][4],
+                                           const double (&c)[NP], const double (&dl)[NP],
+                                           double (&accN)[NP], double (&accR)[NP], double &t2,
+                                           double &z2)
+{
+    const int64_t x0 = xu + (int64_t)sub * kVec;
+    // nothing below moves ahead of loads issued before this call (the next tile's)
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) forget(val[k][e]);
+    }
+    const float base[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    double vv[4], ss[4];
+    combine_rows<NP, LG, false>(val, base, c, dl, 0.0, 0.0, vv, ss);
+
+    // the aggregate as the caller will see it: rounded to fp32
+    float vf[4];
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) vf[e] = (float)vv[e];
+    if (lg == 0) {
+        if (INTERIOR) {
+            f32x4_u o;
+            o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
+            stream_store(v + x0, o);
+        } else {
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) {
+                const int64_t x = x0 + e;
+                if (x >= lo && x < hi) v[x] = vf[e];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) t2 = fma(ss[e], ss[e], t2);
+    }
+
+    float zf[4];
+    zhat_block(seed, x0 >> 2, zf);
+    double z[4], vd[4];
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+        const int64_t x = x0 + e;
+        z[e] = (INTERIOR || (x >= lo && x < hi)) ? (double)zf[e] : 0.0;
+        vd[e] = (double)vf[e];
+    }
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            forget(val[k][e]);   // converted again here instead of kept as 2x the registers
+            const double r = (double)val[k][e] - vd[e];
+            accN[k] = fma(r, r, accN[k]);
+            accR[k] = fma(z[e], r, accR[k]);
+        }
+    }
+    if (lg == 0) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) z2 = fma(z[e], z[e], z2);
+    }
+}
 
 template <int NP, int LG, bool RAGGED>
 __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a)
@@ -34,6 +101,7 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
 
     const int j = blockIdx.y;
     const int n = a.n, S = a.S;
+    if (a.skip_gram_ok && a.st.gram_ok[j]) return;   // uniform: the other kernel's partition
     int iters_now;
     if (a.st.done[j]) {
         const int buf = a.st.final_buf[j];
@@ -61,62 +129,42 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
     for (int k = 0; k < NP; ++k) { accN[k] = 0.0; accR[k] = 0.0; }
     double t2 = 0.0, z2 = 0.0;
 
+    // Interior tiles first.  Two register sets take turns: the loads of the wavefront's
+    // next tile are issued before the arithmetic of the current one, so that memory requests
+    // are in flight all the time and not only while the wavefront waits; every tile's
+    // arithmetic follows the next tile's loads on a straight path (no join in between), so
+    // the wait before it is for the current tile only.
     const TileRange tr = tile_range<G::kW>(lo, hi);
-    for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
-        const int64_t xu = tr.xa + u * G::kW;
-        const bool interior = (xu >= lo) && (xu + G::kW <= hi);
-        const int64_t x0 = xu + (int64_t)sub * kVec;
-        float val[NP][4];
-        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
-        const float base[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        double vv[4], ss[4];
-        combine_rows<NP, LG, false>(val, base, c, dl, cb, db, vv, ss);
-
-        // the aggregate as the caller will see it: rounded to fp32
-        float vf[4];
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) vf[e] = (float)vv[e];
-        if (lg == 0) {
-            if (interior) {
-                f32x4_u o;
-                o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
-                *reinterpret_cast<f32x4_u *>(a.v + x0) = o;
-            } else {
-#pragma unroll
-                for (int e = 0; e < kVec; ++e) {
-                    const int64_t x = x0 + e;
-                    if (x >= lo && x < hi) a.v[x] = vf[e];
-                }
+    const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
+    if (iw.begin < iw.end) {
+        float va[NP][4], vb[NP][4];
+        int64_t u = iw.begin;
+        bool last_in_b = false;
+        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u * G::kW, lo, hi, true, va);
+        for (;;) {
+            const int64_t u1 = u + tr.stride;
+            if (u1 >= iw.end) break;                 // the last tile is in va
+            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u1 * G::kW, lo, hi, true, vb);
+            fused_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, dl,
+                                     accN, accR, t2, z2);
+            const int64_t u2 = u1 + tr.stride;
+            if (u2 >= iw.end) {                      // the last tile is in vb
+                u = u1;
+                last_in_b = true;
+                break;
             }
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) t2 = fma(ss[e], ss[e], t2);
+            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u2 * G::kW, lo, hi, true, va);
+            fused_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, dl,
+                                     accN, accR, t2, z2);
+            u = u2;
         }
-
-        float zf[4];
-        zhat_block(a.seed, x0 >> 2, zf);
-        double z[4], vd[4];
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) {
-            const int64_t x = x0 + e;
-            z[e] = (interior || (x >= lo && x < hi)) ? (double)zf[e] : 0.0;
-            vd[e] = (double)vf[e];
-        }
-#pragma unroll
-        for (int k = 0; k < NP; ++k) {
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) {
-                forget(val[k][e]);
-                const double r = (double)val[k][e] - vd[e];
-                accN[k] = fma(r, r, accN[k]);
-                accR[k] = fma(z[e], r, accR[k]);
-            }
-        }
-        if (lg == 0) {
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) z2 = fma(z[e], z[e], z2);
-        }
+        if (last_in_b)
+            fused_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, vb, c, dl,
+                                     accN, accR, t2, z2);
+        else
+            fused_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, dl,
+                                     accN, accR, t2, z2);
     }
-
     sum_within_group_all<G::kLanes, NP>(accN);
     sum_within_group_all<G::kLanes, NP>(accR);
     z2 = sum_within_group<G::kLanes>(z2);
@@ -132,6 +180,44 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
         sh[wave][2 * G::kPeers] = z2;
         sh[wave][2 * G::kPeers + 1] = t2;
     }
+    // ... then the at most two edge tiles of the partition (its first and its last), by the
+    // wavefronts that own them, with the guarded body and accumulators of their own: the
+    // main loop's are dead by now, so the guarded body costs the main loop no registers.
+    {
+        double eN[NP], eR[NP], et2 = 0.0, ez2 = 0.0;
+#pragma unroll
+        for (int k = 0; k < NP; ++k) { eN[k] = 0.0; eR[k] = 0.0; }
+        bool any = false;   // wavefront-uniform
+#pragma unroll 1
+        for (int t = 0; t < 2; ++t) {
+            const int64_t u = (t == 0) ? 0 : tr.units - 1;
+            if ((t == 1 && tr.units < 2) || !owns_tile(tr, u)) continue;
+            const int64_t xu = tr.xa + u * G::kW;
+            if (tile_is_interior<G::kW>(xu, lo, hi)) continue;
+            float val[NP][4];
+            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, false, val);
+            fused_rows<NP, LG, false>(a.v, a.seed, lg, sub, xu, lo, hi, val, c, dl, eN, eR, et2,
+                                      ez2);
+            any = true;
+        }
+        if (any) {
+            sum_within_group_all<G::kLanes, NP>(eN);
+            sum_within_group_all<G::kLanes, NP>(eR);
+            ez2 = sum_within_group<G::kLanes>(ez2);
+            et2 = sum_within_group<G::kLanes>(et2);
+            if (sub == 0) {
+#pragma unroll
+                for (int k = 0; k < NP; ++k) {
+                    sh[wave][lg * NP + k] += eN[k];
+                    sh[wave][G::kPeers + lg * NP + k] += eR[k];
+                }
+            }
+            if (lane == 0) {
+                sh[wave][2 * G::kPeers] += ez2;
+                sh[wave][2 * G::kPeers + 1] += et2;
+            }
+        }
+    }
     __syncthreads();
     const int B = gridDim.x;
     // buffer (pass & 1) is free: what the earlier passes stored there has been consumed
@@ -145,6 +231,162 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
         double s = 0.0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) s += sh[w][src];
+        pb[q] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The last pass for partitions the Gram iteration finished and vouches for (gram_ok): the
+// norms ||g_i - v|| and the last step norm are already known from the Gram matrix, so one
+// sweep over the tile gives everything else: v = sum_i c_i g_i (rounded to fp32, written)
+// and, with the same converted values, <zhat, g_i>; <zhat, v> is taken on the rounded v.
+// The workgroup's partial sums go out in the layout of cc_finish_verify_kernel
+// (<zhat, r_i> = <zhat, g_i> - <zhat, v>; workgroup 0 supplies the known norms), so the
+// kernels that follow do not care which of the two ran.
+// ---------------------------------------------------------------------------
+template <int NP, bool INTERIOR>
+__device__ __forceinline__ void project_rows(float *__restrict__ v, uint64_t seed, int sub,
+                                             int64_t xu, int64_t lo, int64_t hi,
+                                             float (&val)[NP][4], const double (&c)[NP],
+                                             double (&accR)[NP], double &zv, double &z2)
+{
+    const int64_t x0 = xu + (int64_t)sub * kVec;
+    float zf[4];
+    zhat_block(seed, x0 >> 2, zf);          // needs no data: runs while the loads travel
+    double z[4], vv[4];
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+        const int64_t x = x0 + e;
+        z[e] = (INTERIOR || (x >= lo && x < hi)) ? (double)zf[e] : 0.0;
+        vv[e] = 0.0;
+    }
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            forget(val[k][e]);              // nothing here moves ahead of the next tile's loads
+            const double gd = (double)val[k][e];
+            vv[e] = fma(c[k], gd, vv[e]);
+            accR[k] = fma(z[e], gd, accR[k]);
+        }
+    }
+    float vf[4];
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) vf[e] = (float)vv[e];
+    if (INTERIOR) {
+        f32x4_u o;
+        o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
+        stream_store(v + x0, o);
+    } else {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            const int64_t x = x0 + e;
+            if (x >= lo && x < hi) v[x] = vf[e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+        zv = fma(z[e], (double)vf[e], zv);
+        z2 = fma(z[e], z[e], z2);
+    }
+}
+
+template <int NP, bool RAGGED>
+__global__ __launch_bounds__(kBlock, 2) void cc_finish_project_kernel(FusedArgs a)
+{
+    using G = Geo<NP, 1>;
+    __shared__ double s_c[kBlock], s_a[kBlock];
+    __shared__ double sh[kWaves][NP + 2];
+
+    const int j = blockIdx.y;
+    const int n = a.n, S = a.S, R = a.st.R;
+    if (!a.st.gram_ok[j]) return;                    // uniform: the other kernel's partition
+    if ((int)threadIdx.x < R) {                      // final state: buffer 0
+        s_c[threadIdx.x] = a.st.coef[(int64_t)j * R + threadIdx.x];
+        s_a[threadIdx.x] = 0.0;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.st.report_buf[j] = 0;
+    __syncthreads();
+
+    const int64_t lo = a.st.off[j], hi = a.st.off[j + 1];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int sub = lane;
+
+    double c[NP], dl[NP], cb, db;
+    fetch_coefficients<NP, 1, RAGGED>(s_c, s_a, n, 0, c, dl, cb, db);
+    double accR[NP];
+#pragma unroll
+    for (int k = 0; k < NP; ++k) accR[k] = 0.0;
+    double zv = 0.0, z2 = 0.0;
+
+    // interior tiles, two register sets taking turns (see cc_finish_verify_kernel) ...
+    const TileRange tr = tile_range<G::kW>(lo, hi);
+    const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
+    if (iw.begin < iw.end) {
+        float va[NP][4], vb[NP][4];
+        int64_t u = iw.begin;
+        bool last_in_b = false;
+        load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u * G::kW, lo, hi, true, va);
+        for (;;) {
+            const int64_t u1 = u + tr.stride;
+            if (u1 >= iw.end) break;                 // the last tile is in va
+            load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u1 * G::kW, lo, hi, true, vb);
+            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
+            const int64_t u2 = u1 + tr.stride;
+            if (u2 >= iw.end) {                      // the last tile is in vb
+                u = u1;
+                last_in_b = true;
+                break;
+            }
+            load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u2 * G::kW, lo, hi, true, va);
+            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, accR, zv, z2);
+            u = u2;
+        }
+        if (last_in_b)
+            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, vb, c, accR, zv, z2);
+        else
+            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
+    }
+    // ... then the partition's first and last tile where they are not interior
+#pragma unroll 1
+    for (int t = 0; t < 2; ++t) {
+        const int64_t u = (t == 0) ? 0 : tr.units - 1;
+        if ((t == 1 && tr.units < 2) || !owns_tile(tr, u)) continue;
+        const int64_t xu = tr.xa + u * G::kW;
+        if (tile_is_interior<G::kW>(xu, lo, hi)) continue;
+        float val[NP][4];
+        load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, xu, lo, hi, false, val);
+        project_rows<NP, false>(a.v, a.seed, sub, xu, lo, hi, val, c, accR, zv, z2);
+    }
+
+    sum_within_group_all<64, NP>(accR);
+    zv = sum_within_group<64>(zv);
+    z2 = sum_within_group<64>(z2);
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < NP; ++k) sh[wave][k] = accR[k];
+        sh[wave][NP] = zv;
+        sh[wave][NP + 1] = z2;
+    }
+    __syncthreads();
+    const int B = gridDim.x;
+    double *__restrict__ pb =
+        a.st.partial + (a.pass & 1) * a.st.partial_stride + ((int64_t)j * B + blockIdx.x) * S;
+    const bool first = blockIdx.x == 0;
+    for (int q = threadIdx.x; q < S; q += kBlock) {
+        double s = 0.0;
+        if (q < n) {
+            s = first ? a.st.gram_n2[(int64_t)j * R + q] : 0.0;
+        } else if (q < 2 * n) {
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) s += sh[w][q - n] - sh[w][NP];
+        } else if (q == 2 * n) {
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) s += sh[w][NP + 1];
+        } else {
+            s = first ? a.st.gram_t2[j] : 0.0;
+        }
         pb[q] = s;
     }
 }

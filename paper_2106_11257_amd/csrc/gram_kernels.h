@@ -123,6 +123,9 @@ struct GramIterArgs {
 // sum |x_k x_l|: 2^-46 (about 130 roundings; the accumulation per lane is a chain of a few
 // hundred fused multiply-adds of exact products, the rest are short fixed-order sums).
 constexpr double kGramUnit = 1.4210854715202004e-14;
+// The Gram iteration vouches for a squared norm whose error bar is below this fraction of
+// it (1e-8 relative on the norm: four orders inside the tolerance of the projections).
+constexpr double kGramVouch = 2e-8;
 
 // Value of lane `k` (a compile-time constant) for every lane: two v_readlane into scalar
 // registers, no LDS traffic.
@@ -261,15 +264,37 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
             else if (!(T - band >= a.eps)) break;                 // cannot tell: hand over
         }
     }
+    // A partition that finished here: the norms at the final v and the norm of the last
+    // update are in Gamma as well.  They are handed to the last pass (which then need not
+    // form a single residual) only if their error bars are far inside the tolerances of
+    // the verification quantities; otherwise the last pass measures them on the data.
+    int ok = 0;
+    double N2f = 0.0, T2f = 0.0;
+    if (dn && it > 0) {
+        const double y = row_dot<N>(row, c);
+        const double qv = row_sum16(c * y);
+        const double Sc = row_sum16(fabs(c) * rt);
+        N2f = fmax(diag - 2.0 * y + qv, 0.0);
+        const double eN2 = kGramUnit * (rt + Sc) * (rt + Sc);
+        const double u = row_dot<N>(row, al);
+        T2f = fmax(row_sum16(al * u), 0.0);
+        const double Sa = row_sum16(fabs(al) * rt);
+        const double eT2 = kGramUnit * Sa * Sa;
+        const bool bad = peer && !(eN2 <= kGramVouch * N2f);
+        ok = !__any(bad) && (eT2 <= kGramVouch * T2f || Sa == 0.0);
+    }
     if (t < R) {
         a.st.coef[(int64_t)j * R + t] = (t < n) ? c : 0.0;
         a.st.delta[(int64_t)j * R + t] = (t < n) ? al : 0.0;
+        a.st.gram_n2[(int64_t)j * R + t] = (t < n) ? N2f : 0.0;
     }
     if (t == 0) {
         a.st.iters[j] = it;
         a.st.done[j] = dn;
         a.st.final_buf[j] = 0;
         a.st.remaining[j] = dn ? 0 : (a.max_iters > it ? a.max_iters - it : 0);
+        a.st.gram_ok[j] = ok;
+        a.st.gram_t2[j] = T2f;
     }
 }
 

@@ -38,6 +38,19 @@ __device__ __forceinline__ f32x4_u stream_load(global_f32x4 p)
 #endif
 }
 
+// The aggregate is written once and not read again by the kernel that writes it.
+#ifndef BTARD_NT_STORES
+#define BTARD_NT_STORES 1
+#endif
+__device__ __forceinline__ void stream_store(float *p, f32x4_u t)
+{
+#if BTARD_NT_STORES
+    __builtin_nontemporal_store(t, reinterpret_cast<f32x4_u *>(p));
+#else
+    *reinterpret_cast<f32x4_u *>(p) = t;
+#endif
+}
+
 // Geometry of one wavefront tile.  A wavefront is cut into LG lane groups of
 // LANES = 64/LG lanes.  Lane group lg owns peers [lg*NP, lg*NP + NP); lane
 // `sub` of every group owns the same 4 consecutive coordinates, so a tile
@@ -78,6 +91,20 @@ __device__ __forceinline__ TileRange tile_range(int64_t lo, int64_t hi)
     return t;
 }
 
+// Whether the tile starting at xu lies wholly inside [lo, hi) (wavefront-uniform).  Only
+// the first and the last tile of a partition can fail this.
+template <int W>
+__device__ __forceinline__ bool tile_is_interior(int64_t xu, int64_t lo, int64_t hi)
+{
+    return (xu >= lo) && (xu + W <= hi);
+}
+
+// Whether this wavefront's walk first, first + stride, ... visits tile u.
+__device__ __forceinline__ bool owns_tile(const TileRange &t, int64_t u)
+{
+    return u >= t.first && (u - t.first) % t.stride == 0;
+}
+
 // One row, 4 coordinates starting at x0, each guarded against [lo, hi).
 __device__ __forceinline__ void load_row4_guarded(const float *__restrict__ row, int64_t x0,
                                                   int64_t lo, int64_t hi, float (&out)[4])
@@ -95,6 +122,66 @@ __device__ __forceinline__ void load_row4_vec(const float *__restrict__ p, float
     out[0] = t.x; out[1] = t.y; out[2] = t.z; out[3] = t.w;
 }
 
+// Walks the NP rows of this lane group over one interior tile, one 128-bit load per row.
+// With one lane group the row base is wavefront-uniform and walks from peer to peer in
+// scalar registers (the saddr form of global_load_dwordx4 with a 32-bit per-lane byte
+// offset); the empty asm pins it there, and, being volatile, keeps the loads in program
+// order.  With several lane groups every group starts at its own first peer and the base
+// is a per-lane address.  Rows beyond n (RAGGED only) re-read the last valid row; their
+// coefficients are zero and their accumulators are ignored.
+template <int NP, int LG, bool RAGGED>
+struct RowCursor {
+    global_bytes row;
+    uint32_t lane_bytes;
+
+    __device__ __forceinline__ void begin(const float *__restrict__ g, int64_t ld, int n, int lg,
+                                          int sub, int64_t xu)
+    {
+        lane_bytes = (uint32_t)sub * (uint32_t)(kVec * sizeof(float));
+        if constexpr (LG == 1) {
+            row = (global_bytes)(g + xu);
+        } else {
+            int i0 = lg * NP;
+            if (RAGGED) i0 = i0 < n ? i0 : n - 1;
+            row = (global_bytes)(g + xu) + ((int64_t)i0 * ld * 4 + lane_bytes);
+        }
+    }
+
+    // row k of the tile (k = 0, 1, ... in this order), then step to the next row
+    __device__ __forceinline__ void load(int k, int64_t ld, int n, int lg, float (&out)[4])
+    {
+        f32x4_u t;
+        if constexpr (LG == 1) {
+            asm volatile("" : "+s"(row));
+            t = stream_load((global_f32x4)(row + lane_bytes));
+            if (!RAGGED || k + 1 < n) row += ld * 4;
+        } else {
+            asm volatile("" : "+v"(row));
+            t = stream_load((global_f32x4)row);
+            if (!RAGGED) row += ld * 4;
+            else row += (lg * NP + k + 1 < n) ? ld * 4 : 0;
+        }
+        out[0] = t.x; out[1] = t.y; out[2] = t.z; out[3] = t.w;
+    }
+};
+
+// The tiles u = begin, begin + stride, ... < end of this wavefront that lie wholly inside
+// the partition: its walk without tile 0 and tile units - 1 where those are edge tiles.
+struct InteriorWalk {
+    int64_t begin, end;
+};
+
+template <int W>
+__device__ __forceinline__ InteriorWalk interior_walk(const TileRange &t, int64_t lo, int64_t hi)
+{
+    InteriorWalk w;
+    w.end = t.units;
+    if (t.units > 0 && !tile_is_interior<W>(t.xa + (t.units - 1) * W, lo, hi)) w.end = t.units - 1;
+    w.begin = t.first;
+    if (t.first == 0 && t.units > 0 && !tile_is_interior<W>(t.xa, lo, hi)) w.begin = t.stride;
+    return w;
+}
+
 // Loads the 4 coordinates [x0, x0+4) of this lane group's NP peers.
 //   interior (wavefront-uniform): the whole tile lies inside [lo, hi): straight-line
 //   128-bit loads, all issued before anything waits on them.
@@ -106,51 +193,53 @@ __device__ __forceinline__ void load_tile(const float *__restrict__ g, int64_t l
                                           bool interior, float (&val)[NP][4])
 {
     if (interior) {
-        // uniform 64-bit row base (SGPRs) + 32-bit per-lane byte offset: the saddr form
-        // of global_load_dwordx4, no per-row address registers
-        const uint32_t lane_bytes = (uint32_t)sub * (kVec * sizeof(float));
+        RowCursor<NP, LG, RAGGED> cur;
+        cur.begin(g, ld, n, lg, sub, xu);
+#pragma unroll
+        for (int k = 0; k < NP; ++k) cur.load(k, ld, n, lg, val[k]);
+    } else {
+        // Edge tile (the first or the last of a partition): the same straight-line shape
+        // with one 32-bit load per coordinate.  A coordinate outside [lo, hi) reads the
+        // nearest one inside instead (lo or hi - 1, both within this tile, so the byte
+        // offset from the tile start stays in [0, 4W)) and is then replaced by zero: no
+        // branches, and no address outside the partition is touched.
+        const int64_t x0 = xu + (int64_t)sub * kVec;
+        uint32_t offs[kVec];
+        bool inside[kVec];
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            const int64_t x = x0 + e;
+            inside[e] = (x >= lo) && (x < hi);
+            const int64_t xc = (x < lo) ? lo : ((x >= hi) ? hi - 1 : x);
+            offs[e] = (uint32_t)(xc - xu) * (uint32_t)sizeof(float);
+        }
         if constexpr (LG == 1) {
-            // The row base walks from peer to peer in scalar registers (row += ld); the
-            // empty asm pins it there, so no per-row address is kept in vector registers.
             global_f32 row = (global_f32)(g + xu);
 #pragma unroll
             for (int k = 0; k < NP; ++k) {
                 asm volatile("" : "+s"(row));
-                const f32x4_u t = stream_load((global_f32x4)((global_bytes)row + lane_bytes));
-                val[k][0] = t.x; val[k][1] = t.y; val[k][2] = t.z; val[k][3] = t.w;
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) {
+                    const float t = *(global_f32)((global_bytes)row + offs[e]);
+                    val[k][e] = inside[e] ? t : 0.0f;
+                }
                 if (!RAGGED || k + 1 < n) row += ld;
             }
         } else {
-            // lane group lg starts at its own first peer; the walk from peer to peer is
-            // the same uniform stride
             int i0 = lg * NP;
             if (RAGGED) i0 = i0 < n ? i0 : n - 1;
-            global_bytes row = (global_bytes)(g + xu) + ((int64_t)i0 * ld * 4 + lane_bytes);
+            global_bytes row = (global_bytes)(g + xu) + (int64_t)i0 * ld * 4;
 #pragma unroll
             for (int k = 0; k < NP; ++k) {
                 asm volatile("" : "+v"(row));
-                const f32x4_u t = stream_load((global_f32x4)row);
-                val[k][0] = t.x; val[k][1] = t.y; val[k][2] = t.z; val[k][3] = t.w;
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) {
+                    const float t = *(global_f32)(row + offs[e]);
+                    val[k][e] = inside[e] ? t : 0.0f;
+                }
                 if (!RAGGED) row += ld * 4;
                 else row += (lg * NP + k + 1 < n) ? ld * 4 : 0;
             }
-        }
-    } else {
-        // edge tile (first or last of a partition): every element guarded
-        const int64_t x0 = xu + (int64_t)sub * kVec;
-        int i0 = lg * NP;
-        if (RAGGED) i0 = i0 < n ? i0 : n - 1;
-        global_f32 row = (global_f32)g + (int64_t)i0 * ld;
-#pragma unroll
-        for (int k = 0; k < NP; ++k) {
-            asm volatile("" : "+v"(row));
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) {
-                const int64_t x = x0 + e;
-                val[k][e] = (x >= lo && x < hi) ? row[x] : 0.0f;
-            }
-            if (!RAGGED) row += ld;
-            else row += (lg * NP + k + 1 < n) ? ld : 0;
         }
     }
 }

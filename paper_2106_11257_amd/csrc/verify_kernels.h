@@ -75,10 +75,83 @@ struct VerifyArgs {
     int32_t S;
 };
 
+// One tile of the verification pass; INTERIOR as in fused_tile: a straight-line body for
+// tiles wholly inside the partition, a guarded one for its first and last tile.
+template <int NP, int LG, bool RAGGED, bool INTERIOR>
+__device__ __forceinline__ void verify_tile(const float *__restrict__ g, int64_t ld, int n,
+                                            const float *__restrict__ v, uint64_t seed, int lg,
+                                            int sub, int64_t xu, int64_t lo, int64_t hi,
+                                            double (&accN)[NP], double (&accR)[NP], double &z2)
+{
+    const int64_t x0 = xu + (int64_t)sub * kVec;               // a multiple of 4
+    float val[NP][4];
+    load_tile<NP, LG, RAGGED>(g, ld, n, lg, sub, xu, lo, hi, INTERIOR, val);
+    float vf[4];
+    if (INTERIOR) load_row4_vec(v + x0, vf);
+    else load_row4_guarded(v, x0, lo, hi, vf);
+
+    float zf[4];
+    zhat_block(seed, x0 >> 2, zf);
+    double z[4], vv[4];
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+        const int64_t x = x0 + e;
+        z[e] = (INTERIOR || (x >= lo && x < hi)) ? (double)zf[e] : 0.0;
+        vv[e] = (double)vf[e];
+    }
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            const double r = (double)val[k][e] - vv[e];
+            accN[k] = fma(r, r, accN[k]);
+            accR[k] = fma(z[e], r, accR[k]);
+        }
+    }
+    if (lg == 0) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) z2 = fma(z[e], z[e], z2);
+    }
+}
+
+// The arithmetic of an interior tile whose rows (val) and slice of v (vf) are already in
+// registers.
+template <int NP, int LG>
+__device__ __forceinline__ void verify_rows(uint64_t seed, int lg, int sub, int64_t xu,
+                                            float (&val)[NP][4], float (&vf)[4],
+                                            double (&accN)[NP], double (&accR)[NP], double &z2)
+{
+    const int64_t x0 = xu + (int64_t)sub * kVec;               // a multiple of 4
+    float zf[4];
+    zhat_block(seed, x0 >> 2, zf);
+    double z[4], vv[4];
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+        z[e] = (double)zf[e];
+        forget(vf[e]);           // no use of the tile moves ahead of the next tile's loads
+        vv[e] = (double)vf[e];
+    }
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            forget(val[k][e]);   // converted here, row by row; also keeps this after the loads
+            const double r = (double)val[k][e] - vv[e];
+            accN[k] = fma(r, r, accN[k]);
+            accR[k] = fma(z[e], r, accR[k]);
+        }
+    }
+    if (lg == 0) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) z2 = fma(z[e], z[e], z2);
+    }
+}
+
 template <int NP, int LG, bool RAGGED>
-__global__ __launch_bounds__(kBlock) void verify_pass_kernel(VerifyArgs a)
+__global__ __launch_bounds__(kBlock, 2) void verify_pass_kernel(VerifyArgs a)
 {
     using G = Geo<NP, LG>;
+    __shared__ double sh[kWaves][2 * G::kPeers + 1];
     const int j = blockIdx.y;
     const int n = a.n, S = a.S;
     const int64_t lo = a.off[j], hi = a.off[j + 1];
@@ -91,54 +164,85 @@ __global__ __launch_bounds__(kBlock) void verify_pass_kernel(VerifyArgs a)
     for (int k = 0; k < NP; ++k) { accN[k] = 0.0; accR[k] = 0.0; }
     double z2 = 0.0;
 
+    // interior tiles first ...
     const TileRange tr = tile_range<G::kW>(lo, hi);
-    for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
-        const int64_t xu = tr.xa + u * G::kW;
-        const bool interior = (xu >= lo) && (xu + G::kW <= hi);   // wavefront-uniform
-        const int64_t x0 = xu + (int64_t)sub * kVec;               // a multiple of 4
-        float val[NP][4];
-        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
-        float vf[4];
-        if (interior) load_row4_vec(a.v + x0, vf);
-        else load_row4_guarded(a.v, x0, lo, hi, vf);
-
-        float zf[4];
-        zhat_block(a.seed, x0 >> 2, zf);
-        double z[4], vv[4];
+    // Two register sets take turns: the loads of the wavefront's next tile are issued
+    // before the arithmetic of the current one, so that memory requests are in flight all
+    // the time and not only while the wavefront waits.
+    const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
+    if (iw.begin < iw.end) {
+        float va[NP][4], vb[NP][4], fa[4], fb[4];
+        int64_t u = iw.begin;
+        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u * G::kW, lo, hi, true, va);
+        load_row4_vec(a.v + tr.xa + u * G::kW + sub * kVec, fa);
+        // In the loop every tile's arithmetic follows the next tile's loads on a straight
+        // path (no join in between), so the wait before it is for the current tile only.
+        for (;;) {
+            const int64_t u1 = u + tr.stride;
+            if (u1 >= iw.end) break;                 // the last tile is in (va, fa)
+            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u1 * G::kW, lo, hi, true, vb);
+            load_row4_vec(a.v + tr.xa + u1 * G::kW + sub * kVec, fb);
+            verify_rows<NP, LG>(a.seed, lg, sub, tr.xa + u * G::kW, va, fa, accN, accR, z2);
+            const int64_t u2 = u1 + tr.stride;
+            if (u2 >= iw.end) {                      // the last tile is in (vb, fb): move it
 #pragma unroll
-        for (int e = 0; e < kVec; ++e) {
-            const int64_t x = x0 + e;
-            z[e] = (interior || (x >= lo && x < hi)) ? (double)zf[e] : 0.0;
-            vv[e] = (double)vf[e];
+                for (int k = 0; k < NP; ++k) {
+#pragma unroll
+                    for (int e = 0; e < kVec; ++e) va[k][e] = vb[k][e];
+                }
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) fa[e] = fb[e];
+                u = u1;
+                break;
+            }
+            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u2 * G::kW, lo, hi, true, va);
+            load_row4_vec(a.v + tr.xa + u2 * G::kW + sub * kVec, fa);
+            verify_rows<NP, LG>(a.seed, lg, sub, tr.xa + u1 * G::kW, vb, fb, accN, accR, z2);
+            u = u2;
         }
+        verify_rows<NP, LG>(a.seed, lg, sub, tr.xa + u * G::kW, va, fa, accN, accR, z2);
+    }
+    sum_within_group_all<G::kLanes, NP>(accN);
+    sum_within_group_all<G::kLanes, NP>(accR);
+    z2 = sum_within_group<G::kLanes>(z2);
+    if (sub == 0) {
 #pragma unroll
         for (int k = 0; k < NP; ++k) {
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) {
-                const double r = (double)val[k][e] - vv[e];
-                accN[k] = fma(r, r, accN[k]);
-                accR[k] = fma(z[e], r, accR[k]);
-            }
-        }
-        if (lg == 0) {
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) z2 = fma(z[e], z[e], z2);
+            sh[wave][lg * NP + k] = accN[k];
+            sh[wave][G::kPeers + lg * NP + k] = accR[k];
         }
     }
-
-    __shared__ double sh[kWaves][2 * G::kPeers + 1];
-#pragma unroll
-    for (int k = 0; k < NP; ++k) {
-        const double sN = sum_within_group<G::kLanes>(accN[k]);
-        const double sR = sum_within_group<G::kLanes>(accR[k]);
-        if (sub == 0) {
-            sh[wave][lg * NP + k] = sN;
-            sh[wave][G::kPeers + lg * NP + k] = sR;
-        }
-    }
+    if (lane == 0) sh[wave][2 * G::kPeers] = z2;
+    // ... then the partition's first and last tile where they are not interior, by the
+    // wavefronts that own them, with accumulators of their own (see cc_finish_verify_kernel)
     {
-        const double s = sum_within_group<G::kLanes>(z2);
-        if (lane == 0) sh[wave][2 * G::kPeers] = s;
+        double eN[NP], eR[NP], ez2 = 0.0;
+#pragma unroll
+        for (int k = 0; k < NP; ++k) { eN[k] = 0.0; eR[k] = 0.0; }
+        bool any = false;   // wavefront-uniform
+#pragma unroll 1
+        for (int t = 0; t < 2; ++t) {
+            const int64_t u = (t == 0) ? 0 : tr.units - 1;
+            if ((t == 1 && tr.units < 2) || !owns_tile(tr, u)) continue;
+            const int64_t xu = tr.xa + u * G::kW;
+            if (tile_is_interior<G::kW>(xu, lo, hi)) continue;
+            verify_tile<NP, LG, RAGGED, false>(a.g, a.ld, n, a.v, a.seed, lg, sub, xu, lo, hi, eN,
+                                               eR, ez2);
+            any = true;
+        }
+        if (any) {
+            sum_within_group_all<G::kLanes, NP>(eN);
+            sum_within_group_all<G::kLanes, NP>(eR);
+            ez2 = sum_within_group<G::kLanes>(ez2);
+            if (sub == 0) {
+#pragma unroll
+                for (int k = 0; k < NP; ++k) {
+                    sh[wave][lg * NP + k] += eN[k];
+                    sh[wave][G::kPeers + lg * NP + k] += eR[k];
+                }
+            }
+            if (lane == 0) sh[wave][2 * G::kPeers] += ez2;
+        }
     }
     __syncthreads();
     const int B = gridDim.x;

@@ -233,7 +233,9 @@ def test_zhat_matches_the_z_spec(dev):
                             (7, 4 * (2 ** 32) - 6, 64), (2 ** 63 + 11, 1315758080 - 300, 300)]:
         got = btard.debug_zhat(seed, x0, count, dev).cpu().numpy().astype(np.float64)
         ref = oracle.z_hat(seed, x0, count)
-        assert np.abs(got - ref).max() <= 2e-6 * max(1.0, np.abs(ref).max())
+        err = np.abs(got - ref).max()
+        say(f"[zhat] seed={seed:#x} x0={x0} max abs error {err:.3e}")
+        assert err <= 2e-6 * max(1.0, np.abs(ref).max())
 
 
 # --------------------------------------------------------------------------
@@ -317,10 +319,14 @@ def test_fused_finish_and_verify_equals_the_two_calls(dev, n, d, P, pad, flags):
     v2, iters2, sn2, out = btard.centered_clip_verify(G, off, tau, eps, M, seed, flags=flags)
     torch.cuda.synchronize()
     assert torch.equal(v, v2) and torch.equal(iters, iters2)
-    np.testing.assert_allclose(sn2.cpu().numpy(), sn.cpu().numpy(), rtol=1e-12, atol=1e-300)
+    # With the Gram formulation the fused call takes the norms and the last step norm from
+    # the Gram matrix (vouched for to 1e-8) instead of measuring them against the rounded v.
+    gram = bool(flags & btard.BTARD_FLAG_GRAM)
+    np.testing.assert_allclose(sn2.cpu().numpy(), sn.cpu().numpy(), rtol=1e-6 if gram else 1e-12,
+                               atol=1e-300)
     for k in ("norms", "weights", "proj", "colsum"):
         a, b = out[k].cpu().numpy(), ref[k].cpu().numpy()
-        assert np.abs(a - b).max() <= 1e-12 * max(np.abs(b).max(), 1e-300), k
+        assert np.abs(a - b).max() <= (1e-7 if gram else 1e-12) * max(np.abs(b).max(), 1e-300), k
     # and with a caller-supplied start vector (served by the two separate passes)
     v0 = torch.zeros(d, device=dev)
     a = btard.centered_clip(G, off, tau, eps, 5, v0=v0)
