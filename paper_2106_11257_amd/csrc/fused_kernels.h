@@ -134,9 +134,19 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
     // are in flight all the time and not only while the wavefront waits; every tile's
     // arithmetic follows the next tile's loads on a straight path (no join in between), so
     // the wait before it is for the current tile only.
+    // (With several lane groups the coefficients live in vector registers and a second
+    // register set does not fit: one set, as many wavefronts as fit.)
     const TileRange tr = tile_range<G::kW>(lo, hi);
     const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
-    if (iw.begin < iw.end) {
+    if constexpr (LG > 1) {
+        for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
+            const int64_t xu = tr.xa + u * G::kW;
+            float val[NP][4];
+            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, true, val);
+            fused_rows<NP, LG, true>(a.v, a.seed, lg, sub, xu, lo, hi, val, c, dl, accN, accR, t2,
+                                     z2);
+        }
+    } else if (iw.begin < iw.end) {
         float va[NP][4], vb[NP][4];
         int64_t u = iw.begin;
         bool last_in_b = false;

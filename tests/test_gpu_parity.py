@@ -300,6 +300,40 @@ def test_gram_path_converging_and_low_noise_cases(dev):
     assert rel_l2(got[0].cpu().numpy(), ref[0].cpu().numpy()) < 1e-6
 
 
+def test_gram_last_pass_without_waiting_for_the_iteration(dev):
+    """The last pass enqueued right behind the Gram iteration (no look at what it left), the
+    look taken afterwards: complete where the iteration finished every partition, and
+    completed by the remaining passes plus a second last pass where it handed over."""
+    F, seed = btard.BTARD_FLAG_GRAM, 0xFEEDC0DE
+    gen = torch.Generator(device=dev); gen.manual_seed(11)
+    mu = torch.randn(20000, generator=gen, device=dev) * 100.0
+    low = mu[None, :] + 1e-4 * torch.randn((12, 20000), generator=gen, device=dev)
+    cases = [(workloads.generic_case(16, 30000, 16, seed=2, device=dev, spread=0.005, outliers=4,
+                                     outlier_scale=3.0), 1.0, 1e-6, 200, False),
+             ((low, workloads.split_offsets(20000, 5)), 1e-3, 1e-6, 60, True)]
+    for (G, off), tau, eps, M, hands_over in cases:
+        p = btard.make_problem(G, off, tau, eps, M, flags=F)
+        btard.cc_begin(p); btard.cc_gram_matrix(p); btard.cc_gram_iterate(p)
+        v, iters, sn, out = btard.cc_finish_verify(p, 0, seed)
+        left = btard.cc_remaining(p)
+        assert (left > 0) == hands_over
+        if left > 0:
+            btard.cc_iterate(p, 0, left)
+            v, iters, sn, out = btard.cc_finish_verify(p, left, seed)
+        torch.cuda.synchronize()
+        Gh = G.cpu().numpy()
+        v_ref, it_ref, sn_ref, _ = oracle.centered_clip(Gh, off, tau, eps, M)
+        assert iters.cpu().tolist() == [int(x) for x in it_ref]
+        for j in range(len(off) - 1):
+            lo, hi = off[j], off[j + 1]
+            assert rel_l2(v.cpu().numpy()[lo:hi], v_ref[lo:hi]) <= 1e-5
+        np.testing.assert_allclose(sn.cpu().numpy(), sn_ref, rtol=1e-4, atol=1e-11)
+        ref = oracle.verify(Gh, off, v.cpu().numpy(), tau, seed)
+        np.testing.assert_allclose(out["norms"].cpu().numpy(), ref["norms"], rtol=1e-6, atol=1e-12)
+        pr = out["proj"].cpu().numpy()
+        assert rel_l2(pr, ref["proj"]) <= 1e-4
+
+
 @pytest.mark.parametrize("cfg,d", [(1, 1 << 16), (2, 400_003), (4, 1 << 20), (5, 1_600_016)])
 def test_gram_path_configs_reduced_length(dev, cfg, d):
     wl = workloads.make_workload(cfg, device=dev, d=d)
