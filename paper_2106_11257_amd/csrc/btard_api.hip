@@ -295,11 +295,19 @@ static bool gram_applies(const btard_cc_problem *p)
            p->max_iters > 0;
 }
 
+// n <= 8: two coordinates per MFMA row block (512-wide tiles), else one (256-wide)
+typedef void (*GramFn)(GramArgs);
+static GramFn gram_kernel(const btard_cc_problem *p)
+{
+    return p->n <= kGramPeers / 2 ? gram_pass_kernel<true> : gram_pass_kernel<false>;
+}
+
 static int gram_blocks(const btard_cc_problem *p)
 {
-    const int resident = resident_blocks(reinterpret_cast<const void *>(gram_pass_kernel));
+    const int resident = resident_blocks(reinterpret_cast<const void *>(gram_kernel(p)));
     if (resident <= 0) return 0;
-    return blocks_per_partition(resident, p->parts, p->offsets_host, 256);
+    return blocks_per_partition(resident, p->parts, p->offsets_host,
+                                p->n <= kGramPeers / 2 ? 512 : 256);
 }
 
 int btard_cc_gram_matrix(const btard_cc_problem *p)
@@ -315,7 +323,7 @@ int btard_cc_gram_matrix(const btard_cc_problem *p)
     ga.g = p->g; ga.ld = p->ldg; ga.n = p->n;
     ga.off = carve_cc(p->workspace, p->n, p->parts).off;
     ga.gpart = reinterpret_cast<double *>(static_cast<char *>(p->workspace) + L.gram);
-    hipLaunchKernelGGL(gram_pass_kernel, dim3(B, p->parts), dim3(kBlock), 0, s, ga);
+    hipLaunchKernelGGL(gram_kernel(p), dim3(B, p->parts), dim3(kBlock), 0, s, ga);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
@@ -378,7 +386,7 @@ int btard_debug_gram(const btard_cc_problem *p, double *gram_out)
     GramArgs ga;
     ga.g = p->g; ga.ld = p->ldg; ga.n = p->n; ga.off = st.off;
     ga.gpart = reinterpret_cast<double *>(static_cast<char *>(p->workspace) + L.gram);
-    hipLaunchKernelGGL(gram_pass_kernel, dim3(B, p->parts), dim3(kBlock), 0, s, ga);
+    hipLaunchKernelGGL(gram_kernel(p), dim3(B, p->parts), dim3(kBlock), 0, s, ga);
     hipLaunchKernelGGL(gram_debug_kernel, dim3(p->parts), dim3(kGramEntries), 0, s, ga.gpart, B,
                        gram_out);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;

@@ -49,17 +49,26 @@ __device__ __forceinline__ int gram_entry(int lane, int r) { return ((lane >> 4)
 // transposing through LDS, and prefetching the next tile, were tried: the kernel stays at
 // the fp64 MFMA issue rate either way -- measured 105 cycles per instruction -- so the
 // simple form is kept.)
+//
+// HALF (n <= 8): the 16 rows of the MFMA block are the n peers at TWO coordinates at once.
+// Lanes p < 8 read peer p in the first 256 coordinates of a 512-wide tile, lanes p >= 8
+// read peer p - 8 in the second 256; the product then holds X1 X1^T and X2 X2^T in its two
+// diagonal 8 x 8 blocks (and X1 X2^T, unused, off the diagonal), whose sum is this tile's
+// contribution to Gamma: half the MFMA instructions per coordinate.
+template <bool HALF>
 __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
 {
-    constexpr int kW = 256;
+    constexpr int kW = HALF ? 512 : 256;
     const int j = blockIdx.y;
     const int n = a.n;
     const int64_t lo = a.off[j], hi = a.off[j + 1];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int p = lane & 15, q = lane >> 4;
-    const bool have = p < n;
-    global_f32 row = (global_f32)a.g + (int64_t)(have ? p : n - 1) * a.ld;
+    const int peer = HALF ? (p & 7) : p;
+    const int shift = (HALF && p >= 8) ? 256 : 0;                // this lane's half of the tile
+    const bool have = peer < n;
+    global_f32 row = (global_f32)a.g + (int64_t)(have ? peer : n - 1) * a.ld + shift;
 
     // four independent accumulators: consecutive MFMAs do not wait for each other
     f64x4 acc[4];
@@ -82,8 +91,8 @@ __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
             for (int s = 0; s < 16; ++s) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int64_t x = xu + 16 * s + 4 * q + e;
-                    val[s][e] = (x >= lo && x < hi) ? row[x] : 0.0f;
+                    const int64_t x = xu + 16 * s + 4 * q + e;    // (row already carries shift)
+                    val[s][e] = (x + shift >= lo && x + shift < hi) ? row[x] : 0.0f;
                 }
             }
         }
@@ -105,8 +114,14 @@ __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
     __syncthreads();
     const int t = threadIdx.x;
     double s = 0.0;
+    if (!HALF) {
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) s += sh[w][t];
+        for (int w = 0; w < kWaves; ++w) s += sh[w][t];
+    } else if ((t >> 4) < 8 && (t & 15) < 8) {
+        // entry (i, k), i, k < 8: the two diagonal blocks added; the rest of the matrix is 0
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) s += sh[w][t] + sh[w][t + 8 * kGramPeers + 8];
+    }
     a.gpart[((int64_t)j * gridDim.x + blockIdx.x) * kGramEntries + t] = s;
 }
 

@@ -242,7 +242,8 @@ def test_zhat_matches_the_z_spec(dev):
 # Gram formulation (BTARD_FLAG_GRAM): same contract as the plain iteration
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("n,d,P,pad", [(3, 1031, 2, 0), (9, 5000, 4, 2), (16, 70001, 16, 0),
-                                       (16, 262147, 3, 5), (1, 300, 2, 1), (12, 7, 3, 0)])
+                                       (16, 262147, 3, 5), (1, 300, 2, 1), (12, 7, 3, 0), (8, 5003, 3, 1),
+                                       (5, 40001, 2, 3)])
 def test_gram_matrix_matches_matmul(dev, n, d, P, pad):
     G, off = workloads.generic_case(n, d, P, seed=31 * n + d, device=dev, ld=d + pad, spread=0.5,
                                     outliers=n // 3)
