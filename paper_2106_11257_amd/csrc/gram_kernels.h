@@ -174,6 +174,33 @@ __device__ __forceinline__ double row_sum16(double x)
     return lane_value<15>(x);
 }
 
+// Up to four sums over the 16 peers at once: the wavefront's four rows of 16 lanes hold the
+// same per-peer data, so row q reduces quantity q (one set of DPP steps for all four).
+__device__ __forceinline__ void row_sum16x4(int q, double a0, double a1, double a2, double a3,
+                                            double &s0, double &s1, double &s2, double &s3)
+{
+    double x = (q == 0) ? a0 : (q == 1) ? a1 : (q == 2) ? a2 : a3;
+    x += row_shift_right<0x111>(x);
+    x += row_shift_right<0x112>(x);
+    x += row_shift_right<0x114>(x);
+    x += row_shift_right<0x118>(x);
+    s0 = lane_value<15>(x);
+    s1 = lane_value<31>(x);
+    s2 = lane_value<47>(x);
+    s3 = lane_value<63>(x);
+}
+
+__device__ __forceinline__ void row_sum16x2(int q, double a0, double a1, double &s0, double &s1)
+{
+    double x = (q == 0) ? a0 : a1;
+    x += row_shift_right<0x111>(x);
+    x += row_shift_right<0x112>(x);
+    x += row_shift_right<0x114>(x);
+    x += row_shift_right<0x118>(x);
+    s0 = lane_value<15>(x);
+    s1 = lane_value<31>(x);
+}
+
 // sum_k row[k] * (value of x in lane k)
 template <int N>
 __device__ __forceinline__ double row_dot(const double (&row)[N], double x)
@@ -223,16 +250,21 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
     const double rt = sqrt(fmax(diag, 0.0));
     const double inv_n = 1.0 / (double)n;     // only used as a factor of error bounds
 
+    const int q = t >> 4;                     // which of the four rows of 16 lanes
     double c = peer ? a.st.coef[(int64_t)j * R + i] : 0.0;
     double al = 0.0;
     int it = a.st.iters[j];
     int dn = a.st.done[j];
     double ev = 0.0;                          // bound on the error put into v so far
 
+    // y = Gamma c, qv = c^T Gamma c and Sc = sum_i |c_i| ||g_i|| travel with c: after an
+    // update a, y += Gamma a (the one matrix-vector product of an iteration), and the two
+    // sums for the new c ride along in the reduction that gives the update's norm.
+    double y = row_dot<N>(row, c);
+    double qv, Sc;
+    row_sum16x2(q, c * y, fabs(c) * rt, qv, Sc);
+
     while (!dn) {                             // wavefront-uniform
-        const double y = row_dot<N>(row, c);
-        const double qv = row_sum16(c * y);
-        const double Sc = row_sum16(fabs(c) * rt);
         // norms, weights and how wrong the weights may be
         const double N2 = fmax(diag - 2.0 * y + qv, 0.0);
         const double eN2 = kGramUnit * (rt + Sc) * (rt + Sc);
@@ -250,23 +282,35 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
                 err_w = rel * fmin(Nn, a.tau) * inv_n;
             }
         }
-        const double W = row_sum16(w);
-        const double ev_new = ev + row_sum16(err_w);
+        double W, E;
+        row_sum16x2(q, w, err_w, W, E);
+        const double ev_new = ev + E;
         // the update this would apply, and its norm sqrt(a^T Gamma a)
         const double an = peer ? (w - W * c) / (double)n : 0.0;
         const double u = row_dot<N>(row, an);
-        const double Tn2 = row_sum16(an * u);
-        const double Sa = row_sum16(fabs(an) * rt);
+        const double cn = c + an;
+        double yn = y + u;
+        double Tn2, Sa, Scn, qvn;
+        row_sum16x4(q, an * u, fabs(an) * rt, fabs(cn) * rt, cn * yn, Tn2, Sa, Scn, qvn);
         const double T = sqrt(fmax(Tn2, 0.0));
         // error budget: the (generously bounded, never discounted) error put into v must
         // stay a small fraction of ||v|| and of the step itself (whose norm is compared
-        // with eps below; the norm that is reported is recomputed from the data at the end)
+        // with eps below)
         const double budget = fmin(0.99e-8 * __builtin_amdgcn_sqrt(fmax(qv, 0.0)), 1e-3 * T);
         if (ev_new > budget) break;                               // hand over before this update
         ev = ev_new;
         al = an;
-        c = c + an;
+        c = cn;
         it = it + 1;
+        if ((it & 7) == 0) {
+            // (y by running sums drifts by a rounding per update: recomputed now and then,
+            // the drift stays a small fraction of the assumed accuracy kGramUnit)
+            yn = row_dot<N>(row, c);
+            row_sum16x2(q, c * yn, fabs(c) * rt, qvn, Scn);
+        }
+        y = yn;
+        qv = qvn;
+        Sc = Scn;
         if (it >= a.max_iters) dn = 1;
         // stopping rule on the update just applied, with its error bar
         if (a.eps > 0.0) {
@@ -286,14 +330,13 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
     int ok = 0;
     double N2f = 0.0, T2f = 0.0;
     if (dn && it > 0) {
-        const double y = row_dot<N>(row, c);
-        const double qv = row_sum16(c * y);
-        const double Sc = row_sum16(fabs(c) * rt);
-        N2f = fmax(diag - 2.0 * y + qv, 0.0);
-        const double eN2 = kGramUnit * (rt + Sc) * (rt + Sc);
-        const double u = row_dot<N>(row, al);
-        T2f = fmax(row_sum16(al * u), 0.0);
-        const double Sa = row_sum16(fabs(al) * rt);
+        const double yf = row_dot<N>(row, c);            // afresh, not the running sums
+        const double uf = row_dot<N>(row, al);
+        double qf, Sf, Tf, Sa;
+        row_sum16x4(q, c * yf, fabs(c) * rt, al * uf, fabs(al) * rt, qf, Sf, Tf, Sa);
+        N2f = fmax(diag - 2.0 * yf + qf, 0.0);
+        const double eN2 = kGramUnit * (rt + Sf) * (rt + Sf);
+        T2f = fmax(Tf, 0.0);
         const double eT2 = kGramUnit * Sa * Sa;
         const bool bad = peer && !(eN2 <= kGramVouch * N2f);
         ok = !__any(bad) && (eT2 <= kGramVouch * T2f || Sa == 0.0);
