@@ -260,7 +260,7 @@ def main() -> int:
             synced = True
         it, agg_bytes, pass_bytes = work_done()
         fb = max(fallback_passes) if fallback_passes else 0
-        last = "cc_finish_project_kernel" if fb == 0 else "cc_finish_verify_kernel"
+        last = "cc_finish_verify_kernel"       # light body where the Gram iteration finished
         kernels = {
             # name: (ms between the HIP events around its launch(es), algorithmic bytes)
             "gram_pass_kernel": (seg[1], slab_bytes),

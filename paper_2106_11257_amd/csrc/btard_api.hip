@@ -149,10 +149,6 @@ const FusedFn kFused[kVariants][2] = {BTARD_F_ROW(4, 1),  BTARD_F_ROW(8, 1),  BT
                                       BTARD_F_ROW(16, 2), BTARD_F_ROW(16, 4), BTARD_F_ROW(16, 8),
                                       BTARD_F_ROW(16, 16)};
 #undef BTARD_F_ROW
-// the Gram formulation's last pass: n <= 16, one lane group  [variant][ragged]
-const FusedFn kProject[3][2] = {{cc_finish_project_kernel<4, false>, cc_finish_project_kernel<4, true>},
-                                {cc_finish_project_kernel<8, false>, cc_finish_project_kernel<8, true>},
-                                {cc_finish_project_kernel<16, false>, cc_finish_project_kernel<16, true>}};
 
 int variant_peers(Variant v)
 {
@@ -281,10 +277,15 @@ int btard_cc_begin(const btard_cc_problem *p)
     if (rc != BTARD_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     CcState st = carve_cc(p->workspace, p->n, p->parts);
-    const int up = upload_offsets(p->offsets_host, p->parts, st.off, s);
-    if (up != BTARD_OK) return up;
-    hipLaunchKernelGGL(cc_init_kernel, dim3(p->parts), dim3(64), 0, s, st, p->n, p->v0 ? 1 : 0,
-                       p->max_iters);
+    const int32_t P = p->parts;
+    for (int32_t first = 0; first < P + 1; first += kOffChunk) {
+        OffChunk chunk;
+        const int32_t count = (P + 1 - first < kOffChunk) ? (P + 1 - first) : kOffChunk;
+        for (int32_t t = 0; t < kOffChunk; ++t)
+            chunk.v[t] = (t < count) ? p->offsets_host[first + t] : 0;
+        hipLaunchKernelGGL(cc_begin_kernel, dim3(count), dim3(kOffChunk), 0, s, st, p->n,
+                           p->v0 ? 1 : 0, p->max_iters, first, count, chunk);
+    }
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
@@ -506,39 +507,25 @@ int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float 
     const FusedFn fn = kFused[var][ragged];
     const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
     if (resident <= 0) return BTARD_ERR_DEVICE;
-    int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
+    const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
     const int Bpass = pass_blocks(p, var, ragged, 0);
     if (Bpass <= 0) return BTARD_ERR_DEVICE;
-    // With the Gram formulation two kernels share the partitions (each leaves at once what
-    // is the other's): the light one takes those the Gram iteration finished and vouches
-    // for.  Both write the same partial-sum layout, so they use one grid width.
-    const bool split = gram_applies(p);
-    FusedFn light = nullptr;
-    if (split) {
-        light = kProject[var][ragged];
-        const int res_l = resident_blocks(reinterpret_cast<const void *>(light));
-        if (res_l <= 0) return BTARD_ERR_DEVICE;
-        const int Bl = blocks_per_partition(res_l, p->parts, p->offsets_host, variant_tile_width(var));
-        if (Bl < B) B = Bl;
-    }
     FusedArgs a;
     a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v = v;
     a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
     a.pass = iterations; a.prev_blocks = Bpass; a.seed = seed; a.S = 2 * p->n + 2;
-    a.skip_gram_ok = split ? 1 : 0;
+    // partitions the Gram iteration finished and vouches for take the kernel's light body
+    a.use_gram_norms = gram_applies(p) ? 1 : 0;
     a.st = carve_cc(p->workspace, p->n, p->parts);
-    if (split) hipLaunchKernelGGL(light, dim3(B, p->parts), dim3(kBlock), 0, s, a);
     hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
 
     const double *part = a.st.partial + (iterations & 1) * a.st.partial_stride;
     VerifyFinishArgs f;
     f.partial = part; f.n = p->n; f.P = p->parts; f.B = B; f.S = a.S; f.tau = (double)p->tau;
     f.norms = norms; f.weights = weights; f.proj = proj; f.colsum = colsum;
+    f.report = 1; f.state_iters = a.st.iters; f.report_buf = a.st.report_buf;
+    f.iters_out = iters; f.step_norm_out = last_step_norm;
     hipLaunchKernelGGL(verify_finish_kernel, dim3(p->parts), dim3(kFinishThreads), 0, s, f);
-    FusedReportArgs r;
-    r.st = a.st; r.partial = part; r.blocks = B; r.S = a.S; r.index = 2 * p->n + 1;
-    r.iters_out = iters; r.step_norm_out = last_step_norm;
-    hipLaunchKernelGGL(fused_report_kernel, dim3(p->parts), dim3(kBlock), 0, s, r);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
@@ -607,6 +594,8 @@ int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
     VerifyFinishArgs f;
     f.partial = st.partial; f.n = n; f.P = parts; f.B = B; f.S = a.S; f.tau = (double)tau;
     f.norms = norms; f.weights = weights; f.proj = proj; f.colsum = colsum;
+    f.report = 0; f.state_iters = nullptr; f.report_buf = nullptr;
+    f.iters_out = nullptr; f.step_norm_out = nullptr;
     hipLaunchKernelGGL(verify_finish_kernel, dim3(parts), dim3(kFinishThreads), 0, s, f);
 
     if (delta) {

@@ -74,18 +74,24 @@ __global__ void upload_offsets_kernel(int64_t *off, int32_t first, int32_t count
     if (t < count) off[first + t] = chunk.v[t];
 }
 
-__global__ void cc_init_kernel(CcState st, int32_t n, int32_t has_v0, int32_t max_iters)
+// One launch per chunk of offsets: workgroup b sets up partition first + b (if there is
+// one: the last chunk entry may be the end offset only), workgroup 0 also stores the chunk.
+__global__ __launch_bounds__(kOffChunk) void cc_begin_kernel(CcState st, int32_t n, int32_t has_v0,
+                                                             int32_t max_iters, int32_t first,
+                                                             int32_t count, OffChunk chunk)
 {
-    const int j = blockIdx.x;
+    const int t = threadIdx.x;
+    if (blockIdx.x == 0 && t < count) const_cast<int64_t *>(st.off)[first + t] = chunk.v[t];
+    const int j = first + blockIdx.x;
     if (j >= st.P) return;
-    for (int q = threadIdx.x; q < st.R; q += blockDim.x) {
+    for (int q = t; q < st.R; q += blockDim.x) {
         double c;
         if (has_v0) c = (q == n) ? 1.0 : 0.0;
         else        c = (q == n) ? 0.0 : 1.0 / (double)n;
         st.coef[(int64_t)j * st.R + q] = c;
         st.delta[(int64_t)j * st.R + q] = 0.0;
     }
-    if (threadIdx.x == 0) {
+    if (t == 0) {
         st.iters[j] = 0;
         st.done[j] = (max_iters <= 0) ? 1 : 0;
         st.final_buf[j] = 0;
@@ -114,7 +120,7 @@ __device__ __forceinline__ bool control_step(const CcState &st, int j, int n, do
     const int R = st.R, P = st.P;
     const int t = threadIdx.x;
     if (pass == 0) {
-        // state buffer 0 as set by cc_init_kernel (or left by the Gram iteration)
+        // state buffer 0 as set by cc_begin_kernel (or left by the Gram iteration)
         if (t < R) {
             s_c[t] = st.coef[(int64_t)j * R + t];
             s_a[t] = st.delta[(int64_t)j * R + t];

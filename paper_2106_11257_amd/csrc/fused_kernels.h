@@ -21,7 +21,7 @@ struct FusedArgs {
     int32_t prev_blocks;
     uint64_t seed;
     int32_t S;               // 2n + 2: n norms^2, n <zhat, r_i>, |zhat|^2, |last update|^2
-    int32_t skip_gram_ok;    // leave partitions with gram_ok set to cc_finish_project_kernel
+    int32_t use_gram_norms;  // partitions with gram_ok set take the light body (project_partition)
     CcState st;
 };
 
@@ -91,6 +91,158 @@ __device__ __forceinline__ void fused_rows(float *__restrict__ v, uint64_t seed,
     }
 }
 
+// ---------------------------------------------------------------------------
+// The last pass for partitions the Gram iteration finished and vouches for (gram_ok): the
+// norms ||g_i - v|| and the last step norm are already known from the Gram matrix, so one
+// sweep over the tile gives everything else: v = sum_i c_i g_i (rounded to fp32, written)
+// and, with the same converted values, <zhat, g_i>; <zhat, v> is taken on the rounded v.
+// The workgroup's partial sums go out in the layout of the general body of
+// cc_finish_verify_kernel (<zhat, r_i> = <zhat, g_i> - <zhat, v>; workgroup 0 supplies the
+// known norms), so the kernel that follows does not care which of the two ran.
+// ---------------------------------------------------------------------------
+template <int NP, bool INTERIOR>
+__device__ __forceinline__ void project_rows(float *__restrict__ v, uint64_t seed, int sub,
+                                             int64_t xu, int64_t lo, int64_t hi,
+                                             float (&val)[NP][4], const double (&c)[NP],
+                                             double (&accR)[NP], double &zv, double &z2)
+{
+    const int64_t x0 = xu + (int64_t)sub * kVec;
+    float zf[4];
+    zhat_block(seed, x0 >> 2, zf);          // needs no data: runs while the loads travel
+    double z[4], vv[4];
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+        const int64_t x = x0 + e;
+        z[e] = (INTERIOR || (x >= lo && x < hi)) ? (double)zf[e] : 0.0;
+        vv[e] = 0.0;
+    }
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            forget(val[k][e]);              // nothing here moves ahead of the next tile's loads
+            const double gd = (double)val[k][e];
+            vv[e] = fma(c[k], gd, vv[e]);
+            accR[k] = fma(z[e], gd, accR[k]);
+        }
+    }
+    float vf[4];
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) vf[e] = (float)vv[e];
+    if (INTERIOR) {
+        f32x4_u o;
+        o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
+        stream_store(v + x0, o);
+    } else {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            const int64_t x = x0 + e;
+            if (x >= lo && x < hi) v[x] = vf[e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+        zv = fma(z[e], (double)vf[e], zv);
+        z2 = fma(z[e], z[e], z2);
+    }
+}
+
+template <int NP, bool RAGGED>
+__device__ __forceinline__ void project_partition(const FusedArgs &a, int j, double *s_c,
+                                                  double *s_a, double (&sh)[kWaves][2 * NP + 2])
+{
+    using G = Geo<NP, 1>;
+    const int n = a.n, S = a.S, R = a.st.R;
+    if ((int)threadIdx.x < R) {                      // final state: buffer 0
+        s_c[threadIdx.x] = a.st.coef[(int64_t)j * R + threadIdx.x];
+        s_a[threadIdx.x] = 0.0;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.st.report_buf[j] = 0;
+    __syncthreads();
+
+    const int64_t lo = a.st.off[j], hi = a.st.off[j + 1];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int sub = lane;
+
+    double c[NP], dl[NP], cb, db;
+    fetch_coefficients<NP, 1, RAGGED>(s_c, s_a, n, 0, c, dl, cb, db);
+    double accR[NP];
+#pragma unroll
+    for (int k = 0; k < NP; ++k) accR[k] = 0.0;
+    double zv = 0.0, z2 = 0.0;
+
+    // interior tiles, two register sets taking turns (see cc_finish_verify_kernel) ...
+    const TileRange tr = tile_range<G::kW>(lo, hi);
+    const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
+    if (iw.begin < iw.end) {
+        float va[NP][4], vb[NP][4];
+        int64_t u = iw.begin;
+        bool last_in_b = false;
+        load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u * G::kW, lo, hi, true, va);
+        for (;;) {
+            const int64_t u1 = u + tr.stride;
+            if (u1 >= iw.end) break;                 // the last tile is in va
+            load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u1 * G::kW, lo, hi, true, vb);
+            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
+            const int64_t u2 = u1 + tr.stride;
+            if (u2 >= iw.end) {                      // the last tile is in vb
+                u = u1;
+                last_in_b = true;
+                break;
+            }
+            load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u2 * G::kW, lo, hi, true, va);
+            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, accR, zv, z2);
+            u = u2;
+        }
+        if (last_in_b)
+            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, vb, c, accR, zv, z2);
+        else
+            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
+    }
+    // ... then the partition's first and last tile where they are not interior
+#pragma unroll 1
+    for (int t = 0; t < 2; ++t) {
+        const int64_t u = (t == 0) ? 0 : tr.units - 1;
+        if ((t == 1 && tr.units < 2) || !owns_tile(tr, u)) continue;
+        const int64_t xu = tr.xa + u * G::kW;
+        if (tile_is_interior<G::kW>(xu, lo, hi)) continue;
+        float val[NP][4];
+        load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, xu, lo, hi, false, val);
+        project_rows<NP, false>(a.v, a.seed, sub, xu, lo, hi, val, c, accR, zv, z2);
+    }
+
+    sum_within_group_all<64, NP>(accR);
+    zv = sum_within_group<64>(zv);
+    z2 = sum_within_group<64>(z2);
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < NP; ++k) sh[wave][k] = accR[k];
+        sh[wave][NP] = zv;
+        sh[wave][NP + 1] = z2;
+    }
+    __syncthreads();
+    const int B = gridDim.x;
+    double *__restrict__ pb =
+        a.st.partial + (a.pass & 1) * a.st.partial_stride + ((int64_t)j * B + blockIdx.x) * S;
+    const bool first = blockIdx.x == 0;
+    for (int q = threadIdx.x; q < S; q += kBlock) {
+        double s = 0.0;
+        if (q < n) {
+            s = first ? a.st.gram_n2[(int64_t)j * R + q] : 0.0;
+        } else if (q < 2 * n) {
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) s += sh[w][q - n] - sh[w][NP];
+        } else if (q == 2 * n) {
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) s += sh[w][NP + 1];
+        } else {
+            s = first ? a.st.gram_t2[j] : 0.0;
+        }
+        pb[q] = s;
+    }
+}
+
 template <int NP, int LG, bool RAGGED>
 __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a)
 {
@@ -101,7 +253,13 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
 
     const int j = blockIdx.y;
     const int n = a.n, S = a.S;
-    if (a.skip_gram_ok && a.st.gram_ok[j]) return;   // uniform: the other kernel's partition
+    if constexpr (LG == 1) {
+        // (the Gram formulation serves n <= 16, which is one lane group)
+        if (a.use_gram_norms && a.st.gram_ok[j]) {   // uniform
+            project_partition<NP, RAGGED>(a, j, s_c, s_a, sh);
+            return;
+        }
+    }
     int iters_now;
     if (a.st.done[j]) {
         const int buf = a.st.final_buf[j];
@@ -242,184 +400,6 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) s += sh[w][src];
         pb[q] = s;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// The last pass for partitions the Gram iteration finished and vouches for (gram_ok): the
-// norms ||g_i - v|| and the last step norm are already known from the Gram matrix, so one
-// sweep over the tile gives everything else: v = sum_i c_i g_i (rounded to fp32, written)
-// and, with the same converted values, <zhat, g_i>; <zhat, v> is taken on the rounded v.
-// The workgroup's partial sums go out in the layout of cc_finish_verify_kernel
-// (<zhat, r_i> = <zhat, g_i> - <zhat, v>; workgroup 0 supplies the known norms), so the
-// kernels that follow do not care which of the two ran.
-// ---------------------------------------------------------------------------
-template <int NP, bool INTERIOR>
-__device__ __forceinline__ void project_rows(float *__restrict__ v, uint64_t seed, int sub,
-                                             int64_t xu, int64_t lo, int64_t hi,
-                                             float (&val)[NP][4], const double (&c)[NP],
-                                             double (&accR)[NP], double &zv, double &z2)
-{
-    const int64_t x0 = xu + (int64_t)sub * kVec;
-    float zf[4];
-    zhat_block(seed, x0 >> 2, zf);          // needs no data: runs while the loads travel
-    double z[4], vv[4];
-#pragma unroll
-    for (int e = 0; e < kVec; ++e) {
-        const int64_t x = x0 + e;
-        z[e] = (INTERIOR || (x >= lo && x < hi)) ? (double)zf[e] : 0.0;
-        vv[e] = 0.0;
-    }
-#pragma unroll
-    for (int k = 0; k < NP; ++k) {
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) {
-            forget(val[k][e]);              // nothing here moves ahead of the next tile's loads
-            const double gd = (double)val[k][e];
-            vv[e] = fma(c[k], gd, vv[e]);
-            accR[k] = fma(z[e], gd, accR[k]);
-        }
-    }
-    float vf[4];
-#pragma unroll
-    for (int e = 0; e < kVec; ++e) vf[e] = (float)vv[e];
-    if (INTERIOR) {
-        f32x4_u o;
-        o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
-        stream_store(v + x0, o);
-    } else {
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) {
-            const int64_t x = x0 + e;
-            if (x >= lo && x < hi) v[x] = vf[e];
-        }
-    }
-#pragma unroll
-    for (int e = 0; e < kVec; ++e) {
-        zv = fma(z[e], (double)vf[e], zv);
-        z2 = fma(z[e], z[e], z2);
-    }
-}
-
-template <int NP, bool RAGGED>
-__global__ __launch_bounds__(kBlock, 2) void cc_finish_project_kernel(FusedArgs a)
-{
-    using G = Geo<NP, 1>;
-    __shared__ double s_c[kBlock], s_a[kBlock];
-    __shared__ double sh[kWaves][NP + 2];
-
-    const int j = blockIdx.y;
-    const int n = a.n, S = a.S, R = a.st.R;
-    if (!a.st.gram_ok[j]) return;                    // uniform: the other kernel's partition
-    if ((int)threadIdx.x < R) {                      // final state: buffer 0
-        s_c[threadIdx.x] = a.st.coef[(int64_t)j * R + threadIdx.x];
-        s_a[threadIdx.x] = 0.0;
-    }
-    if (blockIdx.x == 0 && threadIdx.x == 0) a.st.report_buf[j] = 0;
-    __syncthreads();
-
-    const int64_t lo = a.st.off[j], hi = a.st.off[j + 1];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int sub = lane;
-
-    double c[NP], dl[NP], cb, db;
-    fetch_coefficients<NP, 1, RAGGED>(s_c, s_a, n, 0, c, dl, cb, db);
-    double accR[NP];
-#pragma unroll
-    for (int k = 0; k < NP; ++k) accR[k] = 0.0;
-    double zv = 0.0, z2 = 0.0;
-
-    // interior tiles, two register sets taking turns (see cc_finish_verify_kernel) ...
-    const TileRange tr = tile_range<G::kW>(lo, hi);
-    const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
-    if (iw.begin < iw.end) {
-        float va[NP][4], vb[NP][4];
-        int64_t u = iw.begin;
-        bool last_in_b = false;
-        load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u * G::kW, lo, hi, true, va);
-        for (;;) {
-            const int64_t u1 = u + tr.stride;
-            if (u1 >= iw.end) break;                 // the last tile is in va
-            load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u1 * G::kW, lo, hi, true, vb);
-            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
-            const int64_t u2 = u1 + tr.stride;
-            if (u2 >= iw.end) {                      // the last tile is in vb
-                u = u1;
-                last_in_b = true;
-                break;
-            }
-            load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u2 * G::kW, lo, hi, true, va);
-            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, accR, zv, z2);
-            u = u2;
-        }
-        if (last_in_b)
-            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, vb, c, accR, zv, z2);
-        else
-            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
-    }
-    // ... then the partition's first and last tile where they are not interior
-#pragma unroll 1
-    for (int t = 0; t < 2; ++t) {
-        const int64_t u = (t == 0) ? 0 : tr.units - 1;
-        if ((t == 1 && tr.units < 2) || !owns_tile(tr, u)) continue;
-        const int64_t xu = tr.xa + u * G::kW;
-        if (tile_is_interior<G::kW>(xu, lo, hi)) continue;
-        float val[NP][4];
-        load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, xu, lo, hi, false, val);
-        project_rows<NP, false>(a.v, a.seed, sub, xu, lo, hi, val, c, accR, zv, z2);
-    }
-
-    sum_within_group_all<64, NP>(accR);
-    zv = sum_within_group<64>(zv);
-    z2 = sum_within_group<64>(z2);
-    if (lane == 0) {
-#pragma unroll
-        for (int k = 0; k < NP; ++k) sh[wave][k] = accR[k];
-        sh[wave][NP] = zv;
-        sh[wave][NP + 1] = z2;
-    }
-    __syncthreads();
-    const int B = gridDim.x;
-    double *__restrict__ pb =
-        a.st.partial + (a.pass & 1) * a.st.partial_stride + ((int64_t)j * B + blockIdx.x) * S;
-    const bool first = blockIdx.x == 0;
-    for (int q = threadIdx.x; q < S; q += kBlock) {
-        double s = 0.0;
-        if (q < n) {
-            s = first ? a.st.gram_n2[(int64_t)j * R + q] : 0.0;
-        } else if (q < 2 * n) {
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) s += sh[w][q - n] - sh[w][NP];
-        } else if (q == 2 * n) {
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) s += sh[w][NP + 1];
-        } else {
-            s = first ? a.st.gram_t2[j] : 0.0;
-        }
-        pb[q] = s;
-    }
-}
-
-// iters and ||last applied update|| after cc_finish_verify_kernel
-struct FusedReportArgs {
-    CcState st;
-    const double *partial;   // [P][blocks][S]
-    int32_t blocks, S, index;
-    int32_t *iters_out;
-    double *step_norm_out;   // may be null
-};
-
-__global__ __launch_bounds__(kBlock) void fused_report_kernel(FusedReportArgs a)
-{
-    __shared__ double s_red[kBlock];
-    const int j = blockIdx.x;
-    const double *pj = a.partial + (int64_t)j * a.blocks * a.S + a.index;
-    const double tot = reduce_partials<kBlock>(pj, a.blocks, a.S, 1, s_red);
-    if (threadIdx.x == 0) {
-        const int it = a.st.iters[a.st.report_buf[j] * a.st.P + j];
-        a.iters_out[j] = it;
-        if (a.step_norm_out) a.step_norm_out[j] = (it > 0) ? sqrt(tot) : 0.0;
     }
 }
 

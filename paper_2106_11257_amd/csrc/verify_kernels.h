@@ -264,6 +264,12 @@ struct VerifyFinishArgs {
     int32_t n, P, B, S;
     double tau;
     double *norms, *weights, *proj, *colsum;   // colsum may be null
+    // after the fused last pass (S = 2n + 2) also: iters and ||last applied update||
+    int32_t report;
+    const int32_t *state_iters;                // [2][P]
+    const int32_t *report_buf;                 // [P]
+    int32_t *iters_out;
+    double *step_norm_out;                     // may be null
 };
 
 // One workgroup per partition.  |zhat|^2 is summed over every partition's
@@ -288,11 +294,18 @@ __global__ __launch_bounds__(kFinishThreads) void verify_finish_kernel(VerifyFin
     const double Z = sqrt(s_red[0]);
 
     // quantity q < n: norm^2 of peer q; n <= q < 2n: <zhat, r> of peer q - n
-    const double tot = reduce_partials<kFinishThreads>(a.partial + (int64_t)j * B * S, B, S, 2 * n,
+    // (with report: all S = 2n + 2 quantities, the last being ||last applied update||^2)
+    const int Q = a.report ? S : 2 * n;
+    const double tot = reduce_partials<kFinishThreads>(a.partial + (int64_t)j * B * S, B, S, Q,
                                                        s_red);
     __syncthreads();
-    if (t < 2 * n) s_red[t] = tot;
+    if (t < Q) s_red[t] = tot;
     __syncthreads();
+    if (a.report && t == 0) {
+        const int it = a.state_iters[a.report_buf[j] * P + j];
+        a.iters_out[j] = it;
+        if (a.step_norm_out) a.step_norm_out[j] = (it > 0) ? sqrt(s_red[2 * n + 1]) : 0.0;
+    }
     if (t < n) {
         const double N = sqrt(s_red[t]);
         const double Rr = s_red[n + t];
