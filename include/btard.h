@@ -122,7 +122,13 @@ int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
  *                     in the state at which btard_cc_iterate must take over
  *   btard_cc_remaining (optional) synchronises the stream and returns an upper
  *                     bound on the iterations the partitions that have not
- *                     stopped still need (0: btard_cc_iterate can be skipped)
+ *                     stopped still need (0: btard_cc_iterate can be skipped).
+ *                     It may also be asked AFTER a finish call that was enqueued
+ *                     right behind btard_cc_gram with iterations = 0: if it
+ *                     returns 0 that finish was complete; otherwise
+ *                     btard_cc_iterate(0, remaining) and a second finish call
+ *                     complete the run (the state is kept).  That way nothing
+ *                     waits for the device inside the run.
  *   btard_cc_iterate  enqueues iterations first_iteration .. first_iteration +
  *                     count - 1 of eq. (CenteredClip) (one pass over the n x d
  *                     matrix each) on every partition that has not stopped;
@@ -205,6 +211,10 @@ int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
  * delta = NULL) return, with the last pass of the one and the pass of the other
  * merged into a single read of g (the projections are taken against v as it is
  * written, rounded to fp32).  Arguments as in those two calls.
+ * With BTARD_FLAG_GRAM, for partitions the Gram iteration finished, norms and
+ * last_step_norm are those it derives from the Gram matrix whenever their error
+ * bars are below 1e-8 relative (they then differ from norms measured against the
+ * rounded v by less than that); otherwise they are measured on the data.
  */
 int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d,
                                const int64_t *offsets_host, int32_t parts,
