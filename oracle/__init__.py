@@ -8,6 +8,7 @@ from .oracle import (  # noqa: F401
     centered_clip,
     num_threads,
     philox4x32_10,
+    preclip_scales,
     split,
     verify,
     z_hat,

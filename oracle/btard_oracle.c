@@ -16,6 +16,8 @@
  *                       iteration cap M of App. I.1
  *   - Delta, norm, w, s: Alg. 1 lines 8-9; Alg. 6 (BTARD) lines 8-12; eq. (2)
  *   - column check:     Alg. 1 line 16; Alg. 6 Verification 2
+ *   - pre-clipping:     App. E.3, Alg. 9 (BTARD-Clipped-SGD) line 3 and the
+ *                       paragraph after the algorithm (per-partition clipping)
  *   - GetRandomVector:  Alg. 6 line 6 and the paragraph after it (a unit vector,
  *                       uniform on the sphere, derived from the scalar seed r by
  *                       "any standard" generator) -- the concrete generator is
@@ -86,15 +88,19 @@ int oracle_split(int64_t d, int32_t parts, int64_t *off)
 /* A partition whose residual norm is not finite gets iters = -1.            */
 /* trace (optional) receives ||step|| of every applied update, M per part.   */
 /* ------------------------------------------------------------------------ */
+/* srow (optional): n factors; row i of this partition is srow[i] * G[i][.]  */
+/* (the pre-clipped gradients of BTARD-Clipped-SGD), else the rows as given. */
 static void centered_clip_partition(const float *G, int64_t ld, int32_t n,
                                     int64_t lo, int64_t hi, double tau,
                                     double eps, int32_t M, const double *v0,
-                                    double *v, int32_t *iters,
+                                    const double *srow, double *v, int32_t *iters,
                                     double *step_norm, double *trace)
 {
     const int64_t dj = hi - lo;
     double *step = (double *)malloc(sizeof(double) * (size_t)(dj > 0 ? dj : 1));
     double *w = (double *)malloc(sizeof(double) * (size_t)n);
+    double *sc = (double *)malloc(sizeof(double) * (size_t)n);
+    for (int32_t i = 0; i < n; ++i) sc[i] = srow ? srow[i] : 1.0;
 
     /* v^0 */
     if (v0) {
@@ -103,7 +109,7 @@ static void centered_clip_partition(const float *G, int64_t ld, int32_t n,
 #pragma omp parallel for schedule(static)
         for (int64_t x = lo; x < hi; ++x) {
             double sum = 0.0;
-            for (int32_t i = 0; i < n; ++i) sum += (double)G[i * ld + x];
+            for (int32_t i = 0; i < n; ++i) sum += sc[i] * (double)G[i * ld + x];
             v[x] = sum / (double)n;
         }
     }
@@ -115,10 +121,11 @@ static void centered_clip_partition(const float *G, int64_t ld, int32_t n,
         /* norms ||g_i - v^l|| and clip weights min{1, tau/norm} */
         for (int32_t i = 0; i < n; ++i) {
             const float *gi = G + i * ld;
+            const double si = sc[i];
             double N2 = 0.0;
 #pragma omp parallel for schedule(static) reduction(+ : N2)
             for (int64_t x = lo; x < hi; ++x) {
-                double r = (double)gi[x] - v[x];
+                double r = si * (double)gi[x] - v[x];
                 N2 += r * r;
             }
             double N = sqrt(N2);
@@ -133,7 +140,7 @@ static void centered_clip_partition(const float *G, int64_t ld, int32_t n,
         for (int64_t x = lo; x < hi; ++x) {
             double sum = 0.0;
             for (int32_t i = 0; i < n; ++i)
-                sum += w[i] * ((double)G[i * ld + x] - v[x]);
+                sum += w[i] * (sc[i] * (double)G[i * ld + x] - v[x]);
             step[x - lo] = sum / (double)n;
             T2 += step[x - lo] * step[x - lo];
         }
@@ -149,28 +156,74 @@ static void centered_clip_partition(const float *G, int64_t ld, int32_t n,
     if (step_norm) *step_norm = T;
     free(step);
     free(w);
+    free(sc);
 }
 
 /* All partitions, independently (Alg. 2: each aggregator runs its own
  * CenteredClip on its own partition).  off[0..P] ascending, off[0] >= 0,
  * off[P] <= ld.  v0 (fp64, indexed like v) may be NULL.  trace may be NULL or
  * P*M doubles (row j = partition j).  Returns 0, or -1 on bad arguments. */
-int oracle_centered_clip(const float *G, int64_t ld, int32_t n,
-                         const int64_t *off, int32_t P, double tau, double eps,
-                         int32_t M, const double *v0, double *v,
-                         int32_t *iters, double *step_norm, double *trace)
+/* scale (optional): n x P row-major factors alpha_ij: CenteredClip then runs on
+ * the rows alpha_ij * g_i[j] (App. E.3, Alg. 9: BTARD-Clipped-SGD hands the
+ * pre-clipped gradients to BTARD). */
+int oracle_centered_clip_scaled(const float *G, int64_t ld, int32_t n,
+                                const int64_t *off, int32_t P, double tau, double eps,
+                                int32_t M, const double *v0, const double *scale,
+                                double *v, int32_t *iters, double *step_norm,
+                                double *trace)
 {
     if (!G || n <= 0 || !off || P <= 0 || !v || !iters || M < 0 || !(tau > 0.0) ||
         !(eps >= 0.0))
         return -1;
     for (int32_t j = 0; j < P; ++j)
         if (off[j] > off[j + 1] || off[j] < 0 || off[j + 1] > ld) return -1;
+    double *srow = (double *)malloc(sizeof(double) * (size_t)n);
     for (int32_t j = 0; j < P; ++j) {
         if (trace)
             for (int32_t l = 0; l < M; ++l) trace[(int64_t)j * M + l] = -1.0;
-        centered_clip_partition(G, ld, n, off[j], off[j + 1], tau, eps, M, v0, v,
-                                &iters[j], step_norm ? &step_norm[j] : NULL,
+        if (scale)
+            for (int32_t i = 0; i < n; ++i) srow[i] = scale[(int64_t)i * P + j];
+        centered_clip_partition(G, ld, n, off[j], off[j + 1], tau, eps, M, v0,
+                                scale ? srow : NULL, v, &iters[j],
+                                step_norm ? &step_norm[j] : NULL,
                                 trace ? trace + (int64_t)j * M : NULL);
+    }
+    free(srow);
+    return 0;
+}
+
+int oracle_centered_clip(const float *G, int64_t ld, int32_t n,
+                         const int64_t *off, int32_t P, double tau, double eps,
+                         int32_t M, const double *v0, double *v,
+                         int32_t *iters, double *step_norm, double *trace)
+{
+    return oracle_centered_clip_scaled(G, ld, n, off, P, tau, eps, M, v0, NULL, v, iters,
+                                       step_norm, trace);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Pre-clipping of BTARD-Clipped-SGD (App. E.3, Alg. 9 line 3 and the text   */
+/* after it): every peer clips each PARTITION of its gradient to radius      */
+/* lambda:  g~_i(l) = min{1, lambda / ||g_i(l)||_2} g_i(l).  This returns the */
+/* factors alpha_il (n x P row-major; 1 where the norm is <= lambda, also at  */
+/* norm 0) and, optionally, the norms ||g_i(l)||.                            */
+/* ------------------------------------------------------------------------ */
+int oracle_preclip_scales(const float *G, int64_t ld, int32_t n, const int64_t *off,
+                          int32_t P, double lambda, double *alpha, double *norms)
+{
+    if (!G || n <= 0 || !off || P <= 0 || !alpha || !(lambda > 0.0)) return -1;
+    for (int32_t j = 0; j < P; ++j) {
+        const int64_t lo = off[j], hi = off[j + 1];
+        if (lo > hi || lo < 0 || hi > ld) return -1;
+        for (int32_t i = 0; i < n; ++i) {
+            const float *gi = G + i * ld;
+            double N2 = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : N2)
+            for (int64_t x = lo; x < hi; ++x) N2 += (double)gi[x] * (double)gi[x];
+            const double N = sqrt(N2);
+            alpha[(int64_t)i * P + j] = (N <= lambda) ? 1.0 : lambda / N;
+            if (norms) norms[(int64_t)i * P + j] = N;
+        }
     }
     return 0;
 }
@@ -280,10 +333,28 @@ double oracle_z_norm(uint64_t seed, int64_t d)
 /* znorm = oracle_z_norm(seed, d_total).  Outputs are row-major n x P;       */
 /* delta (optional) is n x ldd fp64.                                          */
 /* ------------------------------------------------------------------------ */
+int oracle_verify_scaled(const float *G, int64_t ld, int32_t n, const int64_t *off,
+                         int32_t P, const double *v, double tau, uint64_t seed,
+                         int64_t x_base, double znorm, const double *scale,
+                         double *norms, double *weights, double *proj, double *colsum,
+                         double *delta, int64_t ldd);
+
 int oracle_verify(const float *G, int64_t ld, int32_t n, const int64_t *off,
                   int32_t P, const double *v, double tau, uint64_t seed,
                   int64_t x_base, double znorm, double *norms, double *weights,
                   double *proj, double *colsum, double *delta, int64_t ldd)
+{
+    return oracle_verify_scaled(G, ld, n, off, P, v, tau, seed, x_base, znorm, NULL, norms,
+                                weights, proj, colsum, delta, ldd);
+}
+
+/* scale (optional) as in oracle_centered_clip_scaled: the quantities of the
+ * rows alpha_ij * g_i[j]. */
+int oracle_verify_scaled(const float *G, int64_t ld, int32_t n, const int64_t *off,
+                         int32_t P, const double *v, double tau, uint64_t seed,
+                         int64_t x_base, double znorm, const double *scale,
+                         double *norms, double *weights, double *proj, double *colsum,
+                         double *delta, int64_t ldd)
 {
     if (!G || n <= 0 || !off || P <= 0 || !v || !(tau > 0.0) || !(znorm > 0.0) ||
         !norms || !weights || !proj)
@@ -297,10 +368,11 @@ int oracle_verify(const float *G, int64_t ld, int32_t n, const int64_t *off,
         double cs = 0.0;
         for (int32_t i = 0; i < n; ++i) {
             const float *gi = G + i * ld;
+            const double si = scale ? scale[(int64_t)i * P + j] : 1.0;
             double N2 = 0.0, R = 0.0;
 #pragma omp parallel for schedule(static) reduction(+ : N2, R)
             for (int64_t x = lo; x < hi; ++x) {
-                double r = (double)gi[x] - v[x];
+                double r = si * (double)gi[x] - v[x];
                 N2 += r * r;
                 R += zj[x - lo] * r;
             }
@@ -314,7 +386,7 @@ int oracle_verify(const float *G, int64_t ld, int32_t n, const int64_t *off,
                 double *di = delta + i * ldd;
 #pragma omp parallel for schedule(static)
                 for (int64_t x = lo; x < hi; ++x)
-                    di[x] = w * ((double)gi[x] - v[x]);
+                    di[x] = w * (si * (double)gi[x] - v[x]);
             }
         }
         free(zj);

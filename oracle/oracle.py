@@ -44,6 +44,20 @@ def _load():
         c.c_double, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_void_p]
     lib.oracle_centered_clip.restype = c.c_int
+    lib.oracle_centered_clip_scaled.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, P(c.c_int64), c.c_int32, c.c_double,
+        c.c_double, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p]
+    lib.oracle_centered_clip_scaled.restype = c.c_int
+    lib.oracle_preclip_scales.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, P(c.c_int64), c.c_int32, c.c_double, c.c_void_p,
+        c.c_void_p]
+    lib.oracle_preclip_scales.restype = c.c_int
+    lib.oracle_verify_scaled.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, P(c.c_int64), c.c_int32, c.c_void_p,
+        c.c_double, c.c_uint64, c.c_int64, c.c_double, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64]
+    lib.oracle_verify_scaled.restype = c.c_int
     lib.oracle_philox4x32_10.argtypes = [P(c.c_uint32), P(c.c_uint32), P(c.c_uint32)]
     lib.oracle_philox4x32_10.restype = None
     lib.oracle_z_uniforms.argtypes = [c.c_uint64, c.c_int64, c.c_int64, c.c_void_p]
@@ -84,9 +98,25 @@ def split(d: int, parts: int) -> np.ndarray:
     return np.array(off[:], dtype=np.int64)
 
 
+def preclip_scales(G, off, lam: float):
+    """Pre-clipping factors of BTARD-Clipped-SGD: (alpha [n, P], norms [n, P])."""
+    G = _as_G(G)
+    n, _ = G.shape
+    ld = G.strides[0] // 4 if n > 1 else G.shape[1]
+    Pn = len(off) - 1
+    alpha = np.zeros((n, Pn)); norms = np.zeros((n, Pn))
+    rc = _load().oracle_preclip_scales(G.ctypes.data, ld, n, _offsets(off), Pn, float(lam),
+                                       alpha.ctypes.data, norms.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_preclip_scales: bad arguments")
+    return alpha, norms
+
+
 def centered_clip(G, off, tau: float, eps: float, max_iters: int,
-                  v0: Optional[np.ndarray] = None, want_trace: bool = False):
-    """Returns (v[fp64, ld], iters[int32, P], step_norm[fp64, P], trace|None)."""
+                  v0: Optional[np.ndarray] = None, want_trace: bool = False,
+                  scale: Optional[np.ndarray] = None):
+    """Returns (v[fp64, ld], iters[int32, P], step_norm[fp64, P], trace|None).
+    scale (optional, [n, P]): run on the rows scale[i, j] * G[i, partition j]."""
     G = _as_G(G)
     n, _ = G.shape
     ld = G.strides[0] // 4 if n > 1 else G.shape[1]
@@ -101,9 +131,14 @@ def centered_clip(G, off, tau: float, eps: float, max_iters: int,
         v0 = np.ascontiguousarray(v0, dtype=np.float64)
         assert v0.shape[0] >= width
         v0p = v0.ctypes.data
-    rc = _load().oracle_centered_clip(
+    sp = None
+    if scale is not None:
+        scale = np.ascontiguousarray(scale, dtype=np.float64)
+        assert scale.shape == (n, Pn)
+        sp = scale.ctypes.data
+    rc = _load().oracle_centered_clip_scaled(
         G.ctypes.data, ld, n, _offsets(off), Pn, float(tau), float(eps),
-        int(max_iters), v0p, v.ctypes.data, iters.ctypes.data, sn.ctypes.data,
+        int(max_iters), v0p, sp, v.ctypes.data, iters.ctypes.data, sn.ctypes.data,
         trace.ctypes.data if want_trace else None)
     if rc != 0:
         raise ValueError("oracle_centered_clip: bad arguments")
@@ -135,8 +170,10 @@ def z_norm(seed: int, d: int) -> float:
 
 
 def verify(G, off, v, tau: float, seed: int, x_base: int = 0,
-           znorm: Optional[float] = None, want_delta: bool = False):
-    """Returns dict(norms, weights, proj [n,P], colsum [P], delta [n,width]|None)."""
+           znorm: Optional[float] = None, want_delta: bool = False,
+           scale: Optional[np.ndarray] = None):
+    """Returns dict(norms, weights, proj [n,P], colsum [P], delta [n,width]|None).
+    scale (optional, [n, P]): the quantities of the rows scale[i, j] * G[i, partition j]."""
     G = _as_G(G)
     n, _ = G.shape
     ld = G.strides[0] // 4 if n > 1 else G.shape[1]
@@ -149,9 +186,14 @@ def verify(G, off, v, tau: float, seed: int, x_base: int = 0,
     norms = np.zeros((n, Pn)); weights = np.zeros((n, Pn)); proj = np.zeros((n, Pn))
     colsum = np.zeros(Pn)
     delta = np.zeros((n, max(width, 1))) if want_delta else None
-    rc = _load().oracle_verify(
+    sp = None
+    if scale is not None:
+        scale = np.ascontiguousarray(scale, dtype=np.float64)
+        assert scale.shape == (n, Pn)
+        sp = scale.ctypes.data
+    rc = _load().oracle_verify_scaled(
         G.ctypes.data, ld, n, _offsets(off), Pn, v.ctypes.data, float(tau),
-        int(seed), int(x_base), float(znorm), norms.ctypes.data,
+        int(seed), int(x_base), float(znorm), sp, norms.ctypes.data,
         weights.ctypes.data, proj.ctypes.data, colsum.ctypes.data,
         delta.ctypes.data if want_delta else None, max(width, 1))
     if rc != 0:
