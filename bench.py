@@ -80,6 +80,9 @@ def main() -> int:
                          "last pass at once and checking afterwards")
     ap.add_argument("--with-delta", action="store_true",
                     help="streaming path: also materialise the clipped residuals (optional)")
+    ap.add_argument("--preclip", type=float, default=0.0,
+                    help="pre-clipping radius lambda of BTARD-Clipped-SGD as a multiple of the "
+                         "median row norm of partition 0 (0: none, the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of known size (1 GiB read + 1 GiB "
@@ -114,6 +117,10 @@ def main() -> int:
         vout["delta"] = torch.empty((n, d), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream(dev)
     slab_bytes = 4.0 * n * d
+    lam = 0.0
+    if args.preclip > 0.0:
+        row_norms = G[:, off[0]:off[1]].double().norm(dim=1)
+        lam = float(torch.tensor(args.preclip * float(row_norms.median()), dtype=torch.float32))
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -128,7 +135,7 @@ def main() -> int:
             events[i].record(stream)
 
     # ---- the two ways of running a step; events (if given) mark the segment boundaries
-    prob_s = btard.make_problem(G, off, wl.tau, wl.eps, M, workspace=ws)
+    prob_s = btard.make_problem(G, off, wl.tau, wl.eps, M, workspace=ws, preclip=lam)
     seg_s = ("cc_begin", "cc_iterate", "cc_finish", "verify")
 
     def step_streaming(events=None):
@@ -137,14 +144,20 @@ def main() -> int:
         rec(events, 1)
         btard.cc_iterate(prob_s, 0, M)
         rec(events, 2)
-        btard.cc_finish(prob_s, M, v, iters, step_norm)
-        rec(events, 3)
-        btard.verify_projections(G, off, v, wl.tau, wl.seed_z, want_delta=args.with_delta,
-                                 workspace=ws, out=vout)
+        if lam > 0.0:
+            # (the stand-alone verification call knows nothing of pre-clipping: the fused
+            # last pass serves both segments here)
+            btard.cc_finish_verify(prob_s, M, wl.seed_z, v, iters, step_norm, out=vout)
+            rec(events, 3)
+        else:
+            btard.cc_finish(prob_s, M, v, iters, step_norm)
+            rec(events, 3)
+            btard.verify_projections(G, off, v, wl.tau, wl.seed_z, want_delta=args.with_delta,
+                                     workspace=ws, out=vout)
         rec(events, 4)
 
     prob_h = btard.make_problem(G, off, wl.tau, wl.eps, M, workspace=ws,
-                                flags=btard.BTARD_FLAG_GRAM)
+                                flags=btard.BTARD_FLAG_GRAM, preclip=lam)
     seg_h = ("cc_begin", "gram_matrix", "gram_iterate", "fallback_passes", "finish_verify")
     fallback_passes = []
 
@@ -211,6 +224,8 @@ def main() -> int:
         "config": {"workload": wl.name, "n": n, "d": d, "parts": P, "tau": wl.tau, "eps": wl.eps,
                    "max_iters": M, "seed_inputs": wl.seed_inputs, "seed_z": wl.seed_z},
     }
+    if lam > 0.0:
+        out["config"]["preclip_lambda"] = lam
 
     # ---- streaming path: the per-iteration kernel
     if args.mode in ("both", "streaming"):
@@ -313,7 +328,8 @@ def main() -> int:
         times = []
         while True:                      # at least one run; repeat short ones (best of <= 5)
             t0 = time.perf_counter()
-            _, ito, _, _ = oracle.centered_clip(sub, sub_off, wl.tau, wl.eps, M)
+            scale = oracle.preclip_scales(sub, sub_off, lam)[0] if lam > 0.0 else None
+            _, ito, _, _ = oracle.centered_clip(sub, sub_off, wl.tau, wl.eps, M, scale=scale)
             times.append(time.perf_counter() - t0)
             if sum(times) > 10.0 or len(times) >= 5:
                 break

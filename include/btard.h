@@ -157,8 +157,22 @@ typedef struct btard_cc_problem {
     size_t workspace_bytes;
     void *stream;
     uint32_t flags;
+    float preclip;               /* pre-clipping radius lambda, see below; 0 or +INF: none */
 } btard_cc_problem;
 
+/*
+ * Pre-clipping (BTARD-Clipped-SGD, App. E.3, Alg. 9 line 3 and the paragraph after the
+ * algorithm): with 0 < preclip < +INF every peer's partition is first clipped to radius
+ * lambda = preclip,
+ *     g~_i[j] = min{1, lambda / ||g_i[j]||_2} g_i[j],
+ * and everything the calls below compute (v, iters, last_step_norm, norms, weights, proj,
+ * colsum) is that of the clipped rows.  g itself is not modified: the factors are applied
+ * as the data is read.  They come from the diagonal of the Gram matrix with
+ * BTARD_FLAG_GRAM (no extra pass), else from one extra pass over g in btard_cc_begin.
+ * Where a kernel forms g~ explicitly it does so as a peer holding fp32 tensors would:
+ * factor rounded to fp32, one fp32 multiplication per element.  v0 must be NULL (the
+ * iteration starts at the mean of the clipped rows).
+ */
 int btard_cc_begin(const btard_cc_problem *p);
 int btard_cc_gram(const btard_cc_problem *p);          /* = gram_matrix; gram_iterate */
 int btard_cc_gram_matrix(const btard_cc_problem *p);   /* the pass that forms the Gram matrices */
@@ -229,6 +243,27 @@ int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d
 int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float *v,
                            int32_t *iters, double *last_step_norm, uint64_t seed,
                            double *norms, double *weights, double *proj, double *colsum);
+
+/*
+ * The pre-clipping factors of a run: factors[i * parts + j] = alpha_ij (DEVICE, n * parts
+ * doubles; all 1 without pre-clipping).  Valid after btard_cc_begin, with BTARD_FLAG_GRAM
+ * after btard_cc_gram.  Enqueued on the problem's stream.
+ */
+int btard_cc_preclip_factors(const btard_cc_problem *p, double *factors);
+
+/*
+ * btard_centered_clip_verify on pre-clipped rows (see btard_cc_problem.preclip): lambda > 0
+ * is the radius; factors (DEVICE, n * parts doubles) may be NULL.
+ */
+int btard_centered_clip_verify_preclipped(const float *g, int64_t ldg, int32_t n, int64_t d,
+                                          const int64_t *offsets_host, int32_t parts,
+                                          float lambda, float tau, float eps,
+                                          int32_t max_iters, float *v, int32_t *iters,
+                                          double *last_step_norm, uint64_t seed,
+                                          double *norms, double *weights, double *proj,
+                                          double *colsum, double *factors, void *workspace,
+                                          size_t workspace_bytes, void *stream,
+                                          uint32_t flags);
 
 /*
  * Test hook for the z-spec: writes zhat[x_begin .. x_begin + count) (fp32,

@@ -37,7 +37,7 @@ class _Problem(ctypes.Structure):
         ("parts", ctypes.c_int32), ("tau", ctypes.c_float), ("eps", ctypes.c_float),
         ("max_iters", ctypes.c_int32), ("v0", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
-        ("stream", ctypes.c_void_p), ("flags", ctypes.c_uint32),
+        ("stream", ctypes.c_void_p), ("flags", ctypes.c_uint32), ("preclip", ctypes.c_float),
     ]
 
 
@@ -96,6 +96,14 @@ def load_library():
         c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t,
         c.c_void_p, c.c_uint32]
     lib.btard_centered_clip_verify.restype = c.c_int
+    lib.btard_cc_preclip_factors.argtypes = [c.POINTER(_Problem), c.c_void_p]
+    lib.btard_cc_preclip_factors.restype = c.c_int
+    lib.btard_centered_clip_verify_preclipped.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.POINTER(c.c_int64), c.c_int32,
+        c.c_float, c.c_float, c.c_float, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_size_t, c.c_void_p, c.c_uint32]
+    lib.btard_centered_clip_verify_preclipped.restype = c.c_int
     lib.btard_verify_projections.argtypes = [
         c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.POINTER(c.c_int64), c.c_int32,
         c.c_void_p, c.c_float, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
@@ -180,22 +188,25 @@ def centered_clip(g: torch.Tensor, offsets: Sequence[int], tau: float, eps: floa
 class Problem:
     """Keeps the ctypes problem description (and what it points to) alive."""
 
-    def __init__(self, g, offsets, tau, eps, max_iters, v0, workspace, flags=BTARD_FLAG_NONE):
+    def __init__(self, g, offsets, tau, eps, max_iters, v0, workspace, flags=BTARD_FLAG_NONE,
+                 preclip=0.0):
         self.g, self.v0, self.workspace = g, v0, workspace
         self.offsets = _off_array(offsets)
         self.parts = len(offsets) - 1
         self.c = _Problem(
             _ptr(g), _row_stride(g), int(g.shape[0]), int(g.shape[1]), self.offsets,
             self.parts, float(tau), float(eps), int(max_iters), _ptr(v0), _ptr(workspace),
-            workspace.numel(), _stream_ptr(g.device), int(flags))
+            workspace.numel(), _stream_ptr(g.device), int(flags), float(preclip))
 
 
 def make_problem(g: torch.Tensor, offsets: Sequence[int], tau: float, eps: float,
                  max_iters: int, v0: Optional[torch.Tensor] = None,
-                 workspace: Optional[torch.Tensor] = None, flags: int = BTARD_FLAG_NONE) -> Problem:
+                 workspace: Optional[torch.Tensor] = None, flags: int = BTARD_FLAG_NONE,
+                 preclip: float = 0.0) -> Problem:
+    """preclip: pre-clipping radius lambda of BTARD-Clipped-SGD (0 or inf: none)."""
     if workspace is None:
         workspace = alloc_workspace(int(g.shape[0]), len(offsets) - 1, g.device)
-    return Problem(g, offsets, tau, eps, max_iters, v0, workspace, flags)
+    return Problem(g, offsets, tau, eps, max_iters, v0, workspace, flags, preclip)
 
 
 def cc_begin(p: Problem) -> None:
@@ -302,6 +313,42 @@ def centered_clip_verify(g: torch.Tensor, offsets: Sequence[int], tau: float, ep
     return v, iters, last_step_norm, out
 
 
+def cc_preclip_factors(p: Problem, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """btard_cc_preclip_factors.  Returns the [n, parts] fp64 factors alpha_ij."""
+    n = int(p.g.shape[0])
+    if out is None:
+        out = torch.empty((n, p.parts), dtype=torch.float64, device=p.g.device)
+    _check(load_library().btard_cc_preclip_factors(ctypes.byref(p.c), _ptr(out)),
+           "btard_cc_preclip_factors")
+    return out
+
+
+def centered_clip_verify_preclipped(g: torch.Tensor, offsets: Sequence[int], lam: float,
+                                    tau: float, eps: float, max_iters: int, seed: int,
+                                    workspace: Optional[torch.Tensor] = None,
+                                    flags: int = BTARD_FLAG_NONE):
+    """btard_centered_clip_verify_preclipped.  Returns (v, iters, last_step_norm, dict,
+    factors [n, parts])."""
+    n, d = int(g.shape[0]), int(g.shape[1])
+    P = len(offsets) - 1
+    dev = g.device
+    v = torch.empty(d, dtype=torch.float32, device=dev)
+    iters = torch.empty(P, dtype=torch.int32, device=dev)
+    last_step_norm = torch.empty(P, dtype=torch.float64, device=dev)
+    factors = torch.empty((n, P), dtype=torch.float64, device=dev)
+    out = _verify_outputs(n, P, dev, None)
+    if workspace is None:
+        workspace = alloc_workspace(n, P, dev)
+    rc = load_library().btard_centered_clip_verify_preclipped(
+        _ptr(g), _row_stride(g), n, d, _off_array(offsets), P, float(lam), float(tau),
+        float(eps), int(max_iters), _ptr(v), _ptr(iters), _ptr(last_step_norm),
+        int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(out["norms"]), _ptr(out["weights"]),
+        _ptr(out["proj"]), _ptr(out["colsum"]), _ptr(factors), _ptr(workspace),
+        workspace.numel(), _stream_ptr(dev), int(flags))
+    _check(rc, "btard_centered_clip_verify_preclipped")
+    return v, iters, last_step_norm, out, factors
+
+
 def verify_projections(g: torch.Tensor, offsets: Sequence[int], v: torch.Tensor, tau: float,
                        seed: int, want_delta: bool = False,
                        workspace: Optional[torch.Tensor] = None,
@@ -356,4 +403,6 @@ btard_cc_finish = cc_finish
 btard_verify_projections = verify_projections
 btard_cc_finish_verify = cc_finish_verify
 btard_centered_clip_verify = centered_clip_verify
+btard_cc_preclip_factors = cc_preclip_factors
+btard_centered_clip_verify_preclipped = centered_clip_verify_preclipped
 btard_debug_zhat = debug_zhat

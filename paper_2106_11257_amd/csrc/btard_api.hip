@@ -28,7 +28,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-    size_t off, coef, delta, iters, done, aux, gram_n2, partial, partial_stride_doubles, gram, total;
+    size_t off, coef, delta, iters, done, aux, gram_n2, scale, partial, partial_stride_doubles, gram, total;
 };
 
 // State and partial sums exist twice (double-buffered by pass parity).
@@ -44,6 +44,7 @@ WsLayout ws_layout(int32_t n, int32_t P)
     L.done = p;     p = align_up(p + 2 * sizeof(int32_t) * P);      // done | final_buf
     L.aux = p;      p = align_up(p + 3 * sizeof(int32_t) * P);      // report_buf | remaining | gram_ok
     L.gram_n2 = p;  p = align_up(p + sizeof(double) * P * (R + 1));  // gram_n2 [P][R] | gram_t2 [P]
+    L.scale = p;    p = align_up(p + sizeof(double) * P * R);        // pre-clipping factors
     const size_t blocks = (size_t)(P > kMaxBlocks ? P : kMaxBlocks);
     L.partial_stride_doubles = align_up(sizeof(double) * blocks * S) / sizeof(double);
     L.partial = p;  p = align_up(p + 2 * sizeof(double) * L.partial_stride_doubles);
@@ -88,6 +89,7 @@ CcState carve_cc(void *ws, int32_t n, int32_t P)
     st.gram_ok = st.report_buf + 2 * (size_t)P;
     st.gram_n2 = reinterpret_cast<double *>(b + L.gram_n2);
     st.gram_t2 = st.gram_n2 + (size_t)P * ((size_t)n + 1);
+    st.scale = reinterpret_cast<double *>(b + L.scale);
     st.partial_stride = (int64_t)L.partial_stride_doubles;
     st.R = n + 1;
     st.P = P;
@@ -125,14 +127,23 @@ typedef void (*VerifyFn)(VerifyArgs);
 typedef void (*FusedFn)(FusedArgs);
 
 // [variant][ragged: n < NP*LG][has v0]
+#define BTARD_PASS_ROW(NP, LG)                                                                  \
+    {{cc_pass_kernel<NP, LG, false, false, false>, cc_pass_kernel<NP, LG, false, true, false>},  \
+     {cc_pass_kernel<NP, LG, true, false, false>, cc_pass_kernel<NP, LG, true, true, false>}}
+const CcPassFn kCcPass[kVariants][2][2] = {
+    BTARD_PASS_ROW(4, 1),  BTARD_PASS_ROW(8, 1),  BTARD_PASS_ROW(16, 1), BTARD_PASS_ROW(16, 2),
+    BTARD_PASS_ROW(16, 4), BTARD_PASS_ROW(16, 8), BTARD_PASS_ROW(16, 16)};
+#undef BTARD_PASS_ROW
+// with pre-clipping factors (never with a start vector)  [variant][ragged]
+#define BTARD_PASS_S(NP, LG) \
+    {cc_pass_kernel<NP, LG, false, false, true>, cc_pass_kernel<NP, LG, true, false, true>}
+const CcPassFn kCcPassScaled[kVariants][2] = {
+    BTARD_PASS_S(4, 1),  BTARD_PASS_S(8, 1),  BTARD_PASS_S(16, 1), BTARD_PASS_S(16, 2),
+    BTARD_PASS_S(16, 4), BTARD_PASS_S(16, 8), BTARD_PASS_S(16, 16)};
+#undef BTARD_PASS_S
 #define BTARD_CC_ROW(K, NP, LG)                                                   \
     {{K<NP, LG, false, false>, K<NP, LG, false, true>},                           \
      {K<NP, LG, true, false>, K<NP, LG, true, true>}}
-const CcPassFn kCcPass[kVariants][2][2] = {
-    BTARD_CC_ROW(cc_pass_kernel, 4, 1),  BTARD_CC_ROW(cc_pass_kernel, 8, 1),
-    BTARD_CC_ROW(cc_pass_kernel, 16, 1), BTARD_CC_ROW(cc_pass_kernel, 16, 2),
-    BTARD_CC_ROW(cc_pass_kernel, 16, 4), BTARD_CC_ROW(cc_pass_kernel, 16, 8),
-    BTARD_CC_ROW(cc_pass_kernel, 16, 16)};
 const CcFinishFn kCcFinish[kVariants][2][2] = {
     BTARD_CC_ROW(cc_finish_kernel, 4, 1),  BTARD_CC_ROW(cc_finish_kernel, 8, 1),
     BTARD_CC_ROW(cc_finish_kernel, 16, 1), BTARD_CC_ROW(cc_finish_kernel, 16, 2),
@@ -144,10 +155,16 @@ const VerifyFn kVerify[kVariants][2] = {BTARD_V_ROW(4, 1),  BTARD_V_ROW(8, 1),  
                                         BTARD_V_ROW(16, 2), BTARD_V_ROW(16, 4), BTARD_V_ROW(16, 8),
                                         BTARD_V_ROW(16, 16)};
 #undef BTARD_V_ROW
-#define BTARD_F_ROW(NP, LG) {cc_finish_verify_kernel<NP, LG, false>, cc_finish_verify_kernel<NP, LG, true>}
-const FusedFn kFused[kVariants][2] = {BTARD_F_ROW(4, 1),  BTARD_F_ROW(8, 1),  BTARD_F_ROW(16, 1),
-                                      BTARD_F_ROW(16, 2), BTARD_F_ROW(16, 4), BTARD_F_ROW(16, 8),
-                                      BTARD_F_ROW(16, 16)};
+// [scaled: with pre-clipping factors][variant][ragged]
+#define BTARD_F_ROW(NP, LG, S) \
+    {cc_finish_verify_kernel<NP, LG, false, S>, cc_finish_verify_kernel<NP, LG, true, S>}
+const FusedFn kFused[2][kVariants][2] = {
+    {BTARD_F_ROW(4, 1, false), BTARD_F_ROW(8, 1, false), BTARD_F_ROW(16, 1, false),
+     BTARD_F_ROW(16, 2, false), BTARD_F_ROW(16, 4, false), BTARD_F_ROW(16, 8, false),
+     BTARD_F_ROW(16, 16, false)},
+    {BTARD_F_ROW(4, 1, true), BTARD_F_ROW(8, 1, true), BTARD_F_ROW(16, 1, true),
+     BTARD_F_ROW(16, 2, true), BTARD_F_ROW(16, 4, true), BTARD_F_ROW(16, 8, true),
+     BTARD_F_ROW(16, 16, true)}};
 #undef BTARD_F_ROW
 
 int variant_peers(Variant v)
@@ -223,6 +240,9 @@ bool overlaps(const void *a, const void *b, int64_t elems)
     return pa < pb + len && pb < pa + len;
 }
 
+// pre-clipping of the rows (BTARD-Clipped-SGD) asked for: a positive, finite radius
+bool preclip_on(const btard_cc_problem *p) { return p->preclip > 0.0f && std::isfinite(p->preclip); }
+
 int check_problem(const btard_cc_problem *p)
 {
     if (!p) return BTARD_ERR_INVALID_ARG;
@@ -231,6 +251,8 @@ int check_problem(const btard_cc_problem *p)
     if (!(p->tau > 0.0f) || !(p->eps >= 0.0f) || p->max_iters < 0) return BTARD_ERR_INVALID_ARG;
     if ((p->flags & ~(uint32_t)(BTARD_FLAG_GRAM | BTARD_FLAG_HOST_SYNC)) != 0)
         return BTARD_ERR_INVALID_ARG;
+    if (!(p->preclip >= 0.0f)) return BTARD_ERR_INVALID_ARG;             // NaN or negative
+    if (preclip_on(p) && p->v0) return BTARD_ERR_INVALID_ARG;            // clipped rows start at their mean
     return check_workspace(p->workspace, p->workspace_bytes, p->n, p->parts);
 }
 
@@ -271,6 +293,9 @@ size_t btard_workspace_bytes(int32_t n, int32_t parts)
     return ws_layout(n, parts).total;
 }
 
+static bool gram_applies(const btard_cc_problem *p);
+static int pass_blocks(const btard_cc_problem *p, Variant var, int ragged, int based);
+
 int btard_cc_begin(const btard_cc_problem *p)
 {
     const int rc = check_problem(p);
@@ -278,13 +303,31 @@ int btard_cc_begin(const btard_cc_problem *p)
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     CcState st = carve_cc(p->workspace, p->n, p->parts);
     const int32_t P = p->parts;
+    // With pre-clipping the factors need the rows' norms: the Gram formulation reads them
+    // off its diagonal (btard_cc_gram_iterate), otherwise a pass of its own does it here.
+    const bool norm_pass = preclip_on(p) && !gram_applies(p);
     for (int32_t first = 0; first < P + 1; first += kOffChunk) {
         OffChunk chunk;
         const int32_t count = (P + 1 - first < kOffChunk) ? (P + 1 - first) : kOffChunk;
         for (int32_t t = 0; t < kOffChunk; ++t)
             chunk.v[t] = (t < count) ? p->offsets_host[first + t] : 0;
         hipLaunchKernelGGL(cc_begin_kernel, dim3(count), dim3(kOffChunk), 0, s, st, p->n,
-                           p->v0 ? 1 : 0, p->max_iters, first, count, chunk);
+                           p->v0 ? 1 : 0, (norm_pass && p->max_iters < 1) ? 1 : p->max_iters, first,
+                           count, norm_pass ? 1 : 0, chunk);
+    }
+    if (norm_pass) {
+        // the rows' own norms: one ordinary pass from v^0 = 0, then the factors
+        const Variant var = pick_variant(p->n);
+        const int ragged = p->n < variant_peers(var) ? 1 : 0;
+        const int B = pass_blocks(p, var, ragged, 0);
+        if (B <= 0) return BTARD_ERR_DEVICE;
+        CcArgs a;
+        a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = nullptr;
+        a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
+        a.prev_blocks = B; a.pass = 0; a.scaled = 0; a.st = st;
+        hipLaunchKernelGGL(kCcPass[var][ragged][0], dim3(B, P), dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL(preclip_scales_kernel, dim3(P), dim3(kBlock), 0, s, st, p->n, B,
+                           (double)p->preclip, p->max_iters);
     }
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
@@ -342,6 +385,7 @@ int btard_cc_gram_iterate(const btard_cc_problem *p)
     gi.gpart = reinterpret_cast<const double *>(static_cast<char *>(p->workspace) + L.gram);
     gi.blocks = B; gi.n = p->n;
     gi.tau = (double)p->tau; gi.eps = (double)p->eps; gi.max_iters = p->max_iters;
+    gi.lambda = preclip_on(p) ? (double)p->preclip : 0.0;
     hipLaunchKernelGGL(gram_iterate_kernel, dim3(p->parts), dim3(kBlock), 0, s, gi);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
@@ -396,7 +440,7 @@ int btard_debug_gram(const btard_cc_problem *p, double *gram_out)
 // Workgroups per partition of the pass kernel for this problem (the same in every pass).
 static int pass_blocks(const btard_cc_problem *p, Variant var, int ragged, int based)
 {
-    const CcPassFn fn = kCcPass[var][ragged][based];
+    const CcPassFn fn = preclip_on(p) ? kCcPassScaled[var][ragged] : kCcPass[var][ragged][based];
     const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
     if (resident <= 0) return 0;
     return blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
@@ -411,13 +455,13 @@ int btard_cc_iterate(const btard_cc_problem *p, int32_t first_iteration, int32_t
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     const Variant var = pick_variant(p->n);
     const int ragged = p->n < variant_peers(var) ? 1 : 0, based = p->v0 ? 1 : 0;
-    const CcPassFn fn = kCcPass[var][ragged][based];
+    const CcPassFn fn = preclip_on(p) ? kCcPassScaled[var][ragged] : kCcPass[var][ragged][based];
     const int B = pass_blocks(p, var, ragged, based);
     if (B <= 0) return BTARD_ERR_DEVICE;
     CcArgs a;
     a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = p->v0;
     a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
-    a.prev_blocks = B;
+    a.prev_blocks = B; a.scaled = preclip_on(p) ? 1 : 0;
     a.st = carve_cc(p->workspace, p->n, p->parts);
     for (int32_t l = 0; l < count; ++l) {
         a.pass = first_iteration + l;
@@ -445,7 +489,7 @@ int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int
     CcFinishArgs a;
     a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = p->v0; a.v = v;
     a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
-    a.pass = iterations; a.prev_blocks = Bpass;
+    a.pass = iterations; a.prev_blocks = Bpass; a.scaled = preclip_on(p) ? 1 : 0;
     a.st = carve_cc(p->workspace, p->n, p->parts);
     hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
     CcReportArgs r;
@@ -465,7 +509,7 @@ int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
     p.g = g; p.ldg = ldg; p.n = n; p.d = d; p.offsets_host = offsets_host; p.parts = parts;
     p.tau = tau; p.eps = eps; p.max_iters = max_iters; p.v0 = v0;
     p.workspace = workspace; p.workspace_bytes = workspace_bytes; p.stream = stream;
-    p.flags = flags;
+    p.flags = flags; p.preclip = 0.0f;
     int rc = check_problem(&p);
     if (rc != BTARD_OK) return rc;
     if (!v || !iters || overlaps(v, v0, d)) return BTARD_ERR_INVALID_ARG;
@@ -504,7 +548,7 @@ int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float 
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     const Variant var = pick_variant(p->n);
     const int ragged = p->n < variant_peers(var) ? 1 : 0;
-    const FusedFn fn = kFused[var][ragged];
+    const FusedFn fn = kFused[preclip_on(p) ? 1 : 0][var][ragged];
     const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
     if (resident <= 0) return BTARD_ERR_DEVICE;
     const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
@@ -516,6 +560,7 @@ int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float 
     a.pass = iterations; a.prev_blocks = Bpass; a.seed = seed; a.S = 2 * p->n + 2;
     // partitions the Gram iteration finished and vouches for take the kernel's light body
     a.use_gram_norms = gram_applies(p) ? 1 : 0;
+    a.scaled = preclip_on(p) ? 1 : 0;
     a.st = carve_cc(p->workspace, p->n, p->parts);
     hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
 
@@ -540,7 +585,7 @@ int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d
     p.g = g; p.ldg = ldg; p.n = n; p.d = d; p.offsets_host = offsets_host; p.parts = parts;
     p.tau = tau; p.eps = eps; p.max_iters = max_iters; p.v0 = v0;
     p.workspace = workspace; p.workspace_bytes = workspace_bytes; p.stream = stream;
-    p.flags = flags;
+    p.flags = flags; p.preclip = 0.0f;
     int rc = check_problem(&p);
     if (rc != BTARD_OK) return rc;
     if (!v || !iters || overlaps(v, v0, d) || !norms || !weights || !proj)
@@ -558,6 +603,52 @@ int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d
     if (rc != BTARD_OK) return rc;
     return btard_cc_finish_verify(&p, passes, v, iters, last_step_norm, seed, norms, weights, proj,
                                   colsum);
+}
+
+int btard_cc_preclip_factors(const btard_cc_problem *p, double *factors)
+{
+    const int rc = check_problem(p);
+    if (rc != BTARD_OK) return rc;
+    if (!factors) return BTARD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(p->stream);
+    hipLaunchKernelGGL(preclip_export_kernel, dim3(p->parts), dim3(64), 0, s,
+                       carve_cc(p->workspace, p->n, p->parts), p->n, factors);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+int btard_centered_clip_verify_preclipped(const float *g, int64_t ldg, int32_t n, int64_t d,
+                                          const int64_t *offsets_host, int32_t parts,
+                                          float lambda, float tau, float eps,
+                                          int32_t max_iters, float *v, int32_t *iters,
+                                          double *last_step_norm, uint64_t seed,
+                                          double *norms, double *weights, double *proj,
+                                          double *colsum, double *factors, void *workspace,
+                                          size_t workspace_bytes, void *stream, uint32_t flags)
+{
+    btard_cc_problem p;
+    p.g = g; p.ldg = ldg; p.n = n; p.d = d; p.offsets_host = offsets_host; p.parts = parts;
+    p.tau = tau; p.eps = eps; p.max_iters = max_iters; p.v0 = nullptr;
+    p.workspace = workspace; p.workspace_bytes = workspace_bytes; p.stream = stream;
+    p.flags = flags; p.preclip = lambda;
+    if (!(lambda > 0.0f)) return BTARD_ERR_INVALID_ARG;
+    int rc = check_problem(&p);
+    if (rc != BTARD_OK) return rc;
+    if (!v || !iters || !norms || !weights || !proj) return BTARD_ERR_INVALID_ARG;
+    rc = btard_cc_begin(&p);
+    if (rc != BTARD_OK) return rc;
+    rc = btard_cc_gram(&p);
+    if (rc != BTARD_OK) return rc;
+    int32_t passes = max_iters;
+    if ((flags & BTARD_FLAG_HOST_SYNC) != 0 && gram_applies(&p)) {
+        rc = btard_cc_remaining(&p, &passes);
+        if (rc != BTARD_OK) return rc;
+    }
+    rc = btard_cc_iterate(&p, 0, passes);
+    if (rc != BTARD_OK) return rc;
+    rc = btard_cc_finish_verify(&p, passes, v, iters, last_step_norm, seed, norms, weights, proj,
+                                colsum);
+    if (rc != BTARD_OK) return rc;
+    return factors ? btard_cc_preclip_factors(&p, factors) : BTARD_OK;
 }
 
 int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,

@@ -43,6 +43,7 @@ struct CcState {
                              //     the final norms and the last step norm it left below
     double *gram_n2;         // [P][R] ||g_i - v||^2 at the final v, from the Gram matrix
     double *gram_t2;         // [P]    ||last applied update||^2, from the Gram matrix
+    double *scale;           // [P][R] pre-clipping factors alpha_ij (1 unless pre-clipping)
     int64_t partial_stride;  // doubles between the two partial-sum buffers
     int32_t R;               // n + 1
     int32_t P;
@@ -57,6 +58,7 @@ struct CcArgs {
     int32_t max_iters;
     int32_t pass;            // index l of this pass (0-based)
     int32_t prev_blocks;     // workgroups per partition of the previous pass
+    int32_t scaled;          // rows are taken times st.scale (pre-clipping)
     CcState st;
 };
 
@@ -76,9 +78,11 @@ __global__ void upload_offsets_kernel(int64_t *off, int32_t first, int32_t count
 
 // One launch per chunk of offsets: workgroup b sets up partition first + b (if there is
 // one: the last chunk entry may be the end offset only), workgroup 0 also stores the chunk.
+// zero_start: all coefficients 0 (v^0 = 0), for the pass that measures the rows' own norms.
 __global__ __launch_bounds__(kOffChunk) void cc_begin_kernel(CcState st, int32_t n, int32_t has_v0,
                                                              int32_t max_iters, int32_t first,
-                                                             int32_t count, OffChunk chunk)
+                                                             int32_t count, int32_t zero_start,
+                                                             OffChunk chunk)
 {
     const int t = threadIdx.x;
     if (blockIdx.x == 0 && t < count) const_cast<int64_t *>(st.off)[first + t] = chunk.v[t];
@@ -88,8 +92,9 @@ __global__ __launch_bounds__(kOffChunk) void cc_begin_kernel(CcState st, int32_t
         double c;
         if (has_v0) c = (q == n) ? 1.0 : 0.0;
         else        c = (q == n) ? 0.0 : 1.0 / (double)n;
-        st.coef[(int64_t)j * st.R + q] = c;
+        st.coef[(int64_t)j * st.R + q] = zero_start ? 0.0 : c;
         st.delta[(int64_t)j * st.R + q] = 0.0;
+        st.scale[(int64_t)j * st.R + q] = 1.0;
     }
     if (t == 0) {
         st.iters[j] = 0;
@@ -243,11 +248,34 @@ __device__ __forceinline__ void combine_rows(const float (&val)[NP][4], const fl
     }
 }
 
+// Pre-clipping (BTARD-Clipped-SGD, App. E.3): row i of partition j counts as alpha_ij g_i.
+// The factor costs no instruction: in v = sum_i c_i (alpha_i g_i) it joins the coefficient,
+// and a residual alpha_i g - v is one fused multiply-add where it was one subtraction
+// (with alpha = 1, the case without pre-clipping, that is the same number bit for bit).
+// This fetches this lane group's factors (1 if `scaled` is false) and folds them into the
+// coefficients c and dl.
+template <int NP, int LG, bool RAGGED>
+__device__ __forceinline__ void fold_scales(const CcState &st, int j, int n, int lg, bool scaled,
+                                            double (&c)[NP], double (&dl)[NP], double (&al)[NP])
+{
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const int i = lg * NP + k;
+        const bool have = scaled && (!RAGGED || i < n);
+        const double f = have ? st.scale[(int64_t)j * st.R + (have ? i : 0)] : 1.0;
+        al[k] = f;                                  // (stays in vector registers)
+        c[k] = (LG == 1) ? uniform_double(c[k] * f) : c[k] * f;
+        dl[k] = (LG == 1) ? uniform_double(dl[k] * f) : dl[k] * f;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // one iteration: control step for the previous pass, then norms at v^l
 // ---------------------------------------------------------------------------
-template <int NP, int LG, bool RAGGED, bool HAS_BASE>
-__global__ __launch_bounds__(kBlock, (LG == 1 ? 4 : 2)) void cc_pass_kernel(CcArgs a)
+// SCALED: with pre-clipping factors (a variant of its own: the factors cost 32 registers that
+// the plain pass does not pay for).
+template <int NP, int LG, bool RAGGED, bool HAS_BASE, bool SCALED>
+__global__ __launch_bounds__(kBlock, (LG == 1 && !SCALED ? 4 : 2)) void cc_pass_kernel(CcArgs a)
 {
     using G = Geo<NP, LG>;
     __shared__ double s_c[kBlock], s_a[kBlock], s_red[kBlock];
@@ -289,6 +317,9 @@ __global__ __launch_bounds__(kBlock, (LG == 1 ? 4 : 2)) void cc_pass_kernel(CcAr
     double c[NP], dl[NP], cb, db;
     fetch_coefficients<NP, LG, RAGGED>(s_c, s_a, n, lg, c, dl, cb, db);
 
+    double al[NP];
+    if constexpr (SCALED) fold_scales<NP, LG, RAGGED>(a.st, j, n, lg, true, c, dl, al);
+
     double acc[NP];
 #pragma unroll
     for (int k = 0; k < NP; ++k) acc[k] = 0.0;
@@ -314,7 +345,9 @@ __global__ __launch_bounds__(kBlock, (LG == 1 ? 4 : 2)) void cc_pass_kernel(CcAr
 #pragma unroll
             for (int e = 0; e < kVec; ++e) {
                 forget(val[k][e]);
-                const double r = (double)val[k][e] - vv[e];
+                double r;
+                if constexpr (SCALED) r = fma(al[k], (double)val[k][e], -vv[e]);
+                else r = (double)val[k][e] - vv[e];
                 acc[k] = fma(r, r, acc[k]);
             }
         }
@@ -360,6 +393,7 @@ struct CcFinishArgs {
     int32_t max_iters;
     int32_t pass;            // number of passes that were enqueued
     int32_t prev_blocks;
+    int32_t scaled;          // rows are taken times st.scale (pre-clipping)
     CcState st;
 };
 
@@ -441,6 +475,10 @@ __global__ __launch_bounds__(kBlock, 3) void cc_finish_kernel(CcFinishArgs a)
 
     double c[NP], dl[NP], cb, db;
     fetch_coefficients<NP, LG, RAGGED>(s_c, s_a, n, lg, c, dl, cb, db);
+    if (a.scaled) {                                 // uniform
+        double al[NP];                              // (only the folded coefficients are used)
+        fold_scales<NP, LG, RAGGED>(a.st, j, n, lg, true, c, dl, al);
+    }
     double t2 = 0.0;
 
     // interior tiles, then the partition's first and last tile where they are not interior
@@ -493,6 +531,43 @@ __global__ __launch_bounds__(kBlock) void cc_report_kernel(CcReportArgs a)
         a.iters_out[j] = it;
         if (a.step_norm_out) a.step_norm_out[j] = (it > 0) ? sqrt(tot) : 0.0;
     }
+}
+
+// ---------------------------------------------------------------------------
+// pre-clipping factors (BTARD-Clipped-SGD, App. E.3, Alg. 9 line 3 and the text after the
+// algorithm): alpha_ij = min{1, lambda / ||g_i[j]||}.  The norms come from one ordinary pass
+// started at v^0 = 0 (cc_begin_kernel with zero_start), whose partial sums this kernel
+// reduces; it then sets the coefficients to the real start (the mean of the clipped rows).
+// One workgroup per partition.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void preclip_scales_kernel(CcState st, int32_t n,
+                                                                int32_t blocks, double lambda,
+                                                                int32_t max_iters)
+{
+    __shared__ double s_red[kBlock];
+    const int j = blockIdx.x, R = st.R, t = threadIdx.x;
+    const double *pj = st.partial + (int64_t)j * blocks * R;
+    const double tot = reduce_partials<kBlock>(pj, blocks, R, R, s_red);
+    if (t < R) {
+        double al = 1.0;
+        if (t < n) {
+            const double N = sqrt(tot);
+            al = (N <= lambda) ? 1.0 : lambda / N;      // (a non-finite norm gives a NaN factor,
+        }                                               //  which the first real pass reports)
+        st.scale[(int64_t)j * R + t] = al;
+        st.coef[(int64_t)j * R + t] = (t < n) ? 1.0 / (double)n : 0.0;
+    }
+    if (t == 0) {                                   // (the norm pass ran with a cap of >= 1)
+        st.done[j] = (max_iters <= 0) ? 1 : 0;
+        st.remaining[j] = max_iters > 0 ? max_iters : 0;
+    }
+}
+
+// the factors for the caller: out[i * P + j] = alpha_ij
+__global__ void preclip_export_kernel(CcState st, int32_t n, double *out)
+{
+    const int j = blockIdx.x;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) out[(int64_t)i * st.P + j] = st.scale[(int64_t)j * st.R + i];
 }
 
 }  // namespace btard

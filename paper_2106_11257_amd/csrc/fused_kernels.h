@@ -22,16 +22,18 @@ struct FusedArgs {
     uint64_t seed;
     int32_t S;               // 2n + 2: n norms^2, n <zhat, r_i>, |zhat|^2, |last update|^2
     int32_t use_gram_norms;  // partitions with gram_ok set take the light body (project_partition)
+    int32_t scaled;          // rows are taken times st.scale (pre-clipping)
     CcState st;
 };
 
 // The arithmetic of one tile whose rows are in registers (val).  INTERIOR (the whole tile
 // lies inside the partition, a wavefront-uniform fact) selects a body with a vector store
 // and no masks; the other body guards every coordinate.
-template <int NP, int LG, bool INTERIOR>
+template <int NP, int LG, bool INTERIOR, bool SCALED>
 __device__ __forceinline__ void fused_rows(float *__restrict__ v, uint64_t seed, int lg, int sub,
                                            int64_t xu, int64_t lo, int64_t hi, float (&val)[NP][4],
                                            const double (&c)[NP], const double (&dl)[NP],
+                                           const double (&al)[NP],
                                            double (&accN)[NP], double (&accR)[NP], double &t2,
                                            double &z2)
 {
@@ -80,7 +82,9 @@ __device__ __forceinline__ void fused_rows(float *__restrict__ v, uint64_t seed,
 #pragma unroll
         for (int e = 0; e < kVec; ++e) {
             forget(val[k][e]);   // converted again here instead of kept as 2x the registers
-            const double r = (double)val[k][e] - vd[e];
+            double r;
+            if constexpr (SCALED) r = fma(al[k], (double)val[k][e], -vd[e]);
+            else r = (double)val[k][e] - vd[e];
             accN[k] = fma(r, r, accN[k]);
             accR[k] = fma(z[e], r, accR[k]);
         }
@@ -154,8 +158,12 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
     using G = Geo<NP, 1>;
     const int n = a.n, S = a.S, R = a.st.R;
     if ((int)threadIdx.x < R) {                      // final state: buffer 0
-        s_c[threadIdx.x] = a.st.coef[(int64_t)j * R + threadIdx.x];
-        s_a[threadIdx.x] = 0.0;
+        // With pre-clipping v = sum_i c_i (alpha_i g_i): the factor joins the coefficient,
+        // and <zhat, alpha_i g_i> = alpha_i <zhat, g_i> is applied to the sums at the end
+        // (exact products here; the Gram iteration worked on the exactly scaled matrix).
+        const double al = a.scaled ? a.st.scale[(int64_t)j * R + threadIdx.x] : 1.0;
+        s_c[threadIdx.x] = a.st.coef[(int64_t)j * R + threadIdx.x] * al;
+        s_a[threadIdx.x] = al;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) a.st.report_buf[j] = 0;
     __syncthreads();
@@ -231,8 +239,9 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
         if (q < n) {
             s = first ? a.st.gram_n2[(int64_t)j * R + q] : 0.0;
         } else if (q < 2 * n) {
+            const double al = s_a[q - n];
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) s += sh[w][q - n] - sh[w][NP];
+            for (int w = 0; w < kWaves; ++w) s += al * sh[w][q - n] - sh[w][NP];
         } else if (q == 2 * n) {
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) s += sh[w][NP + 1];
@@ -243,7 +252,8 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
     }
 }
 
-template <int NP, int LG, bool RAGGED>
+// SCALED: with pre-clipping factors (general body; the light body folds them for free).
+template <int NP, int LG, bool RAGGED, bool SCALED>
 __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a)
 {
     using G = Geo<NP, LG>;
@@ -282,6 +292,8 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
 
     double c[NP], dl[NP], cb, db;
     fetch_coefficients<NP, LG, RAGGED>(s_c, s_a, n, lg, c, dl, cb, db);
+    double al[NP];
+    if constexpr (SCALED) fold_scales<NP, LG, RAGGED>(a.st, j, n, lg, true, c, dl, al);
     double accN[NP], accR[NP];
 #pragma unroll
     for (int k = 0; k < NP; ++k) { accN[k] = 0.0; accR[k] = 0.0; }
@@ -292,16 +304,16 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
     // are in flight all the time and not only while the wavefront waits; every tile's
     // arithmetic follows the next tile's loads on a straight path (no join in between), so
     // the wait before it is for the current tile only.
-    // (With several lane groups the coefficients live in vector registers and a second
-    // register set does not fit: one set, as many wavefronts as fit.)
+    // (With several lane groups the coefficients live in vector registers, with pre-clipping
+    // the factors do, and a second register set does not fit: one set then.)
     const TileRange tr = tile_range<G::kW>(lo, hi);
     const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
-    if constexpr (LG > 1) {
+    if constexpr (LG > 1 || SCALED) {
         for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
             const int64_t xu = tr.xa + u * G::kW;
             float val[NP][4];
             load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, true, val);
-            fused_rows<NP, LG, true>(a.v, a.seed, lg, sub, xu, lo, hi, val, c, dl, accN, accR, t2,
+            fused_rows<NP, LG, true, SCALED>(a.v, a.seed, lg, sub, xu, lo, hi, val, c, dl, al, accN, accR, t2,
                                      z2);
         }
     } else if (iw.begin < iw.end) {
@@ -313,7 +325,7 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
             const int64_t u1 = u + tr.stride;
             if (u1 >= iw.end) break;                 // the last tile is in va
             load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u1 * G::kW, lo, hi, true, vb);
-            fused_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, dl,
+            fused_rows<NP, LG, true, SCALED>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, dl, al,
                                      accN, accR, t2, z2);
             const int64_t u2 = u1 + tr.stride;
             if (u2 >= iw.end) {                      // the last tile is in vb
@@ -322,15 +334,15 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
                 break;
             }
             load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u2 * G::kW, lo, hi, true, va);
-            fused_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, dl,
+            fused_rows<NP, LG, true, SCALED>(a.v, a.seed, lg, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, dl, al,
                                      accN, accR, t2, z2);
             u = u2;
         }
         if (last_in_b)
-            fused_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, vb, c, dl,
+            fused_rows<NP, LG, true, SCALED>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, vb, c, dl, al,
                                      accN, accR, t2, z2);
         else
-            fused_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, dl,
+            fused_rows<NP, LG, true, SCALED>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, dl, al,
                                      accN, accR, t2, z2);
     }
     sum_within_group_all<G::kLanes, NP>(accN);
@@ -364,7 +376,7 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
             if (tile_is_interior<G::kW>(xu, lo, hi)) continue;
             float val[NP][4];
             load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, false, val);
-            fused_rows<NP, LG, false>(a.v, a.seed, lg, sub, xu, lo, hi, val, c, dl, eN, eR, et2,
+            fused_rows<NP, LG, false, SCALED>(a.v, a.seed, lg, sub, xu, lo, hi, val, c, dl, al, eN, eR, et2,
                                       ez2);
             any = true;
         }

@@ -132,6 +132,7 @@ struct GramIterArgs {
     int32_t n;
     double tau, eps;
     int32_t max_iters;
+    double lambda;           // pre-clipping radius (BTARD-Clipped-SGD); <= 0: none
 };
 
 // Relative accuracy assumed for a Gram entry and for a quadratic form in it, in units of
@@ -239,6 +240,22 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         G[t / N][t % N] = s;
     }
     __syncthreads();
+    if (a.lambda > 0.0) {
+        // Pre-clipping (App. E.3): the rows become alpha_i g_i with alpha_i =
+        // min{1, lambda / ||g_i||} and ||g_i||^2 = Gamma_ii, so their Gram matrix is
+        // D Gamma D -- no pass over the data.  The factors are left in st.scale for the
+        // passes that follow.
+        __shared__ double s_alpha[N];
+        if (t < N) {
+            const double Nn = sqrt(fmax(G[t][t], 0.0));
+            const double al = (t < n && !(Nn <= a.lambda)) ? a.lambda / Nn : 1.0;
+            s_alpha[t] = al;
+            if (t < n) a.st.scale[(int64_t)j * R + t] = al;
+        }
+        __syncthreads();
+        G[t / N][t % N] *= s_alpha[t / N] * s_alpha[t % N];
+        __syncthreads();
+    }
     if (t >= 64) return;
 
     const int i = t & 15;

@@ -371,6 +371,106 @@ def test_fused_finish_and_verify_equals_the_two_calls(dev, n, d, P, pad, flags):
 
 
 # --------------------------------------------------------------------------
+# pre-clipping of BTARD-Clipped-SGD (App. E.3): everything on min{1, lambda/||g_i[j]||} g_i[j]
+# --------------------------------------------------------------------------
+def check_preclipped(G, off, lam, tau, eps, M, seed, flags, label):
+    lam = float(np.float32(lam))                   # the radius crosses the ABI as fp32
+    say(f"[preclip] {label} n={G.shape[0]} d={G.shape[1]} P={len(off) - 1} lambda={lam} tau={tau} "
+        f"eps={eps} M={M} flags={flags}")
+    v, iters, sn, out, fac = btard.centered_clip_verify_preclipped(G, off, lam, tau, eps, M, seed,
+                                                                   flags=flags)
+    torch.cuda.synchronize()
+    Gh = G.cpu().numpy()
+    alpha, _ = oracle.preclip_scales(Gh, off, lam)
+    np.testing.assert_allclose(fac.cpu().numpy(), alpha, rtol=1e-12)
+    vo, ito, sno, _ = oracle.centered_clip(Gh, off, tau, eps, M, scale=alpha)
+    np.testing.assert_array_equal(iters.cpu().numpy(), ito)
+    v_h = v.cpu().numpy()
+    for j in range(len(off) - 1):
+        lo, hi = off[j], off[j + 1]
+        assert rel_l2(v_h[lo:hi], vo[lo:hi]) <= V_TOL, f"partition {j}"
+    np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=1e-4, atol=1e-11)
+    ref = oracle.verify(Gh, off, v_h.astype(np.float64), tau, seed, scale=alpha)
+    np.testing.assert_allclose(out["norms"].cpu().numpy(), ref["norms"], rtol=1e-6, atol=1e-9)
+    np.testing.assert_allclose(out["weights"].cpu().numpy(), ref["weights"], rtol=1e-6)
+    assert rel_l2(out["proj"].cpu().numpy(), ref["proj"]) <= PROJ_TOL
+    cs, cs_ref = out["colsum"].cpu().numpy(), ref["colsum"]
+    assert np.abs(cs - cs_ref).max() <= PROJ_TOL * np.abs(ref["proj"]).sum(axis=0).max()
+    return alpha
+
+
+@pytest.mark.parametrize("n,d,P,pad", [(3, 1031, 2, 0), (9, 5000, 4, 2), (16, 70001, 16, 0),
+                                       (16, 262147, 3, 5), (33, 2000, 3, 1), (64, 20000, 64, 0),
+                                       (130, 700, 2, 0)])
+@pytest.mark.parametrize("flags", [0, 1])
+def test_preclipped_small_shapes(dev, n, d, P, pad, flags):
+    G, off = workloads.generic_case(n, d, P, seed=7 * n + d, device=dev, ld=d + pad, spread=0.05,
+                                    outliers=max(1, n // 4), outlier_scale=30.0)
+    # a radius between the honest rows' norms and the outliers': some rows clipped, some not
+    norms = np.linalg.norm(G.cpu().numpy().astype(np.float64)[:, off[0]:off[1]], axis=1)
+    lam = float(np.sqrt(norms.min() * norms.max()))
+    alpha = check_preclipped(G, off, lam, 1.0, 1e-6, 40, 0xC11F, flags, "mixed")
+    assert (alpha < 1.0).any() and (alpha == 1.0).any()
+    check_preclipped(G, off, 1e-3 * lam, 0.3, 0.0, 5, 0xC11F, flags, "all clipped")
+    check_preclipped(G, off, 1e6 * lam, 1.0, 1e-6, 1, 0xC11F, flags, "none clipped")
+    check_preclipped(G, off, lam, 1.0, 1e-6, 0, 0xC11F, flags, "M = 0")
+
+
+def test_preclipped_none_clipped_equals_the_plain_run(dev):
+    G, off = workloads.generic_case(16, 50001, 5, seed=5, device=dev, spread=0.05, outliers=4)
+    for flags in (0, 1):
+        a = btard.centered_clip_verify_preclipped(G, off, 1e30, 1.0, 1e-6, 30, 77, flags=flags)
+        b = btard.centered_clip_verify(G, off, 1.0, 1e-6, 30, 77, flags=flags)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+        assert (a[4] == 1.0).all()
+        for k in ("norms", "weights", "proj", "colsum"):
+            np.testing.assert_allclose(a[3][k].cpu().numpy(), b[3][k].cpu().numpy(), rtol=1e-12,
+                                       atol=1e-300)
+
+
+def test_preclipped_gram_hand_over_and_phased_calls(dev):
+    """Low-noise rows (the Gram iteration must hand over) with pre-clipping: the passes that
+    take over use the factors the Gram kernel left; and the same through the phased calls
+    without a Gram matrix, where btard_cc_begin measures the norms in a pass of its own."""
+    gen = torch.Generator(device=dev); gen.manual_seed(12)
+    mu = torch.randn(20000, generator=gen, device=dev) * 100.0
+    G = mu[None, :] + 1e-4 * torch.randn((12, 20000), generator=gen, device=dev)
+    off = workloads.split_offsets(20000, 5)
+    lam = float(0.5 * mu[:4000].norm())            # every row is clipped, to nearly the same point
+    alpha = check_preclipped(G, off, lam, 1e-3, 1e-6, 40, 5, btard.BTARD_FLAG_GRAM, "low noise")
+    assert (alpha < 1.0).all()
+    p = btard.make_problem(G, off, 1e-3, 1e-6, 40, flags=btard.BTARD_FLAG_GRAM, preclip=lam)
+    btard.cc_begin(p); btard.cc_gram(p)
+    assert btard.cc_remaining(p) > 0
+    p2 = btard.make_problem(G, off, 1e-3, 1e-6, 40, preclip=lam)
+    btard.cc_begin(p2)
+    fac = btard.cc_preclip_factors(p2)
+    btard.cc_iterate(p2, 0, 40)
+    v, iters, sn = btard.cc_finish(p2, 40)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(fac.cpu().numpy(), alpha, rtol=1e-12)
+    vo, ito, _, _ = oracle.centered_clip(G.cpu().numpy(), off, 1e-3, 1e-6, 40, scale=alpha)
+    np.testing.assert_array_equal(iters.cpu().numpy(), ito)
+    assert rel_l2(v.cpu().numpy(), vo) <= V_TOL
+    with pytest.raises(btard.BtardError):        # a start vector and pre-clipping do not go together
+        btard.cc_begin(btard.make_problem(G, off, 1.0, 1e-6, 5, v0=torch.zeros(20000, device=dev),
+                                          preclip=lam))
+
+
+@pytest.mark.parametrize("cfg,d", [(2, 400_003), (4, 1 << 20), (3, 300_000)])
+def test_preclipped_configs_reduced_length(dev, cfg, d):
+    wl = workloads.make_workload(cfg, device=dev, d=d)
+    Gh = wl.G.cpu().numpy().astype(np.float64)
+    lo, hi = wl.offsets[0], wl.offsets[1]
+    norms = np.linalg.norm(Gh[:, lo:hi], axis=1)
+    lam = float(2.0 * np.median(norms))            # honest rows pass, amplified rows are clipped
+    for flags in (0, btard.BTARD_FLAG_GRAM):
+        check_preclipped(wl.G, wl.offsets, lam, wl.tau, wl.eps, wl.max_iters, wl.seed_z, flags,
+                         wl.name)
+
+
+# --------------------------------------------------------------------------
 # the five benchmark configurations: reduced length (whole oracle) and full size
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("cfg,d", [(1, 1 << 16), (2, 400_003), (3, 1_200_000), (4, 1 << 20),
