@@ -10,6 +10,8 @@ from .oracle import (  # noqa: F401
     philox4x32_10,
     preclip_scales,
     split,
+    tau_schedule,
+    verification3,
     verify,
     z_hat,
     z_norm,

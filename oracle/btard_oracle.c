@@ -16,6 +16,8 @@
  *                       iteration cap M of App. I.1
  *   - Delta, norm, w, s: Alg. 1 lines 8-9; Alg. 6 (BTARD) lines 8-12; eq. (2)
  *   - column check:     Alg. 1 line 16; Alg. 6 Verification 2
+ *   - tau_l schedule:   App. D.2, eq. (5)
+ *   - Verification 3:   Alg. 6 (BTARD), the block of that name
  *   - pre-clipping:     App. E.3, Alg. 9 (BTARD-Clipped-SGD) line 3 and the
  *                       paragraph after the algorithm (per-partition clipping)
  *   - GetRandomVector:  Alg. 6 line 6 and the paragraph after it (a unit vector,
@@ -90,10 +92,13 @@ int oracle_split(int64_t d, int32_t parts, int64_t *off)
 /* ------------------------------------------------------------------------ */
 /* srow (optional): n factors; row i of this partition is srow[i] * G[i][.]  */
 /* (the pre-clipped gradients of BTARD-Clipped-SGD), else the rows as given. */
+/* tau_l (optional): M clipping radii, update number l (0-based) uses        */
+/* tau_l[l] as eq. (CenteredClip) is written (tau_l of eq. (5)), else tau.    */
 static void centered_clip_partition(const float *G, int64_t ld, int32_t n,
                                     int64_t lo, int64_t hi, double tau,
                                     double eps, int32_t M, const double *v0,
-                                    const double *srow, double *v, int32_t *iters,
+                                    const double *srow, const double *tau_l,
+                                    double *v, int32_t *iters,
                                     double *step_norm, double *trace)
 {
     const int64_t dj = hi - lo;
@@ -118,6 +123,7 @@ static void centered_clip_partition(const float *G, int64_t ld, int32_t n,
     double T = 0.0;
     int bad = 0;
     while (it < M) {
+        const double tau_now = tau_l ? tau_l[it] : tau;
         /* norms ||g_i - v^l|| and clip weights min{1, tau/norm} */
         for (int32_t i = 0; i < n; ++i) {
             const float *gi = G + i * ld;
@@ -130,7 +136,7 @@ static void centered_clip_partition(const float *G, int64_t ld, int32_t n,
             }
             double N = sqrt(N2);
             if (!isfinite(N)) bad = 1;
-            w[i] = (N <= tau) ? 1.0 : tau / N;
+            w[i] = (N <= tau_now) ? 1.0 : tau_now / N;
         }
         if (bad) break;
 
@@ -166,15 +172,18 @@ static void centered_clip_partition(const float *G, int64_t ld, int32_t n,
 /* scale (optional): n x P row-major factors alpha_ij: CenteredClip then runs on
  * the rows alpha_ij * g_i[j] (App. E.3, Alg. 9: BTARD-Clipped-SGD hands the
  * pre-clipped gradients to BTARD). */
-int oracle_centered_clip_scaled(const float *G, int64_t ld, int32_t n,
-                                const int64_t *off, int32_t P, double tau, double eps,
-                                int32_t M, const double *v0, const double *scale,
-                                double *v, int32_t *iters, double *step_norm,
-                                double *trace)
+int oracle_centered_clip_general(const float *G, int64_t ld, int32_t n,
+                                 const int64_t *off, int32_t P, double tau, double eps,
+                                 int32_t M, const double *v0, const double *scale,
+                                 const double *tau_l, double *v, int32_t *iters,
+                                 double *step_norm, double *trace)
 {
     if (!G || n <= 0 || !off || P <= 0 || !v || !iters || M < 0 || !(tau > 0.0) ||
         !(eps >= 0.0))
         return -1;
+    if (tau_l)
+        for (int32_t l = 0; l < M; ++l)
+            if (!(tau_l[l] > 0.0)) return -1;
     for (int32_t j = 0; j < P; ++j)
         if (off[j] > off[j + 1] || off[j] < 0 || off[j + 1] > ld) return -1;
     double *srow = (double *)malloc(sizeof(double) * (size_t)n);
@@ -184,7 +193,7 @@ int oracle_centered_clip_scaled(const float *G, int64_t ld, int32_t n,
         if (scale)
             for (int32_t i = 0; i < n; ++i) srow[i] = scale[(int64_t)i * P + j];
         centered_clip_partition(G, ld, n, off[j], off[j + 1], tau, eps, M, v0,
-                                scale ? srow : NULL, v, &iters[j],
+                                scale ? srow : NULL, tau_l, v, &iters[j],
                                 step_norm ? &step_norm[j] : NULL,
                                 trace ? trace + (int64_t)j * M : NULL);
     }
@@ -192,13 +201,68 @@ int oracle_centered_clip_scaled(const float *G, int64_t ld, int32_t n,
     return 0;
 }
 
+int oracle_centered_clip_scaled(const float *G, int64_t ld, int32_t n,
+                                const int64_t *off, int32_t P, double tau, double eps,
+                                int32_t M, const double *v0, const double *scale,
+                                double *v, int32_t *iters, double *step_norm,
+                                double *trace)
+{
+    return oracle_centered_clip_general(G, ld, n, off, P, tau, eps, M, v0, scale, NULL, v,
+                                        iters, step_norm, trace);
+}
+
 int oracle_centered_clip(const float *G, int64_t ld, int32_t n,
                          const int64_t *off, int32_t P, double tau, double eps,
                          int32_t M, const double *v0, double *v,
                          int32_t *iters, double *step_norm, double *trace)
 {
-    return oracle_centered_clip_scaled(G, ld, n, off, P, tau, eps, M, v0, NULL, v, iters,
-                                       step_norm, trace);
+    return oracle_centered_clip_general(G, ld, n, off, P, tau, eps, M, v0, NULL, NULL, v,
+                                        iters, step_norm, trace);
+}
+
+/* ------------------------------------------------------------------------ */
+/* The clipping radii of eq. (5) (App. D.2):                                 */
+/*   tau_l = 4 sqrt( (1 - delta)(B_l^2/3 + sigma^2) / (sqrt(3) delta) ),      */
+/*   B_{l+1}^2 = 6.45 delta B_l^2 + 5 sigma^2,                               */
+/* delta = fraction of Byzantine inputs, sigma^2 = bound on the honest       */
+/* inputs' pairwise variance, B_0^2 = bound on E||v^0 - mean||^2.            */
+/* tau[count], B2[count] (optional) = B_l^2.                                 */
+/* ------------------------------------------------------------------------ */
+int oracle_tau_schedule(double delta, double sigma, double B0, int32_t count,
+                        double *tau, double *B2)
+{
+    if (!(delta > 0.0) || !(delta < 1.0) || !(sigma >= 0.0) || !(B0 >= 0.0) || count < 0 ||
+        !tau)
+        return -1;
+    double b2 = B0 * B0;
+    for (int32_t l = 0; l < count; ++l) {
+        tau[l] = 4.0 * sqrt((1.0 - delta) * (b2 / 3.0 + sigma * sigma) / (sqrt(3.0) * delta));
+        if (B2) B2[l] = b2;
+        b2 = 6.45 * delta * b2 + 5.0 * sigma * sigma;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Verification 3 of Alg. 6 (BTARD): check_ij = [ ||g_i(j) - g^(j)|| >       */
+/* Delta_max ], votes_j = sum_i check_ij, and CheckAveraging(j) is triggered */
+/* when votes_j > n/2.  norms is n x P row-major (as oracle_verify returns). */
+/* ------------------------------------------------------------------------ */
+int oracle_verification3(const double *norms, int32_t n, int32_t P, double delta_max,
+                         uint8_t *check, int32_t *votes, uint8_t *trigger)
+{
+    if (!norms || n <= 0 || P <= 0 || !check || !votes || !trigger) return -1;
+    for (int32_t j = 0; j < P; ++j) {
+        int32_t cnt = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            const uint8_t c = norms[(int64_t)i * P + j] > delta_max ? 1 : 0;
+            check[(int64_t)i * P + j] = c;
+            cnt += c;
+        }
+        votes[j] = cnt;
+        trigger[j] = (2 * cnt > n) ? 1 : 0;
+    }
+    return 0;
 }
 
 /* ------------------------------------------------------------------------ */

@@ -49,6 +49,17 @@ def _load():
         c.c_double, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_void_p]
     lib.oracle_centered_clip_scaled.restype = c.c_int
+    lib.oracle_centered_clip_general.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, P(c.c_int64), c.c_int32, c.c_double,
+        c.c_double, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_void_p]
+    lib.oracle_centered_clip_general.restype = c.c_int
+    lib.oracle_tau_schedule.argtypes = [c.c_double, c.c_double, c.c_double, c.c_int32,
+                                        c.c_void_p, c.c_void_p]
+    lib.oracle_tau_schedule.restype = c.c_int
+    lib.oracle_verification3.argtypes = [c.c_void_p, c.c_int32, c.c_int32, c.c_double,
+                                         c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.oracle_verification3.restype = c.c_int
     lib.oracle_preclip_scales.argtypes = [
         c.c_void_p, c.c_int64, c.c_int32, P(c.c_int64), c.c_int32, c.c_double, c.c_void_p,
         c.c_void_p]
@@ -112,11 +123,34 @@ def preclip_scales(G, off, lam: float):
     return alpha, norms
 
 
+def tau_schedule(delta: float, sigma: float, B0: float, count: int):
+    """The clipping radii tau_l of eq. (5): (tau [count], B_l^2 [count])."""
+    tau = np.zeros(max(count, 1)); b2 = np.zeros(max(count, 1))
+    if _load().oracle_tau_schedule(float(delta), float(sigma), float(B0), int(count),
+                                   tau.ctypes.data, b2.ctypes.data) != 0:
+        raise ValueError("oracle_tau_schedule: bad arguments")
+    return tau[:count], b2[:count]
+
+
+def verification3(norms, delta_max: float):
+    """Verification 3 of Alg. 6: (check [n, P] uint8, votes [P] int32, trigger [P] uint8)."""
+    norms = np.ascontiguousarray(norms, dtype=np.float64)
+    n, Pn = norms.shape
+    check = np.zeros((n, Pn), dtype=np.uint8)
+    votes = np.zeros(Pn, dtype=np.int32)
+    trigger = np.zeros(Pn, dtype=np.uint8)
+    if _load().oracle_verification3(norms.ctypes.data, n, Pn, float(delta_max), check.ctypes.data,
+                                    votes.ctypes.data, trigger.ctypes.data) != 0:
+        raise ValueError("oracle_verification3: bad arguments")
+    return check, votes, trigger
+
+
 def centered_clip(G, off, tau: float, eps: float, max_iters: int,
                   v0: Optional[np.ndarray] = None, want_trace: bool = False,
-                  scale: Optional[np.ndarray] = None):
+                  scale: Optional[np.ndarray] = None, tau_l: Optional[Sequence[float]] = None):
     """Returns (v[fp64, ld], iters[int32, P], step_norm[fp64, P], trace|None).
-    scale (optional, [n, P]): run on the rows scale[i, j] * G[i, partition j]."""
+    scale (optional, [n, P]): run on the rows scale[i, j] * G[i, partition j].
+    tau_l (optional, max_iters radii): update l uses tau_l[l] instead of tau."""
     G = _as_G(G)
     n, _ = G.shape
     ld = G.strides[0] // 4 if n > 1 else G.shape[1]
@@ -136,9 +170,14 @@ def centered_clip(G, off, tau: float, eps: float, max_iters: int,
         scale = np.ascontiguousarray(scale, dtype=np.float64)
         assert scale.shape == (n, Pn)
         sp = scale.ctypes.data
-    rc = _load().oracle_centered_clip_scaled(
+    tp = None
+    if tau_l is not None:
+        tau_l = np.ascontiguousarray(tau_l, dtype=np.float64)
+        assert tau_l.shape == (max_iters,)
+        tp = tau_l.ctypes.data
+    rc = _load().oracle_centered_clip_general(
         G.ctypes.data, ld, n, _offsets(off), Pn, float(tau), float(eps),
-        int(max_iters), v0p, sp, v.ctypes.data, iters.ctypes.data, sn.ctypes.data,
+        int(max_iters), v0p, sp, tp, v.ctypes.data, iters.ctypes.data, sn.ctypes.data,
         trace.ctypes.data if want_trace else None)
     if rc != 0:
         raise ValueError("oracle_centered_clip: bad arguments")
