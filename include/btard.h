@@ -158,6 +158,7 @@ typedef struct btard_cc_problem {
     void *stream;
     uint32_t flags;
     float preclip;               /* pre-clipping radius lambda, see below; 0 or +INF: none */
+    const float *tau_schedule;   /* HOST, max_iters radii tau_l (eq. (5)), or NULL: constant tau */
 } btard_cc_problem;
 
 /*
@@ -173,6 +174,15 @@ typedef struct btard_cc_problem {
  * factor rounded to fp32, one fp32 multiplication per element.  v0 must be NULL (the
  * iteration starts at the mean of the clipped rows).
  */
+/*
+ * Clipping radii per iteration: eq. (CenteredClip) is written with tau_l, which App. D.2,
+ * eq. (5) derives from the Byzantine fraction delta, the honest inputs' variance bound
+ * sigma^2 and a bound B_0^2 on E||v^0 - mean||^2 (btard_tau_schedule below computes it).
+ * With tau_schedule != NULL update number l (0-based) of every partition uses
+ * tau_schedule[l]; max_iters must not exceed BTARD_MAX_SCHEDULE.  The weights of the
+ * verification quantities use `tau` (Alg. 6 has one tau).
+ */
+#define BTARD_MAX_SCHEDULE 1024
 int btard_cc_begin(const btard_cc_problem *p);
 int btard_cc_gram(const btard_cc_problem *p);          /* = gram_matrix; gram_iterate */
 int btard_cc_gram_matrix(const btard_cc_problem *p);   /* the pass that forms the Gram matrices */
@@ -243,6 +253,23 @@ int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d
 int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float *v,
                            int32_t *iters, double *last_step_norm, uint64_t seed,
                            double *norms, double *weights, double *proj, double *colsum);
+
+/*
+ * tau_l of App. D.2, eq. (5), for l = 0 .. count - 1 (HOST out):
+ *   tau_l = 4 sqrt((1 - delta)(B_l^2 / 3 + sigma^2) / (sqrt(3) delta)),
+ *   B_{l+1}^2 = 6.45 delta B_l^2 + 5 sigma^2,  B_0 = b0.
+ * 0 < delta < 1, sigma >= 0, b0 >= 0.  Pure host function.
+ */
+int btard_tau_schedule(double delta, double sigma, double b0, int32_t count, float *tau_host);
+
+/*
+ * Verification 3 of Alg. 6 on the norms btard_verify_projections returned (DEVICE,
+ * norms[i * parts + j]): check[i * parts + j] = [norm_ij > delta_max] (DEVICE uint8),
+ * votes[j] = sum_i check_ij (DEVICE int32), trigger[j] = [votes_j > n / 2] (DEVICE uint8: the
+ * partitions for which CheckAveraging must run).  Enqueued on `stream`.
+ */
+int btard_verification3(const double *norms, int32_t n, int32_t parts, double delta_max,
+                        uint8_t *check, int32_t *votes, uint8_t *trigger, void *stream);
 
 /*
  * The pre-clipping factors of a run: factors[i * parts + j] = alpha_ij (DEVICE, n * parts

@@ -9,7 +9,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Optional, Sequence
+from typing import List, Optional, Sequence
 
 import torch
 
@@ -38,6 +38,7 @@ class _Problem(ctypes.Structure):
         ("max_iters", ctypes.c_int32), ("v0", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p), ("flags", ctypes.c_uint32), ("preclip", ctypes.c_float),
+        ("tau_schedule", ctypes.POINTER(ctypes.c_float)),
     ]
 
 
@@ -96,6 +97,12 @@ def load_library():
         c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t,
         c.c_void_p, c.c_uint32]
     lib.btard_centered_clip_verify.restype = c.c_int
+    lib.btard_tau_schedule.argtypes = [c.c_double, c.c_double, c.c_double, c.c_int32,
+                                       c.POINTER(c.c_float)]
+    lib.btard_tau_schedule.restype = c.c_int
+    lib.btard_verification3.argtypes = [c.c_void_p, c.c_int32, c.c_int32, c.c_double, c.c_void_p,
+                                        c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.btard_verification3.restype = c.c_int
     lib.btard_cc_preclip_factors.argtypes = [c.POINTER(_Problem), c.c_void_p]
     lib.btard_cc_preclip_factors.restype = c.c_int
     lib.btard_centered_clip_verify_preclipped.argtypes = [
@@ -189,24 +196,31 @@ class Problem:
     """Keeps the ctypes problem description (and what it points to) alive."""
 
     def __init__(self, g, offsets, tau, eps, max_iters, v0, workspace, flags=BTARD_FLAG_NONE,
-                 preclip=0.0):
+                 preclip=0.0, tau_schedule=None):
         self.g, self.v0, self.workspace = g, v0, workspace
         self.offsets = _off_array(offsets)
         self.parts = len(offsets) - 1
         self.c = _Problem(
             _ptr(g), _row_stride(g), int(g.shape[0]), int(g.shape[1]), self.offsets,
             self.parts, float(tau), float(eps), int(max_iters), _ptr(v0), _ptr(workspace),
-            workspace.numel(), _stream_ptr(g.device), int(flags), float(preclip))
+            workspace.numel(), _stream_ptr(g.device), int(flags), float(preclip), None)
+        if tau_schedule is not None:
+            vals = [float(x) for x in tau_schedule]
+            if len(vals) != int(max_iters):
+                raise ValueError("tau_schedule needs max_iters entries")
+            self.schedule = (ctypes.c_float * max(len(vals), 1))(*vals)
+            self.c.tau_schedule = ctypes.cast(self.schedule, ctypes.POINTER(ctypes.c_float))
 
 
 def make_problem(g: torch.Tensor, offsets: Sequence[int], tau: float, eps: float,
                  max_iters: int, v0: Optional[torch.Tensor] = None,
                  workspace: Optional[torch.Tensor] = None, flags: int = BTARD_FLAG_NONE,
-                 preclip: float = 0.0) -> Problem:
-    """preclip: pre-clipping radius lambda of BTARD-Clipped-SGD (0 or inf: none)."""
+                 preclip: float = 0.0, tau_schedule: Optional[Sequence[float]] = None) -> Problem:
+    """preclip: pre-clipping radius lambda of BTARD-Clipped-SGD (0 or inf: none);
+    tau_schedule: max_iters clipping radii tau_l (eq. (5)), None: constant tau."""
     if workspace is None:
         workspace = alloc_workspace(int(g.shape[0]), len(offsets) - 1, g.device)
-    return Problem(g, offsets, tau, eps, max_iters, v0, workspace, flags, preclip)
+    return Problem(g, offsets, tau, eps, max_iters, v0, workspace, flags, preclip, tau_schedule)
 
 
 def cc_begin(p: Problem) -> None:
@@ -313,6 +327,29 @@ def centered_clip_verify(g: torch.Tensor, offsets: Sequence[int], tau: float, ep
     return v, iters, last_step_norm, out
 
 
+def tau_schedule(delta: float, sigma: float, b0: float, count: int) -> List[float]:
+    """btard_tau_schedule: the radii tau_l of eq. (5), as the fp32 values the library uses."""
+    out = (ctypes.c_float * max(count, 1))()
+    _check(load_library().btard_tau_schedule(float(delta), float(sigma), float(b0), int(count), out),
+           "btard_tau_schedule")
+    return [float(out[i]) for i in range(count)]
+
+
+def verification3(norms: torch.Tensor, delta_max: float):
+    """btard_verification3.  norms: [n, parts] fp64 on the device.  Returns (check [n, parts]
+    uint8, votes [parts] int32, trigger [parts] uint8)."""
+    n, P = int(norms.shape[0]), int(norms.shape[1])
+    assert norms.dtype == torch.float64 and norms.is_contiguous()
+    dev = norms.device
+    check = torch.empty((n, P), dtype=torch.uint8, device=dev)
+    votes = torch.empty(P, dtype=torch.int32, device=dev)
+    trigger = torch.empty(P, dtype=torch.uint8, device=dev)
+    _check(load_library().btard_verification3(_ptr(norms), n, P, float(delta_max), _ptr(check),
+                                              _ptr(votes), _ptr(trigger), _stream_ptr(dev)),
+           "btard_verification3")
+    return check, votes, trigger
+
+
 def cc_preclip_factors(p: Problem, out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """btard_cc_preclip_factors.  Returns the [n, parts] fp64 factors alpha_ij."""
     n = int(p.g.shape[0])
@@ -404,5 +441,7 @@ btard_verify_projections = verify_projections
 btard_cc_finish_verify = cc_finish_verify
 btard_centered_clip_verify = centered_clip_verify
 btard_cc_preclip_factors = cc_preclip_factors
+btard_tau_schedule = tau_schedule
+btard_verification3 = verification3
 btard_centered_clip_verify_preclipped = centered_clip_verify_preclipped
 btard_debug_zhat = debug_zhat

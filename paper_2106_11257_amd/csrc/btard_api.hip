@@ -28,7 +28,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WsLayout {
-    size_t off, coef, delta, iters, done, aux, gram_n2, scale, partial, partial_stride_doubles, gram, total;
+    size_t off, coef, delta, iters, done, aux, gram_n2, scale, sched, partial, partial_stride_doubles, gram, total;
 };
 
 // State and partial sums exist twice (double-buffered by pass parity).
@@ -45,6 +45,7 @@ WsLayout ws_layout(int32_t n, int32_t P)
     L.aux = p;      p = align_up(p + 3 * sizeof(int32_t) * P);      // report_buf | remaining | gram_ok
     L.gram_n2 = p;  p = align_up(p + sizeof(double) * P * (R + 1));  // gram_n2 [P][R] | gram_t2 [P]
     L.scale = p;    p = align_up(p + sizeof(double) * P * R);        // pre-clipping factors
+    L.sched = p;    p = align_up(p + sizeof(double) * kMaxSchedule); // clipping radii per iteration
     const size_t blocks = (size_t)(P > kMaxBlocks ? P : kMaxBlocks);
     L.partial_stride_doubles = align_up(sizeof(double) * blocks * S) / sizeof(double);
     L.partial = p;  p = align_up(p + 2 * sizeof(double) * L.partial_stride_doubles);
@@ -90,6 +91,8 @@ CcState carve_cc(void *ws, int32_t n, int32_t P)
     st.gram_n2 = reinterpret_cast<double *>(b + L.gram_n2);
     st.gram_t2 = st.gram_n2 + (size_t)P * ((size_t)n + 1);
     st.scale = reinterpret_cast<double *>(b + L.scale);
+    st.tau_sched = reinterpret_cast<const double *>(b + L.sched);
+    st.has_sched = 0;
     st.partial_stride = (int64_t)L.partial_stride_doubles;
     st.R = n + 1;
     st.P = P;
@@ -240,6 +243,14 @@ bool overlaps(const void *a, const void *b, int64_t elems)
     return pa < pb + len && pb < pa + len;
 }
 
+// the state of a problem's run (carve_cc + what depends on the problem description)
+CcState carve_problem(const btard_cc_problem *p)
+{
+    CcState st = carve_cc(p->workspace, p->n, p->parts);
+    st.has_sched = p->tau_schedule ? 1 : 0;
+    return st;
+}
+
 // pre-clipping of the rows (BTARD-Clipped-SGD) asked for: a positive, finite radius
 bool preclip_on(const btard_cc_problem *p) { return p->preclip > 0.0f && std::isfinite(p->preclip); }
 
@@ -251,6 +262,11 @@ int check_problem(const btard_cc_problem *p)
     if (!(p->tau > 0.0f) || !(p->eps >= 0.0f) || p->max_iters < 0) return BTARD_ERR_INVALID_ARG;
     if ((p->flags & ~(uint32_t)(BTARD_FLAG_GRAM | BTARD_FLAG_HOST_SYNC)) != 0)
         return BTARD_ERR_INVALID_ARG;
+    if (p->tau_schedule) {
+        if (p->max_iters > kMaxSchedule) return BTARD_ERR_INVALID_ARG;
+        for (int32_t l = 0; l < p->max_iters; ++l)
+            if (!(p->tau_schedule[l] > 0.0f)) return BTARD_ERR_INVALID_ARG;
+    }
     if (!(p->preclip >= 0.0f)) return BTARD_ERR_INVALID_ARG;             // NaN or negative
     if (preclip_on(p) && p->v0) return BTARD_ERR_INVALID_ARG;            // clipped rows start at their mean
     return check_workspace(p->workspace, p->workspace_bytes, p->n, p->parts);
@@ -301,7 +317,7 @@ int btard_cc_begin(const btard_cc_problem *p)
     const int rc = check_problem(p);
     if (rc != BTARD_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(p->stream);
-    CcState st = carve_cc(p->workspace, p->n, p->parts);
+    CcState st = carve_problem(p);
     const int32_t P = p->parts;
     // With pre-clipping the factors need the rows' norms: the Gram formulation reads them
     // off its diagonal (btard_cc_gram_iterate), otherwise a pass of its own does it here.
@@ -314,6 +330,17 @@ int btard_cc_begin(const btard_cc_problem *p)
         hipLaunchKernelGGL(cc_begin_kernel, dim3(count), dim3(kOffChunk), 0, s, st, p->n,
                            p->v0 ? 1 : 0, (norm_pass && p->max_iters < 1) ? 1 : p->max_iters, first,
                            count, norm_pass ? 1 : 0, chunk);
+    }
+    if (p->tau_schedule) {
+        double *dst = const_cast<double *>(st.tau_sched);
+        for (int32_t first = 0; first < p->max_iters; first += kOffChunk) {
+            DblChunk chunk;
+            const int32_t count = (p->max_iters - first < kOffChunk) ? (p->max_iters - first) : kOffChunk;
+            for (int32_t t = 0; t < kOffChunk; ++t)
+                chunk.v[t] = (t < count) ? (double)p->tau_schedule[first + t] : 0.0;
+            hipLaunchKernelGGL(upload_doubles_kernel, dim3(1), dim3(kOffChunk), 0, s, dst, first,
+                               count, chunk);
+        }
     }
     if (norm_pass) {
         // the rows' own norms: one ordinary pass from v^0 = 0, then the factors
@@ -365,7 +392,7 @@ int btard_cc_gram_matrix(const btard_cc_problem *p)
     const WsLayout L = ws_layout(p->n, p->parts);
     GramArgs ga;
     ga.g = p->g; ga.ld = p->ldg; ga.n = p->n;
-    ga.off = carve_cc(p->workspace, p->n, p->parts).off;
+    ga.off = carve_problem(p).off;
     ga.gpart = reinterpret_cast<double *>(static_cast<char *>(p->workspace) + L.gram);
     hipLaunchKernelGGL(gram_kernel(p), dim3(B, p->parts), dim3(kBlock), 0, s, ga);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
@@ -381,7 +408,7 @@ int btard_cc_gram_iterate(const btard_cc_problem *p)
     if (B <= 0) return BTARD_ERR_DEVICE;
     const WsLayout L = ws_layout(p->n, p->parts);
     GramIterArgs gi;
-    gi.st = carve_cc(p->workspace, p->n, p->parts);
+    gi.st = carve_problem(p);
     gi.gpart = reinterpret_cast<const double *>(static_cast<char *>(p->workspace) + L.gram);
     gi.blocks = B; gi.n = p->n;
     gi.tau = (double)p->tau; gi.eps = (double)p->eps; gi.max_iters = p->max_iters;
@@ -403,7 +430,7 @@ int btard_cc_remaining(const btard_cc_problem *p, int32_t *remaining_host)
     if (rc != BTARD_OK) return rc;
     if (!remaining_host) return BTARD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(p->stream);
-    const CcState st = carve_cc(p->workspace, p->n, p->parts);
+    const CcState st = carve_problem(p);
     std::vector<int32_t> host((size_t)p->parts);
     if (hipMemcpyAsync(host.data(), st.remaining, sizeof(int32_t) * (size_t)p->parts,
                        hipMemcpyDeviceToHost, s) != hipSuccess)
@@ -425,7 +452,7 @@ int btard_debug_gram(const btard_cc_problem *p, double *gram_out)
     const int B = gram_blocks(p);
     if (B <= 0) return BTARD_ERR_DEVICE;
     const WsLayout L = ws_layout(p->n, p->parts);
-    CcState st = carve_cc(p->workspace, p->n, p->parts);
+    CcState st = carve_problem(p);
     const int up = upload_offsets(p->offsets_host, p->parts, st.off, s);
     if (up != BTARD_OK) return up;
     GramArgs ga;
@@ -462,7 +489,7 @@ int btard_cc_iterate(const btard_cc_problem *p, int32_t first_iteration, int32_t
     a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = p->v0;
     a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
     a.prev_blocks = B; a.scaled = preclip_on(p) ? 1 : 0;
-    a.st = carve_cc(p->workspace, p->n, p->parts);
+    a.st = carve_problem(p);
     for (int32_t l = 0; l < count; ++l) {
         a.pass = first_iteration + l;
         hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
@@ -490,7 +517,7 @@ int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int
     a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = p->v0; a.v = v;
     a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
     a.pass = iterations; a.prev_blocks = Bpass; a.scaled = preclip_on(p) ? 1 : 0;
-    a.st = carve_cc(p->workspace, p->n, p->parts);
+    a.st = carve_problem(p);
     hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
     CcReportArgs r;
     r.st = a.st; r.pass = iterations; r.blocks = B; r.iters_out = iters;
@@ -509,7 +536,7 @@ int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
     p.g = g; p.ldg = ldg; p.n = n; p.d = d; p.offsets_host = offsets_host; p.parts = parts;
     p.tau = tau; p.eps = eps; p.max_iters = max_iters; p.v0 = v0;
     p.workspace = workspace; p.workspace_bytes = workspace_bytes; p.stream = stream;
-    p.flags = flags; p.preclip = 0.0f;
+    p.flags = flags; p.preclip = 0.0f; p.tau_schedule = nullptr;
     int rc = check_problem(&p);
     if (rc != BTARD_OK) return rc;
     if (!v || !iters || overlaps(v, v0, d)) return BTARD_ERR_INVALID_ARG;
@@ -561,7 +588,7 @@ int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float 
     // partitions the Gram iteration finished and vouches for take the kernel's light body
     a.use_gram_norms = gram_applies(p) ? 1 : 0;
     a.scaled = preclip_on(p) ? 1 : 0;
-    a.st = carve_cc(p->workspace, p->n, p->parts);
+    a.st = carve_problem(p);
     hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
 
     const double *part = a.st.partial + (iterations & 1) * a.st.partial_stride;
@@ -585,7 +612,7 @@ int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d
     p.g = g; p.ldg = ldg; p.n = n; p.d = d; p.offsets_host = offsets_host; p.parts = parts;
     p.tau = tau; p.eps = eps; p.max_iters = max_iters; p.v0 = v0;
     p.workspace = workspace; p.workspace_bytes = workspace_bytes; p.stream = stream;
-    p.flags = flags; p.preclip = 0.0f;
+    p.flags = flags; p.preclip = 0.0f; p.tau_schedule = nullptr;
     int rc = check_problem(&p);
     if (rc != BTARD_OK) return rc;
     if (!v || !iters || overlaps(v, v0, d) || !norms || !weights || !proj)
@@ -605,6 +632,32 @@ int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d
                                   colsum);
 }
 
+int btard_tau_schedule(double delta, double sigma, double b0, int32_t count, float *tau_host)
+{
+    if (!(delta > 0.0) || !(delta < 1.0) || !(sigma >= 0.0) || !(b0 >= 0.0) || count < 0 ||
+        (count > 0 && !tau_host))
+        return BTARD_ERR_INVALID_ARG;
+    double b2 = b0 * b0;
+    for (int32_t l = 0; l < count; ++l) {
+        tau_host[l] = (float)(4.0 * std::sqrt((1.0 - delta) * (b2 / 3.0 + sigma * sigma) /
+                                              (std::sqrt(3.0) * delta)));
+        b2 = 6.45 * delta * b2 + 5.0 * sigma * sigma;
+    }
+    return BTARD_OK;
+}
+
+int btard_verification3(const double *norms, int32_t n, int32_t parts, double delta_max,
+                        uint8_t *check, int32_t *votes, uint8_t *trigger, void *stream)
+{
+    if (!norms || !check || !votes || !trigger || n < 1 || n > kMaxPeers || parts < 1 ||
+        parts > kMaxParts || delta_max != delta_max)
+        return BTARD_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(verification3_kernel, dim3((parts + 63) / 64), dim3(64), 0,
+                       static_cast<hipStream_t>(stream), norms, n, parts, delta_max, check, votes,
+                       trigger);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
 int btard_cc_preclip_factors(const btard_cc_problem *p, double *factors)
 {
     const int rc = check_problem(p);
@@ -612,7 +665,7 @@ int btard_cc_preclip_factors(const btard_cc_problem *p, double *factors)
     if (!factors) return BTARD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     hipLaunchKernelGGL(preclip_export_kernel, dim3(p->parts), dim3(64), 0, s,
-                       carve_cc(p->workspace, p->n, p->parts), p->n, factors);
+                       carve_problem(p), p->n, factors);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
@@ -629,7 +682,7 @@ int btard_centered_clip_verify_preclipped(const float *g, int64_t ldg, int32_t n
     p.g = g; p.ldg = ldg; p.n = n; p.d = d; p.offsets_host = offsets_host; p.parts = parts;
     p.tau = tau; p.eps = eps; p.max_iters = max_iters; p.v0 = nullptr;
     p.workspace = workspace; p.workspace_bytes = workspace_bytes; p.stream = stream;
-    p.flags = flags; p.preclip = lambda;
+    p.flags = flags; p.preclip = lambda; p.tau_schedule = nullptr;
     if (!(lambda > 0.0f)) return BTARD_ERR_INVALID_ARG;
     int rc = check_problem(&p);
     if (rc != BTARD_OK) return rc;

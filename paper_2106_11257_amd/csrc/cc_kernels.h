@@ -44,6 +44,8 @@ struct CcState {
     double *gram_n2;         // [P][R] ||g_i - v||^2 at the final v, from the Gram matrix
     double *gram_t2;         // [P]    ||last applied update||^2, from the Gram matrix
     double *scale;           // [P][R] pre-clipping factors alpha_ij (1 unless pre-clipping)
+    const double *tau_sched; // [kMaxSchedule] clipping radius of update l (only if has_sched)
+    int32_t has_sched;
     int64_t partial_stride;  // doubles between the two partial-sum buffers
     int32_t R;               // n + 1
     int32_t P;
@@ -65,10 +67,21 @@ struct CcArgs {
 // ---------------------------------------------------------------------------
 // begin: upload offsets (through the kernel arguments), set c^0, clear state
 // ---------------------------------------------------------------------------
+constexpr int kMaxSchedule = 1024;   // longest per-iteration schedule of clipping radii
 constexpr int kOffChunk = 256;
 struct OffChunk {
     int64_t v[kOffChunk];
 };
+
+struct DblChunk {
+    double v[kOffChunk];
+};
+
+__global__ void upload_doubles_kernel(double *dst, int32_t first, int32_t count, DblChunk chunk)
+{
+    const int t = threadIdx.x;
+    if (t < count) dst[first + t] = chunk.v[t];
+}
 
 __global__ void upload_offsets_kernel(int64_t *off, int32_t first, int32_t count, OffChunk chunk)
 {
@@ -141,6 +154,8 @@ __device__ __forceinline__ bool control_step(const CcState &st, int j, int n, do
     if (t < R) { cq = cp[t]; aq = ap[t]; }
     int it = st.iters[prev * P + j];
     int dn = 0;
+    // update number `it` (0-based) is the one prepared here: tau_l of eq. (5) if scheduled
+    if (st.has_sched && it >= 0 && it < kMaxSchedule) tau = st.tau_sched[it];
 
     const double *pj = st.partial + prev * st.partial_stride + (int64_t)j * prev_blocks * R;
     const double tot = reduce_partials<kBlock>(pj, prev_blocks, R, R, s_red);
@@ -568,6 +583,23 @@ __global__ void preclip_export_kernel(CcState st, int32_t n, double *out)
 {
     const int j = blockIdx.x;
     for (int i = threadIdx.x; i < n; i += blockDim.x) out[(int64_t)i * st.P + j] = st.scale[(int64_t)j * st.R + i];
+}
+
+// Verification 3 of Alg. 6: check_ij = [norm_ij > Delta_max], votes per partition and the
+// strict-majority trigger of CheckAveraging.  One thread per partition.
+__global__ void verification3_kernel(const double *norms, int32_t n, int32_t P, double delta_max,
+                                     uint8_t *check, int32_t *votes, uint8_t *trigger)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= P) return;
+    int cnt = 0;
+    for (int i = 0; i < n; ++i) {
+        const uint8_t c = norms[(int64_t)i * P + j] > delta_max ? 1 : 0;
+        check[(int64_t)i * P + j] = c;
+        cnt += c;
+    }
+    votes[j] = cnt;
+    trigger[j] = (2 * cnt > n) ? 1 : 0;
 }
 
 }  // namespace btard

@@ -282,6 +282,8 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
     row_sum16x2(q, c * y, fabs(c) * rt, qv, Sc);
 
     while (!dn) {                             // wavefront-uniform
+        // (tau_l of eq. (5) if the caller gave a schedule)
+        const double tau = (a.st.has_sched && it < kMaxSchedule) ? a.st.tau_sched[it] : a.tau;
         // norms, weights and how wrong the weights may be
         const double N2 = fmax(diag - 2.0 * y + qv, 0.0);
         const double eN2 = kGramUnit * (rt + Sc) * (rt + Sc);
@@ -289,14 +291,14 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         if (__any(peer && !isfinite(Nn))) { it = -1; dn = 1; break; }
         double w = 0.0, err_w = 0.0;
         if (peer) {
-            w = (Nn <= a.tau) ? 1.0 : a.tau / Nn;
+            w = (Nn <= tau) ? 1.0 : tau / Nn;
             // a weight that is (or may be) tau/N inherits half the relative error of N^2;
             // its contribution to v is w * N <= tau
-            if (N2 + eN2 > a.tau * a.tau) {
+            if (N2 + eN2 > tau * tau) {
                 // (error bars are bounds: hardware reciprocal / square-root estimates,
                 // rounded up by 1 %, instead of full divisions)
                 const double rel = (N2 > eN2) ? 0.505 * eN2 * __builtin_amdgcn_rcp(N2) : 1.0;
-                err_w = rel * fmin(Nn, a.tau) * inv_n;
+                err_w = rel * fmin(Nn, tau) * inv_n;
             }
         }
         double W, E;

@@ -471,6 +471,74 @@ def test_preclipped_configs_reduced_length(dev, cfg, d):
 
 
 # --------------------------------------------------------------------------
+# tau_l schedule of eq. (5) and Verification 3 of Alg. 6
+# --------------------------------------------------------------------------
+def test_tau_schedule_matches_the_oracle():
+    for delta, sigma, b0, L in [(0.1, 1.0, 10.0, 50), (0.05, 0.3, 0.0, 7), (0.15, 2.0, 1.0, 1024)]:
+        got = np.array(btard.tau_schedule(delta, sigma, b0, L))
+        ref, _ = oracle.tau_schedule(delta, sigma, b0, L)
+        np.testing.assert_allclose(got, ref.astype(np.float32), rtol=1.2e-7)
+    with pytest.raises(btard.BtardError):
+        btard.tau_schedule(0.0, 1.0, 1.0, 3)
+
+
+@pytest.mark.parametrize("n,d,P,flags", [(7, 3001, 3, 0), (16, 70001, 16, 0), (16, 70001, 16, 1),
+                                         (40, 9000, 5, 0), (12, 20000, 5, 1)])
+def test_scheduled_radii_match_the_oracle(dev, n, d, P, flags):
+    G, off = workloads.generic_case(n, d, P, seed=3 * n + d, device=dev, spread=0.05,
+                                    outliers=max(1, n // 4), outlier_scale=20.0)
+    M = 30
+    # radii shrinking from far above to far below the honest spread (as eq. (5) does when
+    # B_0 is large), so early updates are mean-like and late ones clip everything
+    sched = btard.tau_schedule(0.1, 0.05 * math.sqrt(d / P) / 6.0, 40.0 * math.sqrt(d / P), M)
+    assert sched[0] > 4 * sched[-1]
+    for eps in (1e-6, 0.0):
+        p = btard.make_problem(G, off, 1.0, eps, M, flags=flags, tau_schedule=sched)
+        btard.cc_begin(p); btard.cc_gram(p)
+        left = btard.cc_remaining(p)
+        btard.cc_iterate(p, 0, left)
+        v, iters, sn, out = btard.cc_finish_verify(p, left, 0xBEE)
+        torch.cuda.synchronize()
+        Gh = G.cpu().numpy()
+        vo, ito, sno, _ = oracle.centered_clip(Gh, off, 1.0, eps, M, tau_l=sched)
+        np.testing.assert_array_equal(iters.cpu().numpy(), ito)
+        assert rel_l2(v.cpu().numpy(), vo) <= V_TOL
+        np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=1e-4, atol=1e-11)
+        # the verification weights use the constant tau of the problem (Alg. 6 has one tau)
+        ref = oracle.verify(Gh, off, v.cpu().numpy().astype(np.float64), 1.0, 0xBEE)
+        np.testing.assert_allclose(out["norms"].cpu().numpy(), ref["norms"], rtol=1e-6, atol=1e-9)
+        assert rel_l2(out["proj"].cpu().numpy(), ref["proj"]) <= PROJ_TOL
+    # a constant schedule is the constant-tau run
+    a = btard.make_problem(G, off, 0.7, 1e-6, M, flags=flags, tau_schedule=[0.7] * M)
+    btard.cc_begin(a); btard.cc_gram(a); btard.cc_iterate(a, 0, M)
+    va = btard.cc_finish(a, M)
+    vb = btard.centered_clip(G, off, 0.7, 1e-6, M, flags=flags)
+    torch.cuda.synchronize()
+    assert torch.equal(va[0], vb[0]) and torch.equal(va[1], vb[1])
+    with pytest.raises(btard.BtardError):
+        btard.cc_begin(btard.make_problem(G, off, 1.0, 1e-6, 3, tau_schedule=[1.0, 0.0, 1.0]))
+
+
+def test_verification3_flags(dev):
+    G, off = workloads.generic_case(9, 4000, 6, seed=77, device=dev, spread=0.05, outliers=3,
+                                    outlier_scale=3.0)
+    v, iters, sn = btard.centered_clip(G, off, 1.0, 1e-6, 40)
+    out = btard.verify_projections(G, off, v, 1.0, 5)
+    norms = out["norms"]
+    torch.cuda.synchronize()
+    nh = norms.cpu().numpy()
+    for delta_max in (float(np.median(nh)), 0.0, 1e30, float(nh.max())):
+        check, votes, trigger = btard.verification3(norms, delta_max)
+        torch.cuda.synchronize()
+        c_ref, v_ref, t_ref = oracle.verification3(nh, delta_max)
+        assert np.array_equal(check.cpu().numpy(), c_ref)
+        assert np.array_equal(votes.cpu().numpy(), v_ref)
+        assert np.array_equal(trigger.cpu().numpy(), t_ref)
+    check, votes, trigger = btard.verification3(norms, float(np.median(nh)))
+    assert 0 < int(votes.sum()) < nh.size
+
+
+# --------------------------------------------------------------------------
 # the five benchmark configurations: reduced length (whole oracle) and full size
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("cfg,d", [(1, 1 << 16), (2, 400_003), (3, 1_200_000), (4, 1 << 20),
