@@ -262,9 +262,9 @@ def main() -> int:
             left = 0 if host_sync else complete_headline()
             return ms, seg, left
 
-        # (the Gram formulation serves n <= 16; beyond that every pass is a streaming pass
+        # (the Gram formulation serves n <= 64; beyond that every pass is a streaming pass
         # and the step cannot skip the look at what is left)
-        synced = args.host_sync or n > 16
+        synced = args.host_sync or n > 64
         ms, seg, left = headline_numbers(synced, args.steps)
         unsync_note = None
         if left > 0:

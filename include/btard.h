@@ -47,7 +47,7 @@ typedef enum btard_status {
 /* btard_centered_clip / btard_cc_*: run the iteration on the n x n Gram matrix of each
  * partition (one pass over the data for all iterations) wherever that is accurate enough
  * to reproduce the plain iteration, and fall back to one pass per iteration elsewhere.
- * Takes effect for n <= 16 and v0 == NULL; ignored otherwise.  Same results contract. */
+ * Takes effect for n <= 64 and v0 == NULL; ignored otherwise.  Same results contract. */
 #define BTARD_FLAG_GRAM 1u
 /* btard_centered_clip with BTARD_FLAG_GRAM: allow ONE synchronisation of the stream inside
  * the call (after the Gram iteration), so that the per-iteration passes are only enqueued
@@ -302,8 +302,9 @@ int btard_debug_zhat(uint64_t seed, int64_t x_begin, int64_t count, float *out,
 
 /*
  * Test hook for the Gram formulation: writes the n x n Gram matrix G G^T of every
- * partition (fp64, zero-padded to 16 x 16, row-major, parts * 256 entries) to DEVICE
- * gram_out.  Needs n <= 16.  Uses the workspace of `p`.
+ * partition (fp64, row-major, zero-padded to 16 x 16 for n <= 16 and to 64 x 64 for
+ * 16 < n <= 64: parts * 256 or parts * 4096 entries) to DEVICE gram_out.  Uses the
+ * workspace of `p`.
  */
 int btard_debug_gram(const btard_cc_problem *p, double *gram_out);
 

@@ -248,7 +248,8 @@ def cc_remaining(p: Problem) -> int:
 
 
 def debug_gram(p: Problem) -> torch.Tensor:
-    out = torch.empty((p.parts, 16, 16), dtype=torch.float64, device=p.g.device)
+    N = 16 if int(p.g.shape[0]) <= 16 else 64
+    out = torch.empty((p.parts, N, N), dtype=torch.float64, device=p.g.device)
     _check(load_library().btard_debug_gram(ctypes.byref(p.c), _ptr(out)), "btard_debug_gram")
     return out
 

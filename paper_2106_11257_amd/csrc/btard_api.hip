@@ -49,7 +49,8 @@ WsLayout ws_layout(int32_t n, int32_t P)
     const size_t blocks = (size_t)(P > kMaxBlocks ? P : kMaxBlocks);
     L.partial_stride_doubles = align_up(sizeof(double) * blocks * S) / sizeof(double);
     L.partial = p;  p = align_up(p + 2 * sizeof(double) * L.partial_stride_doubles);
-    L.gram = p;     p = align_up(p + sizeof(double) * blocks * kGramEntries);   // partial Gram matrices
+    // partial Gram matrices: one 16 x 16 block per workgroup, or the 10 block pairs of n <= 64
+    L.gram = p;     p = align_up(p + sizeof(double) * blocks * (n > kGramPeers ? kWideEntries : kGramEntries));
     L.total = p;
     return L;
 }
@@ -359,26 +360,35 @@ int btard_cc_begin(const btard_cc_problem *p)
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
-// The Gram formulation is built for one 16 x 16 MFMA block and a start at the mean.
+// The Gram formulation is built for up to 4 x 4 MFMA blocks of 16 peers and a start at the mean.
+constexpr int kGramMaxPeers = 16 * kWideBlocks;
 static bool gram_applies(const btard_cc_problem *p)
 {
-    return (p->flags & BTARD_FLAG_GRAM) != 0 && p->n <= kGramPeers && p->v0 == nullptr &&
+    return (p->flags & BTARD_FLAG_GRAM) != 0 && p->n <= kGramMaxPeers && p->v0 == nullptr &&
            p->max_iters > 0;
 }
 
-// n <= 8: two coordinates per MFMA row block (512-wide tiles), else one (256-wide)
+// n <= 8: two coordinates per MFMA row block (512-wide tiles); n <= 16: one block (256-wide);
+// n <= 64: ceil(n / 16) blocks of peers, the block pairs on and above the diagonal (64-wide)
 typedef void (*GramFn)(GramArgs);
+static int gram_peer_blocks(const btard_cc_problem *p) { return (p->n + 15) / 16; }
 static GramFn gram_kernel(const btard_cc_problem *p)
 {
-    return p->n <= kGramPeers / 2 ? gram_pass_kernel<true> : gram_pass_kernel<false>;
+    if (p->n <= kGramPeers / 2) return gram_pass_kernel<true>;
+    if (p->n <= kGramPeers) return gram_pass_kernel<false>;
+    switch (gram_peer_blocks(p)) {
+        case 2: return gram_pass_wide_kernel<2>;
+        case 3: return gram_pass_wide_kernel<3>;
+        default: return gram_pass_wide_kernel<4>;
+    }
 }
 
 static int gram_blocks(const btard_cc_problem *p)
 {
     const int resident = resident_blocks(reinterpret_cast<const void *>(gram_kernel(p)));
     if (resident <= 0) return 0;
-    return blocks_per_partition(resident, p->parts, p->offsets_host,
-                                p->n <= kGramPeers / 2 ? 512 : 256);
+    const int tile = p->n <= kGramPeers / 2 ? 512 : (p->n <= kGramPeers ? 256 : 64);
+    return blocks_per_partition(resident, p->parts, p->offsets_host, tile);
 }
 
 int btard_cc_gram_matrix(const btard_cc_problem *p)
@@ -413,7 +423,11 @@ int btard_cc_gram_iterate(const btard_cc_problem *p)
     gi.blocks = B; gi.n = p->n;
     gi.tau = (double)p->tau; gi.eps = (double)p->eps; gi.max_iters = p->max_iters;
     gi.lambda = preclip_on(p) ? (double)p->preclip : 0.0;
-    hipLaunchKernelGGL(gram_iterate_kernel, dim3(p->parts), dim3(kBlock), 0, s, gi);
+    gi.nb = gram_peer_blocks(p);
+    if (p->n <= kGramPeers)
+        hipLaunchKernelGGL(gram_iterate_kernel<16>, dim3(p->parts), dim3(kBlock), 0, s, gi);
+    else
+        hipLaunchKernelGGL(gram_iterate_kernel<64>, dim3(p->parts), dim3(kBlock), 0, s, gi);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
@@ -447,7 +461,7 @@ int btard_debug_gram(const btard_cc_problem *p, double *gram_out)
 {
     const int rc = check_problem(p);
     if (rc != BTARD_OK) return rc;
-    if (!gram_out || p->n > kGramPeers) return BTARD_ERR_INVALID_ARG;
+    if (!gram_out || p->n > kGramMaxPeers) return BTARD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     const int B = gram_blocks(p);
     if (B <= 0) return BTARD_ERR_DEVICE;
@@ -459,8 +473,12 @@ int btard_debug_gram(const btard_cc_problem *p, double *gram_out)
     ga.g = p->g; ga.ld = p->ldg; ga.n = p->n; ga.off = st.off;
     ga.gpart = reinterpret_cast<double *>(static_cast<char *>(p->workspace) + L.gram);
     hipLaunchKernelGGL(gram_kernel(p), dim3(B, p->parts), dim3(kBlock), 0, s, ga);
-    hipLaunchKernelGGL(gram_debug_kernel, dim3(p->parts), dim3(kGramEntries), 0, s, ga.gpart, B,
-                       gram_out);
+    if (p->n <= kGramPeers)
+        hipLaunchKernelGGL(gram_debug_kernel, dim3(p->parts), dim3(kGramEntries), 0, s, ga.gpart, B,
+                           gram_out);
+    else
+        hipLaunchKernelGGL(gram_debug_wide_kernel, dim3(p->parts), dim3(kBlock), 0, s, ga.gpart, B,
+                           gram_peer_blocks(p), gram_out);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 

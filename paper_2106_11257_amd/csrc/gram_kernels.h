@@ -125,6 +125,119 @@ __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
     a.gpart[((int64_t)j * gridDim.x + blockIdx.x) * kGramEntries + t] = s;
 }
 
+// ---------------------------------------------------------------------------
+// 16 < n <= 64: Gamma is NB x NB blocks of 16 x 16 (NB = ceil(n / 16)), of which the
+// NB (NB + 1) / 2 on and above the diagonal are formed: per 4 coordinates one operand
+// register per block of peers, and one MFMA per pair of blocks (b <= c) with block b's
+// values as the first and block c's as the second operand.  Tiles are 64 coordinates (each
+// lane holds 4 coordinates of its peer in each of the NB blocks).  The workgroup's partial
+// result is kWidePairs x 256 doubles: pair (b, c) at slot wide_pair(b, c), entry (i, k) of
+// the block at i * 16 + k = Gamma[16 b + i][16 c + k] (slots of absent blocks stay unwritten
+// and unread).  With 10 MFMAs per 4 coordinates at NB = 4 the pass is bound by the fp64
+// MFMA issue rate, about 2.7 times the time of reading the slab.
+// ---------------------------------------------------------------------------
+constexpr int kWideBlocks = 4;                                     // n <= 64
+constexpr int kWidePairs = kWideBlocks * (kWideBlocks + 1) / 2;    // 10
+constexpr int kWideEntries = kWidePairs * kGramEntries;
+__host__ __device__ constexpr int wide_pair(int b, int c) { return b * kWideBlocks - b * (b - 1) / 2 + (c - b); }
+
+template <int NB>
+__global__ __launch_bounds__(kBlock) void gram_pass_wide_kernel(GramArgs a)
+{
+    constexpr int kW = 64;
+    constexpr int kPairs = NB * (NB + 1) / 2;
+    __shared__ double sh[kPairs * kGramEntries];
+    const int j = blockIdx.y;
+    const int n = a.n;
+    const int64_t lo = a.off[j], hi = a.off[j + 1];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int p = lane & 15, q = lane >> 4;
+    bool have[NB];
+    global_f32 row[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        have[b] = 16 * b + p < n;
+        row[b] = (global_f32)a.g + (int64_t)(have[b] ? 16 * b + p : n - 1) * a.ld;
+    }
+
+    f64x4 acc[kPairs];
+#pragma unroll
+    for (int t = 0; t < kPairs; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+    const TileRange tr = tile_range<kW>(lo, hi);
+    for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
+        const int64_t xu = tr.xa + u * kW;
+        const bool interior = (xu >= lo) && (xu + kW <= hi);     // wavefront-uniform
+        float val[NB][4][4];
+        if (interior) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const f32x4_u t = *(global_f32x4)(row[b] + xu + 4 * q + 16 * s);
+                    val[b][s][0] = t.x; val[b][s][1] = t.y; val[b][s][2] = t.z; val[b][s][3] = t.w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int64_t x = xu + 16 * s + 4 * q + e;
+                        val[b][s][e] = (x >= lo && x < hi) ? row[b][x] : 0.0f;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                double d[NB];
+#pragma unroll
+                for (int b = 0; b < NB; ++b) d[b] = have[b] ? (double)val[b][s][e] : 0.0;
+                int t = 0;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                    for (int c = b; c < NB; ++c) {
+                        acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(d[b], d[c], acc[t], 0, 0, 0);
+                        ++t;
+                    }
+                }
+            }
+        }
+    }
+
+    // workgroup partial: the 4 wavefronts' matrices added in order through one LDS copy
+#pragma unroll 1
+    for (int w = 0; w < kWaves; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int t = 0; t < kPairs; ++t) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int idx = t * kGramEntries + gram_entry(lane, r);
+                    sh[idx] = (w == 0) ? acc[t][r] : sh[idx] + acc[t][r];
+                }
+            }
+        }
+        __syncthreads();
+    }
+    double *out = a.gpart + ((int64_t)j * gridDim.x + blockIdx.x) * kWideEntries;
+    int t = 0;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+#pragma unroll
+        for (int c = b; c < NB; ++c) {
+            out[wide_pair(b, c) * kGramEntries + threadIdx.x] = sh[t * kGramEntries + threadIdx.x];
+            ++t;
+        }
+    }
+}
+
 struct GramIterArgs {
     CcState st;
     const double *gpart;
@@ -133,6 +246,7 @@ struct GramIterArgs {
     double tau, eps;
     int32_t max_iters;
     double lambda;           // pre-clipping radius (BTARD-Clipped-SGD); <= 0: none
+    int32_t nb;              // wide layout only: blocks of 16 peers that were formed
 };
 
 // Relative accuracy assumed for a Gram entry and for a quadratic form in it, in units of
@@ -202,20 +316,61 @@ __device__ __forceinline__ void row_sum16x2(int q, double a0, double a1, double 
     s1 = lane_value<31>(x);
 }
 
+// Value of lane k for every lane, k known after unrolling.
+__device__ __forceinline__ double lane_value_at(double x, int k)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, k);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), k);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
 // sum_k row[k] * (value of x in lane k)
 template <int N>
 __device__ __forceinline__ double row_dot(const double (&row)[N], double x)
 {
     double y = 0.0;
-    y = fma(row[0], lane_value<0>(x), y);   y = fma(row[1], lane_value<1>(x), y);
-    y = fma(row[2], lane_value<2>(x), y);   y = fma(row[3], lane_value<3>(x), y);
-    y = fma(row[4], lane_value<4>(x), y);   y = fma(row[5], lane_value<5>(x), y);
-    y = fma(row[6], lane_value<6>(x), y);   y = fma(row[7], lane_value<7>(x), y);
-    y = fma(row[8], lane_value<8>(x), y);   y = fma(row[9], lane_value<9>(x), y);
-    y = fma(row[10], lane_value<10>(x), y); y = fma(row[11], lane_value<11>(x), y);
-    y = fma(row[12], lane_value<12>(x), y); y = fma(row[13], lane_value<13>(x), y);
-    y = fma(row[14], lane_value<14>(x), y); y = fma(row[15], lane_value<15>(x), y);
+#pragma unroll
+    for (int k = 0; k < N; ++k) y = fma(row[k], lane_value_at(x, k), y);
     return y;
+}
+
+// Sum over all 64 lanes (one peer per lane): DPP within the rows of 16, then the four row
+// sums by v_readlane.
+__device__ __forceinline__ double wave_sum64(double x)
+{
+    x += row_shift_right<0x111>(x);
+    x += row_shift_right<0x112>(x);
+    x += row_shift_right<0x114>(x);
+    x += row_shift_right<0x118>(x);
+    return (lane_value<15>(x) + lane_value<31>(x)) + (lane_value<47>(x) + lane_value<63>(x));
+}
+
+// The reductions of the iteration for either lane layout: N = 16 (peers replicated in the
+// four rows of 16 lanes, row q reduces quantity q) or N = 64 (one peer per lane).
+template <int N>
+__device__ __forceinline__ void peers_sum2(int q, double a0, double a1, double &s0, double &s1)
+{
+    if constexpr (N == 16) {
+        row_sum16x2(q, a0, a1, s0, s1);
+    } else {
+        s0 = wave_sum64(a0);
+        s1 = wave_sum64(a1);
+    }
+}
+
+template <int N>
+__device__ __forceinline__ void peers_sum4(int q, double a0, double a1, double a2, double a3,
+                                           double &s0, double &s1, double &s2, double &s3)
+{
+    if constexpr (N == 16) {
+        row_sum16x4(q, a0, a1, a2, a3, s0, s1, s2, s3);
+    } else {
+        s0 = wave_sum64(a0);
+        s1 = wave_sum64(a1);
+        s2 = wave_sum64(a2);
+        s3 = wave_sum64(a3);
+    }
 }
 
 // One workgroup per partition: the whole iteration of eq. (CenteredClip) on the Gram
@@ -224,20 +379,40 @@ __device__ __forceinline__ double row_dot(const double (&row)[N], double x)
 // After the workgroup has summed the partial matrices, one wavefront runs the iteration
 // in registers: lane i (mod 16) owns peer i and row i of Gamma; the scalars every peer
 // needs travel by v_readlane broadcasts and DPP row shifts, with no LDS and no barriers.
+// N = 16: the layout above (peers replicated in the four rows of 16 lanes); N = 64 (n <= 64):
+// lane i owns peer i and the partial matrices come in the block-pair layout of
+// gram_pass_wide_kernel.
+template <int N>
 __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
 {
-    constexpr int N = kGramPeers;
+    static_assert(N == 16 || N == 64, "one 16 x 16 block or 4 x 4 of them");
     __shared__ double G[N][N + 1];
     const int j = blockIdx.x;
     const int t = threadIdx.x;
     const int n = a.n, R = a.st.R;
 
-    {   // Gamma = sum of the workgroups' partial matrices, in order
+    // Gamma = sum of the workgroups' partial matrices, in order
+    if constexpr (N == 16) {
         const double *pj = a.gpart + (int64_t)j * a.blocks * kGramEntries;
         double s = 0.0;
 #pragma unroll 8
         for (int b = 0; b < a.blocks; ++b) s += pj[(int64_t)b * kGramEntries + t];
         G[t / N][t % N] = s;
+    } else {
+        const double *pj = a.gpart + (int64_t)j * a.blocks * kWideEntries;
+        for (int e = t; e < N * N; e += kBlock) {
+            const int I = e / N, K = e % N;
+            const int bI = I >> 4, bK = K >> 4;
+            double s = 0.0;
+            if (bI < a.nb && bK < a.nb) {
+                // stored on and above the diagonal of blocks; below it, the transpose
+                const int src = (bI <= bK) ? wide_pair(bI, bK) * kGramEntries + (I & 15) * 16 + (K & 15)
+                                           : wide_pair(bK, bI) * kGramEntries + (K & 15) * 16 + (I & 15);
+#pragma unroll 4
+                for (int b = 0; b < a.blocks; ++b) s += pj[(int64_t)b * kWideEntries + src];
+            }
+            G[I][K] = s;
+        }
     }
     __syncthreads();
     if (a.lambda > 0.0) {
@@ -253,12 +428,12 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
             if (t < n) a.st.scale[(int64_t)j * R + t] = al;
         }
         __syncthreads();
-        G[t / N][t % N] *= s_alpha[t / N] * s_alpha[t % N];
+        for (int e = t; e < N * N; e += kBlock) G[e / N][e % N] *= s_alpha[e / N] * s_alpha[e % N];
         __syncthreads();
     }
     if (t >= 64) return;
 
-    const int i = t & 15;
+    const int i = (N == 16) ? (t & 15) : t;
     const bool peer = i < n;
     double row[N];
 #pragma unroll
@@ -279,7 +454,7 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
     // sums for the new c ride along in the reduction that gives the update's norm.
     double y = row_dot<N>(row, c);
     double qv, Sc;
-    row_sum16x2(q, c * y, fabs(c) * rt, qv, Sc);
+    peers_sum2<N>(q, c * y, fabs(c) * rt, qv, Sc);
 
     while (!dn) {                             // wavefront-uniform
         // (tau_l of eq. (5) if the caller gave a schedule)
@@ -302,7 +477,7 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
             }
         }
         double W, E;
-        row_sum16x2(q, w, err_w, W, E);
+        peers_sum2<N>(q, w, err_w, W, E);
         const double ev_new = ev + E;
         // the update this would apply, and its norm sqrt(a^T Gamma a)
         const double an = peer ? (w - W * c) / (double)n : 0.0;
@@ -310,7 +485,7 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         const double cn = c + an;
         double yn = y + u;
         double Tn2, Sa, Scn, qvn;
-        row_sum16x4(q, an * u, fabs(an) * rt, fabs(cn) * rt, cn * yn, Tn2, Sa, Scn, qvn);
+        peers_sum4<N>(q, an * u, fabs(an) * rt, fabs(cn) * rt, cn * yn, Tn2, Sa, Scn, qvn);
         const double T = sqrt(fmax(Tn2, 0.0));
         // error budget: the (generously bounded, never discounted) error put into v must
         // stay a small fraction of ||v|| and of the step itself (whose norm is compared
@@ -325,7 +500,7 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
             // (y by running sums drifts by a rounding per update: recomputed now and then,
             // the drift stays a small fraction of the assumed accuracy kGramUnit)
             yn = row_dot<N>(row, c);
-            row_sum16x2(q, c * yn, fabs(c) * rt, qvn, Scn);
+            peers_sum2<N>(q, c * yn, fabs(c) * rt, qvn, Scn);
         }
         y = yn;
         qv = qvn;
@@ -352,7 +527,7 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         const double yf = row_dot<N>(row, c);            // afresh, not the running sums
         const double uf = row_dot<N>(row, al);
         double qf, Sf, Tf, Sa;
-        row_sum16x4(q, c * yf, fabs(c) * rt, al * uf, fabs(al) * rt, qf, Sf, Tf, Sa);
+        peers_sum4<N>(q, c * yf, fabs(c) * rt, al * uf, fabs(al) * rt, qf, Sf, Tf, Sa);
         N2f = fmax(diag - 2.0 * yf + qf, 0.0);
         const double eN2 = kGramUnit * (rt + Sf) * (rt + Sf);
         T2f = fmax(Tf, 0.0);
@@ -360,12 +535,15 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         const bool bad = peer && !(eN2 <= kGramVouch * N2f);
         ok = !__any(bad) && (eT2 <= kGramVouch * T2f || Sa == 0.0);
     }
-    if (t < R) {
-        a.st.coef[(int64_t)j * R + t] = (t < n) ? c : 0.0;
-        a.st.delta[(int64_t)j * R + t] = (t < n) ? al : 0.0;
-        a.st.gram_n2[(int64_t)j * R + t] = (t < n) ? N2f : 0.0;
+    if (t < n) {                                  // (N = 16: lanes 0..15 hold peers 0..15)
+        a.st.coef[(int64_t)j * R + t] = c;
+        a.st.delta[(int64_t)j * R + t] = al;
+        a.st.gram_n2[(int64_t)j * R + t] = N2f;
     }
     if (t == 0) {
+        a.st.coef[(int64_t)j * R + n] = 0.0;      // the start vector's slot
+        a.st.delta[(int64_t)j * R + n] = 0.0;
+        a.st.gram_n2[(int64_t)j * R + n] = 0.0;
         a.st.iters[j] = it;
         a.st.done[j] = dn;
         a.st.final_buf[j] = 0;
@@ -383,6 +561,25 @@ __global__ void gram_debug_kernel(const double *gpart, int32_t blocks, double *o
     double s = 0.0;
     for (int b = 0; b < blocks; ++b) s += pj[(int64_t)b * kGramEntries + t];
     out[(int64_t)j * kGramEntries + t] = s;
+}
+
+// The same for the block-pair layout: the full symmetric 64 x 64 matrix of partition j.
+__global__ void gram_debug_wide_kernel(const double *gpart, int32_t blocks, int32_t nb, double *out)
+{
+    constexpr int N = 16 * kWideBlocks;
+    const int j = blockIdx.x;
+    const double *pj = gpart + (int64_t)j * blocks * kWideEntries;
+    for (int e = threadIdx.x; e < N * N; e += blockDim.x) {
+        const int I = e / N, K = e % N;
+        const int bI = I >> 4, bK = K >> 4;
+        double s = 0.0;
+        if (bI < nb && bK < nb) {
+            const int src = (bI <= bK) ? wide_pair(bI, bK) * kGramEntries + (I & 15) * 16 + (K & 15)
+                                       : wide_pair(bK, bI) * kGramEntries + (K & 15) * 16 + (I & 15);
+            for (int b = 0; b < blocks; ++b) s += pj[(int64_t)b * kWideEntries + src];
+        }
+        out[(int64_t)j * N * N + e] = s;
+    }
 }
 
 }  // namespace btard

@@ -243,7 +243,8 @@ def test_zhat_matches_the_z_spec(dev):
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("n,d,P,pad", [(3, 1031, 2, 0), (9, 5000, 4, 2), (16, 70001, 16, 0),
                                        (16, 262147, 3, 5), (1, 300, 2, 1), (12, 7, 3, 0), (8, 5003, 3, 1),
-                                       (5, 40001, 2, 3)])
+                                       (5, 40001, 2, 3), (17, 3000, 2, 1), (33, 2000, 3, 1),
+                                       (40, 70003, 4, 0), (64, 20000, 64, 0), (64, 333, 1, 2)])
 def test_gram_matrix_matches_matmul(dev, n, d, P, pad):
     G, off = workloads.generic_case(n, d, P, seed=31 * n + d, device=dev, ld=d + pad, spread=0.5,
                                     outliers=n // 3)
@@ -252,14 +253,15 @@ def test_gram_matrix_matches_matmul(dev, n, d, P, pad):
     Gh = G.cpu().numpy().astype(np.float64)
     for j in range(P):
         X = Gh[:, off[j]:off[j + 1]]
-        ref = np.zeros((16, 16))
+        N = 16 if n <= 16 else 64
+        ref = np.zeros((N, N))
         ref[:n, :n] = X @ X.T
         scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref))) + 1e-300
         assert np.abs(got[j] - ref).max() <= 1e-13 * scale.max(), f"partition {j}"
         assert (got[j] == got[j].T).all()
 
 
-@pytest.mark.parametrize("n,d,P,pad,outliers", [s for s in SHAPES if s[0] <= 16])
+@pytest.mark.parametrize("n,d,P,pad,outliers", [s for s in SHAPES if s[0] <= 64])
 def test_gram_path_small_shapes(dev, n, d, P, pad, outliers):
     G, off = workloads.generic_case(n, d, P, seed=n * 1000 + d, device=dev, ld=d + pad,
                                     spread=0.05, outliers=outliers)
@@ -335,7 +337,8 @@ def test_gram_last_pass_without_waiting_for_the_iteration(dev):
         assert rel_l2(pr, ref["proj"]) <= 1e-4
 
 
-@pytest.mark.parametrize("cfg,d", [(1, 1 << 16), (2, 400_003), (4, 1 << 20), (5, 1_600_016)])
+@pytest.mark.parametrize("cfg,d", [(1, 1 << 16), (2, 400_003), (3, 300_000), (4, 1 << 20),
+                                   (5, 1_600_016)])
 def test_gram_path_configs_reduced_length(dev, cfg, d):
     wl = workloads.make_workload(cfg, device=dev, d=d)
     check_cc(wl.G, wl.offsets, wl.tau, wl.eps, wl.max_iters, label=wl.name,
