@@ -104,8 +104,8 @@ __device__ __forceinline__ void fused_rows(float *__restrict__ v, uint64_t seed,
 // cc_finish_verify_kernel (<zhat, r_i> = <zhat, g_i> - <zhat, v>; workgroup 0 supplies the
 // known norms), so the kernel that follows does not care which of the two ran.
 // ---------------------------------------------------------------------------
-template <int NP, bool INTERIOR>
-__device__ __forceinline__ void project_rows(float *__restrict__ v, uint64_t seed, int sub,
+template <int NP, int LG, bool INTERIOR>
+__device__ __forceinline__ void project_rows(float *__restrict__ v, uint64_t seed, int lg, int sub,
                                              int64_t xu, int64_t lo, int64_t hi,
                                              float (&val)[NP][4], const double (&c)[NP],
                                              double (&accR)[NP], double &zv, double &z2)
@@ -132,30 +132,36 @@ __device__ __forceinline__ void project_rows(float *__restrict__ v, uint64_t see
     }
     float vf[4];
 #pragma unroll
-    for (int e = 0; e < kVec; ++e) vf[e] = (float)vv[e];
-    if (INTERIOR) {
-        f32x4_u o;
-        o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
-        stream_store(v + x0, o);
-    } else {
+    for (int e = 0; e < kVec; ++e) {
+        vv[e] = sum_across_groups<Geo<NP, LG>::kLanes>(vv[e]);   // (nothing to do with one group)
+        vf[e] = (float)vv[e];
+    }
+    if (lg == 0) {
+        if (INTERIOR) {
+            f32x4_u o;
+            o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
+            stream_store(v + x0, o);
+        } else {
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) {
+                const int64_t x = x0 + e;
+                if (x >= lo && x < hi) v[x] = vf[e];
+            }
+        }
 #pragma unroll
         for (int e = 0; e < kVec; ++e) {
-            const int64_t x = x0 + e;
-            if (x >= lo && x < hi) v[x] = vf[e];
+            zv = fma(z[e], (double)vf[e], zv);
+            z2 = fma(z[e], z[e], z2);
         }
-    }
-#pragma unroll
-    for (int e = 0; e < kVec; ++e) {
-        zv = fma(z[e], (double)vf[e], zv);
-        z2 = fma(z[e], z[e], z2);
     }
 }
 
-template <int NP, bool RAGGED>
+template <int NP, int LG, bool RAGGED>
 __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, double *s_c,
-                                                  double *s_a, double (&sh)[kWaves][2 * NP + 2])
+                                                  double *s_a,
+                                                  double (&sh)[kWaves][2 * NP * LG + 2])
 {
-    using G = Geo<NP, 1>;
+    using G = Geo<NP, LG>;
     const int n = a.n, S = a.S, R = a.st.R;
     if ((int)threadIdx.x < R) {                      // final state: buffer 0
         // With pre-clipping v = sum_i c_i (alpha_i g_i): the factor joins the coefficient,
@@ -171,42 +177,50 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
     const int64_t lo = a.st.off[j], hi = a.st.off[j + 1];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int sub = lane;
+    const int lg = lane / G::kLanes, sub = lane % G::kLanes;
 
     double c[NP], dl[NP], cb, db;
-    fetch_coefficients<NP, 1, RAGGED>(s_c, s_a, n, 0, c, dl, cb, db);
+    fetch_coefficients<NP, LG, RAGGED>(s_c, s_a, n, lg, c, dl, cb, db);
     double accR[NP];
 #pragma unroll
     for (int k = 0; k < NP; ++k) accR[k] = 0.0;
     double zv = 0.0, z2 = 0.0;
 
-    // interior tiles, two register sets taking turns (see cc_finish_verify_kernel) ...
+    // interior tiles, two register sets taking turns (see cc_finish_verify_kernel; one set
+    // with several lane groups, whose coefficients take vector registers) ...
     const TileRange tr = tile_range<G::kW>(lo, hi);
     const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
-    if (iw.begin < iw.end) {
+    if constexpr (LG > 1) {
+        for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
+            const int64_t xu = tr.xa + u * G::kW;
+            float val[NP][4];
+            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, true, val);
+            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, xu, lo, hi, val, c, accR, zv, z2);
+        }
+    } else if (iw.begin < iw.end) {
         float va[NP][4], vb[NP][4];
         int64_t u = iw.begin;
         bool last_in_b = false;
-        load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u * G::kW, lo, hi, true, va);
+        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u * G::kW, lo, hi, true, va);
         for (;;) {
             const int64_t u1 = u + tr.stride;
             if (u1 >= iw.end) break;                 // the last tile is in va
-            load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u1 * G::kW, lo, hi, true, vb);
-            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
+            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u1 * G::kW, lo, hi, true, vb);
+            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
             const int64_t u2 = u1 + tr.stride;
             if (u2 >= iw.end) {                      // the last tile is in vb
                 u = u1;
                 last_in_b = true;
                 break;
             }
-            load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, tr.xa + u2 * G::kW, lo, hi, true, va);
-            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, accR, zv, z2);
+            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u2 * G::kW, lo, hi, true, va);
+            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, accR, zv, z2);
             u = u2;
         }
         if (last_in_b)
-            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, vb, c, accR, zv, z2);
+            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, vb, c, accR, zv, z2);
         else
-            project_rows<NP, true>(a.v, a.seed, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
+            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
     }
     // ... then the partition's first and last tile where they are not interior
 #pragma unroll 1
@@ -216,18 +230,20 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
         const int64_t xu = tr.xa + u * G::kW;
         if (tile_is_interior<G::kW>(xu, lo, hi)) continue;
         float val[NP][4];
-        load_tile<NP, 1, RAGGED>(a.g, a.ld, n, 0, sub, xu, lo, hi, false, val);
-        project_rows<NP, false>(a.v, a.seed, sub, xu, lo, hi, val, c, accR, zv, z2);
+        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, false, val);
+        project_rows<NP, LG, false>(a.v, a.seed, lg, sub, xu, lo, hi, val, c, accR, zv, z2);
     }
 
-    sum_within_group_all<64, NP>(accR);
-    zv = sum_within_group<64>(zv);
-    z2 = sum_within_group<64>(z2);
-    if (lane == 0) {
+    sum_within_group_all<G::kLanes, NP>(accR);
+    zv = sum_within_group<G::kLanes>(zv);
+    z2 = sum_within_group<G::kLanes>(z2);
+    if (sub == 0) {
 #pragma unroll
-        for (int k = 0; k < NP; ++k) sh[wave][k] = accR[k];
-        sh[wave][NP] = zv;
-        sh[wave][NP + 1] = z2;
+        for (int k = 0; k < NP; ++k) sh[wave][lg * NP + k] = accR[k];
+    }
+    if (lane == 0) {
+        sh[wave][G::kPeers] = zv;
+        sh[wave][G::kPeers + 1] = z2;
     }
     __syncthreads();
     const int B = gridDim.x;
@@ -241,10 +257,10 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
         } else if (q < 2 * n) {
             const double al = s_a[q - n];
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) s += al * sh[w][q - n] - sh[w][NP];
+            for (int w = 0; w < kWaves; ++w) s += al * sh[w][q - n] - sh[w][G::kPeers];
         } else if (q == 2 * n) {
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) s += sh[w][NP + 1];
+            for (int w = 0; w < kWaves; ++w) s += sh[w][G::kPeers + 1];
         } else {
             s = first ? a.st.gram_t2[j] : 0.0;
         }
@@ -263,10 +279,10 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
 
     const int j = blockIdx.y;
     const int n = a.n, S = a.S;
-    if constexpr (LG == 1) {
-        // (the Gram formulation serves n <= 16, which is one lane group)
+    if constexpr (LG <= 4) {
+        // (the Gram formulation serves n <= 64: up to four lane groups)
         if (a.use_gram_norms && a.st.gram_ok[j]) {   // uniform
-            project_partition<NP, RAGGED>(a, j, s_c, s_a, sh);
+            project_partition<NP, LG, RAGGED>(a, j, s_c, s_a, sh);
             return;
         }
     }
