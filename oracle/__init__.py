@@ -6,6 +6,8 @@ Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 from .oracle import (  # noqa: F401
     build,
     centered_clip,
+    coordinate_median,
+    geometric_median,
     num_threads,
     philox4x32_10,
     preclip_scales,

@@ -17,6 +17,8 @@
  *   - Delta, norm, w, s: Alg. 1 lines 8-9; Alg. 6 (BTARD) lines 8-12; eq. (2)
  *   - column check:     Alg. 1 line 16; Alg. 6 Verification 2
  *   - tau_l schedule:   App. D.2, eq. (5)
+ *   - baselines:        Sec. 4.1 names them (coordinate-wise and geometric
+ *                       medians); their textbook definitions are used
  *   - Verification 3:   Alg. 6 (BTARD), the block of that name
  *   - pre-clipping:     App. E.3, Alg. 9 (BTARD-Clipped-SGD) line 3 and the
  *                       paragraph after the algorithm (per-partition clipping)
@@ -218,6 +220,100 @@ int oracle_centered_clip(const float *G, int64_t ld, int32_t n,
 {
     return oracle_centered_clip_general(G, ld, n, off, P, tau, eps, M, v0, NULL, NULL, v,
                                         iters, step_norm, trace);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Baseline aggregators of Sec. 4.1 (the comparison set: "the coordinate-wise */
+/* and geometric medians"), per partition like CenteredClip.                  */
+/*                                                                            */
+/* Geometric median: the minimiser of sum_i ||g_i - v||_2, by Weiszfeld's     */
+/* iteration  v <- sum_i w_i g_i / sum_i w_i,  w_i = 1 / max(||g_i - v||, nu) */
+/* (nu > 0 guards the division when v reaches an input), from v0 (mean if     */
+/* NULL), stopped like CenteredClip: ||v_new - v|| < eps after the update, or */
+/* M updates.  App. D.2 describes it as the tau -> 0 end of CenteredClip.     */
+/* ------------------------------------------------------------------------ */
+int oracle_geometric_median(const float *G, int64_t ld, int32_t n, const int64_t *off,
+                            int32_t P, double nu, double eps, int32_t M, const double *v0,
+                            double *v, int32_t *iters, double *step_norm)
+{
+    if (!G || n <= 0 || !off || P <= 0 || !v || !iters || M < 0 || !(nu > 0.0) || !(eps >= 0.0))
+        return -1;
+    double *w = (double *)malloc(sizeof(double) * (size_t)n);
+    for (int32_t j = 0; j < P; ++j) {
+        const int64_t lo = off[j], hi = off[j + 1];
+        if (lo > hi || lo < 0 || hi > ld) { free(w); return -1; }
+        if (v0) {
+            for (int64_t x = lo; x < hi; ++x) v[x] = v0[x];
+        } else {
+#pragma omp parallel for schedule(static)
+            for (int64_t x = lo; x < hi; ++x) {
+                double sum = 0.0;
+                for (int32_t i = 0; i < n; ++i) sum += (double)G[i * ld + x];
+                v[x] = sum / (double)n;
+            }
+        }
+        int32_t it = 0;
+        double T = 0.0;
+        int bad = 0;
+        while (it < M) {
+            double W = 0.0;
+            for (int32_t i = 0; i < n; ++i) {
+                const float *gi = G + i * ld;
+                double N2 = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : N2)
+                for (int64_t x = lo; x < hi; ++x) {
+                    double r = (double)gi[x] - v[x];
+                    N2 += r * r;
+                }
+                const double N = sqrt(N2);
+                if (!isfinite(N)) bad = 1;
+                w[i] = 1.0 / (N > nu ? N : nu);
+                W += w[i];
+            }
+            if (bad) break;
+            double T2 = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : T2)
+            for (int64_t x = lo; x < hi; ++x) {
+                double sum = 0.0;
+                for (int32_t i = 0; i < n; ++i) sum += w[i] * (double)G[i * ld + x];
+                const double vn = sum / W;
+                T2 += (vn - v[x]) * (vn - v[x]);
+                v[x] = vn;
+            }
+            T = sqrt(T2);
+            ++it;
+            if (T < eps) break;
+        }
+        iters[j] = bad ? -1 : it;
+        if (step_norm) step_norm[j] = T;
+    }
+    free(w);
+    return 0;
+}
+
+static int cmp_double(const void *a, const void *b)
+{
+    const double x = *(const double *)a, y = *(const double *)b;
+    return (x > y) - (x < y);
+}
+
+/* Coordinate-wise median: v[x] = median of G[0][x] .. G[n-1][x]; for even n   */
+/* the mean of the two middle values.  x in [0, d).                            */
+int oracle_coordinate_median(const float *G, int64_t ld, int32_t n, int64_t d, double *v)
+{
+    if (!G || n <= 0 || d < 0 || ld < d || !v) return -1;
+#pragma omp parallel
+    {
+        double *col = (double *)malloc(sizeof(double) * (size_t)n);
+#pragma omp for schedule(static)
+        for (int64_t x = 0; x < d; ++x) {
+            for (int32_t i = 0; i < n; ++i) col[i] = (double)G[i * ld + x];
+            qsort(col, (size_t)n, sizeof(double), cmp_double);
+            v[x] = (n & 1) ? col[n / 2] : 0.5 * (col[n / 2 - 1] + col[n / 2]);
+        }
+        free(col);
+    }
+    return 0;
 }
 
 /* ------------------------------------------------------------------------ */

@@ -54,6 +54,13 @@ def _load():
         c.c_double, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_void_p, c.c_void_p]
     lib.oracle_centered_clip_general.restype = c.c_int
+    lib.oracle_geometric_median.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, P(c.c_int64), c.c_int32, c.c_double, c.c_double,
+        c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.oracle_geometric_median.restype = c.c_int
+    lib.oracle_coordinate_median.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int64,
+                                             c.c_void_p]
+    lib.oracle_coordinate_median.restype = c.c_int
     lib.oracle_tau_schedule.argtypes = [c.c_double, c.c_double, c.c_double, c.c_int32,
                                         c.c_void_p, c.c_void_p]
     lib.oracle_tau_schedule.restype = c.c_int
@@ -121,6 +128,41 @@ def preclip_scales(G, off, lam: float):
     if rc != 0:
         raise ValueError("oracle_preclip_scales: bad arguments")
     return alpha, norms
+
+
+def geometric_median(G, off, nu: float, eps: float, max_iters: int,
+                     v0: Optional[np.ndarray] = None):
+    """Weiszfeld's iteration per partition: (v [fp64], iters [int32, P], step_norm [fp64, P])."""
+    G = _as_G(G)
+    n, _ = G.shape
+    ld = G.strides[0] // 4 if n > 1 else G.shape[1]
+    Pn = len(off) - 1
+    width = int(off[-1])
+    v = np.zeros(max(width, 1), dtype=np.float64)
+    iters = np.zeros(Pn, dtype=np.int32)
+    sn = np.zeros(Pn, dtype=np.float64)
+    v0p = None
+    if v0 is not None:
+        v0 = np.ascontiguousarray(v0, dtype=np.float64)
+        assert v0.shape[0] >= width
+        v0p = v0.ctypes.data
+    rc = _load().oracle_geometric_median(G.ctypes.data, ld, n, _offsets(off), Pn, float(nu),
+                                         float(eps), int(max_iters), v0p, v.ctypes.data,
+                                         iters.ctypes.data, sn.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_geometric_median: bad arguments")
+    return v[:width], iters, sn
+
+
+def coordinate_median(G) -> np.ndarray:
+    """Coordinate-wise median of the rows (mean of the two middle values for even n)."""
+    G = _as_G(G)
+    n, d = G.shape
+    ld = G.strides[0] // 4 if n > 1 else d
+    v = np.zeros(max(d, 1), dtype=np.float64)
+    if _load().oracle_coordinate_median(G.ctypes.data, ld, n, d, v.ctypes.data) != 0:
+        raise ValueError("oracle_coordinate_median: bad arguments")
+    return v[:d]
 
 
 def tau_schedule(delta: float, sigma: float, B0: float, count: int):
