@@ -50,7 +50,8 @@ WsLayout ws_layout(int32_t n, int32_t P)
     L.partial_stride_doubles = align_up(sizeof(double) * blocks * S) / sizeof(double);
     L.partial = p;  p = align_up(p + 2 * sizeof(double) * L.partial_stride_doubles);
     // partial Gram matrices: one 16 x 16 block per workgroup, or the 10 block pairs of n <= 64
-    L.gram = p;     p = align_up(p + sizeof(double) * blocks * (n > kGramPeers ? kWideEntries : kGramEntries));
+    const size_t gram_entries = n <= kGramPeers ? kGramEntries : (n <= 16 * kWideBlocks ? kWideEntries : 0);
+    L.gram = p;     p = align_up(p + sizeof(double) * blocks * gram_entries);
     L.total = p;
     return L;
 }
