@@ -54,6 +54,14 @@ typedef enum btard_status {
  * if some partition still needs them.  Without it the call stays asynchronous and enqueues
  * max_iters passes that return at once for stopped partitions (about 2 us each). */
 #define BTARD_FLAG_HOST_SYNC 2u
+/* btard_cc_* (btard_cc_begin, btard_cc_iterate, btard_cc_finish): Weiszfeld's iteration for
+ * the GEOMETRIC MEDIAN of each partition's rows instead of CenteredClip -- the same passes
+ * with the weights 1 / max(||g_i - v||, tau), normalised (v <- sum w_i g_i / sum w_i): the
+ * tau -> 0 end of CenteredClip (App. D.2) and one of the baselines of Sec. 4.1.  `tau` is
+ * then the floor under the norms; stopping rule, v0, iters, last_step_norm as for
+ * CenteredClip.  Not with BTARD_FLAG_GRAM (ignored), tau_schedule or
+ * btard_cc_finish_verify (there are no clipped residuals to verify). */
+#define BTARD_FLAG_GEOMETRIC_MEDIAN 4u
 
 /* Human-readable name of a status code (static storage). */
 const char *btard_status_string(int status);
@@ -253,6 +261,22 @@ int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d
 int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float *v,
                            int32_t *iters, double *last_step_norm, uint64_t seed,
                            double *norms, double *weights, double *proj, double *colsum);
+
+/*
+ * Baseline aggregators of Sec. 4.1 on the same layout.
+ * btard_geometric_median: per partition, the minimiser of sum_i ||g_i - v||_2 by Weiszfeld's
+ * iteration (BTARD_FLAG_GEOMETRIC_MEDIAN above) from v0 (NULL: the mean); nu > 0 is the floor
+ * under the norms; arguments otherwise as btard_centered_clip.
+ * btard_coordinate_median: v[x] = median of g[0][x] .. g[n-1][x] (mean of the two middle
+ * values for even n), x in [0, d); inputs must not be NaN.  No workspace.
+ */
+int btard_geometric_median(const float *g, int64_t ldg, int32_t n, int64_t d,
+                           const int64_t *offsets_host, int32_t parts, float nu, float eps,
+                           int32_t max_iters, const float *v0, float *v, int32_t *iters,
+                           double *last_step_norm, void *workspace, size_t workspace_bytes,
+                           void *stream);
+int btard_coordinate_median(const float *g, int64_t ldg, int32_t n, int64_t d, float *v,
+                            void *stream);
 
 /*
  * tau_l of App. D.2, eq. (5), for l = 0 .. count - 1 (HOST out):

@@ -21,6 +21,7 @@ BTARD_OK = 0
 BTARD_FLAG_NONE = 0
 BTARD_FLAG_GRAM = 1
 BTARD_FLAG_HOST_SYNC = 2
+BTARD_FLAG_GEOMETRIC_MEDIAN = 4
 
 
 class BtardError(RuntimeError):
@@ -97,6 +98,14 @@ def load_library():
         c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t,
         c.c_void_p, c.c_uint32]
     lib.btard_centered_clip_verify.restype = c.c_int
+    lib.btard_geometric_median.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.POINTER(c.c_int64), c.c_int32,
+        c.c_float, c.c_float, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.btard_geometric_median.restype = c.c_int
+    lib.btard_coordinate_median.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int64,
+                                            c.c_void_p, c.c_void_p]
+    lib.btard_coordinate_median.restype = c.c_int
     lib.btard_tau_schedule.argtypes = [c.c_double, c.c_double, c.c_double, c.c_int32,
                                        c.POINTER(c.c_float)]
     lib.btard_tau_schedule.restype = c.c_int
@@ -328,6 +337,37 @@ def centered_clip_verify(g: torch.Tensor, offsets: Sequence[int], tau: float, ep
     return v, iters, last_step_norm, out
 
 
+def geometric_median(g: torch.Tensor, offsets: Sequence[int], nu: float, eps: float,
+                     max_iters: int, v0: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None):
+    """btard_geometric_median.  Returns (v fp32 [d], iters int32 [P], last_step_norm fp64 [P])."""
+    n, d = int(g.shape[0]), int(g.shape[1])
+    P = len(offsets) - 1
+    dev = g.device
+    v = torch.empty(d, dtype=torch.float32, device=dev)
+    iters = torch.empty(P, dtype=torch.int32, device=dev)
+    last_step_norm = torch.empty(P, dtype=torch.float64, device=dev)
+    if workspace is None:
+        workspace = alloc_workspace(n, P, dev)
+    rc = load_library().btard_geometric_median(
+        _ptr(g), _row_stride(g), n, d, _off_array(offsets), P, float(nu), float(eps),
+        int(max_iters), _ptr(v0), _ptr(v), _ptr(iters), _ptr(last_step_norm),
+        _ptr(workspace), workspace.numel(), _stream_ptr(dev))
+    _check(rc, "btard_geometric_median")
+    return v, iters, last_step_norm
+
+
+def coordinate_median(g: torch.Tensor, v: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """btard_coordinate_median.  Returns v fp32 [d]."""
+    n, d = int(g.shape[0]), int(g.shape[1])
+    if v is None:
+        v = torch.empty(d, dtype=torch.float32, device=g.device)
+    rc = load_library().btard_coordinate_median(_ptr(g), _row_stride(g), n, d, _ptr(v),
+                                                _stream_ptr(g.device))
+    _check(rc, "btard_coordinate_median")
+    return v
+
+
 def tau_schedule(delta: float, sigma: float, b0: float, count: int) -> List[float]:
     """btard_tau_schedule: the radii tau_l of eq. (5), as the fp32 values the library uses."""
     out = (ctypes.c_float * max(count, 1))()
@@ -443,6 +483,8 @@ btard_cc_finish_verify = cc_finish_verify
 btard_centered_clip_verify = centered_clip_verify
 btard_cc_preclip_factors = cc_preclip_factors
 btard_tau_schedule = tau_schedule
+btard_geometric_median = geometric_median
+btard_coordinate_median = coordinate_median
 btard_verification3 = verification3
 btard_centered_clip_verify_preclipped = centered_clip_verify_preclipped
 btard_debug_zhat = debug_zhat

@@ -15,6 +15,7 @@
 #include "cc_kernels.h"
 #include "fused_kernels.h"
 #include "gram_kernels.h"
+#include "median_kernels.h"
 #include "verify_kernels.h"
 
 namespace btard {
@@ -172,6 +173,14 @@ const FusedFn kFused[2][kVariants][2] = {
      BTARD_F_ROW(16, 16, true)}};
 #undef BTARD_F_ROW
 
+typedef void (*MedianFn)(MedianArgs);
+#define BTARD_M_ROW(NP, LG) \
+    {coordinate_median_kernel<NP, LG, false>, coordinate_median_kernel<NP, LG, true>}
+const MedianFn kMedian[kVariants][2] = {BTARD_M_ROW(4, 1),  BTARD_M_ROW(8, 1),  BTARD_M_ROW(16, 1),
+                                        BTARD_M_ROW(16, 2), BTARD_M_ROW(16, 4), BTARD_M_ROW(16, 8),
+                                        BTARD_M_ROW(16, 16)};
+#undef BTARD_M_ROW
+
 int variant_peers(Variant v)
 {
     static const int peers[kVariants] = {4, 8, 16, 32, 64, 128, 256};
@@ -253,6 +262,11 @@ CcState carve_problem(const btard_cc_problem *p)
     return st;
 }
 
+int rule_of(const btard_cc_problem *p)
+{
+    return (p->flags & BTARD_FLAG_GEOMETRIC_MEDIAN) != 0 ? kRuleGeometricMedian : kRuleCenteredClip;
+}
+
 // pre-clipping of the rows (BTARD-Clipped-SGD) asked for: a positive, finite radius
 bool preclip_on(const btard_cc_problem *p) { return p->preclip > 0.0f && std::isfinite(p->preclip); }
 
@@ -262,8 +276,10 @@ int check_problem(const btard_cc_problem *p)
     if (!basic_args_ok(p->g, p->ldg, p->n, p->d, p->offsets_host, p->parts))
         return BTARD_ERR_INVALID_ARG;
     if (!(p->tau > 0.0f) || !(p->eps >= 0.0f) || p->max_iters < 0) return BTARD_ERR_INVALID_ARG;
-    if ((p->flags & ~(uint32_t)(BTARD_FLAG_GRAM | BTARD_FLAG_HOST_SYNC)) != 0)
+    if ((p->flags & ~(uint32_t)(BTARD_FLAG_GRAM | BTARD_FLAG_HOST_SYNC |
+                                BTARD_FLAG_GEOMETRIC_MEDIAN)) != 0)
         return BTARD_ERR_INVALID_ARG;
+    if ((p->flags & BTARD_FLAG_GEOMETRIC_MEDIAN) != 0 && p->tau_schedule) return BTARD_ERR_INVALID_ARG;
     if (p->tau_schedule) {
         if (p->max_iters > kMaxSchedule) return BTARD_ERR_INVALID_ARG;
         for (int32_t l = 0; l < p->max_iters; ++l)
@@ -353,7 +369,7 @@ int btard_cc_begin(const btard_cc_problem *p)
         CcArgs a;
         a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = nullptr;
         a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
-        a.prev_blocks = B; a.pass = 0; a.scaled = 0; a.st = st;
+        a.prev_blocks = B; a.pass = 0; a.scaled = 0; a.rule = kRuleCenteredClip; a.st = st;
         hipLaunchKernelGGL(kCcPass[var][ragged][0], dim3(B, P), dim3(kBlock), 0, s, a);
         hipLaunchKernelGGL(preclip_scales_kernel, dim3(P), dim3(kBlock), 0, s, st, p->n, B,
                            (double)p->preclip, p->max_iters);
@@ -365,8 +381,8 @@ int btard_cc_begin(const btard_cc_problem *p)
 constexpr int kGramMaxPeers = 16 * kWideBlocks;
 static bool gram_applies(const btard_cc_problem *p)
 {
-    return (p->flags & BTARD_FLAG_GRAM) != 0 && p->n <= kGramMaxPeers && p->v0 == nullptr &&
-           p->max_iters > 0;
+    return (p->flags & BTARD_FLAG_GRAM) != 0 && (p->flags & BTARD_FLAG_GEOMETRIC_MEDIAN) == 0 &&
+           p->n <= kGramMaxPeers && p->v0 == nullptr && p->max_iters > 0;
 }
 
 // n <= 8: two coordinates per MFMA row block (512-wide tiles); n <= 16: one block (256-wide);
@@ -507,7 +523,7 @@ int btard_cc_iterate(const btard_cc_problem *p, int32_t first_iteration, int32_t
     CcArgs a;
     a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = p->v0;
     a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
-    a.prev_blocks = B; a.scaled = preclip_on(p) ? 1 : 0;
+    a.prev_blocks = B; a.scaled = preclip_on(p) ? 1 : 0; a.rule = rule_of(p);
     a.st = carve_problem(p);
     for (int32_t l = 0; l < count; ++l) {
         a.pass = first_iteration + l;
@@ -536,6 +552,7 @@ int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int
     a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = p->v0; a.v = v;
     a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
     a.pass = iterations; a.prev_blocks = Bpass; a.scaled = preclip_on(p) ? 1 : 0;
+    a.rule = rule_of(p);
     a.st = carve_problem(p);
     hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
     CcReportArgs r;
@@ -582,6 +599,7 @@ int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float 
     const int rc = check_problem(p);
     if (rc != BTARD_OK) return rc;
     if (!v || !iters || iterations < 0 || !norms || !weights || !proj) return BTARD_ERR_INVALID_ARG;
+    if ((p->flags & BTARD_FLAG_GEOMETRIC_MEDIAN) != 0) return BTARD_ERR_INVALID_ARG;
     if (p->v0) {
         // with a caller-supplied start vector: the two separate passes
         const int r1 = btard_cc_finish(p, iterations, v, iters, last_step_norm);
@@ -649,6 +667,46 @@ int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d
     if (rc != BTARD_OK) return rc;
     return btard_cc_finish_verify(&p, passes, v, iters, last_step_norm, seed, norms, weights, proj,
                                   colsum);
+}
+
+int btard_geometric_median(const float *g, int64_t ldg, int32_t n, int64_t d,
+                           const int64_t *offsets_host, int32_t parts, float nu, float eps,
+                           int32_t max_iters, const float *v0, float *v, int32_t *iters,
+                           double *last_step_norm, void *workspace, size_t workspace_bytes,
+                           void *stream)
+{
+    btard_cc_problem p;
+    p.g = g; p.ldg = ldg; p.n = n; p.d = d; p.offsets_host = offsets_host; p.parts = parts;
+    p.tau = nu; p.eps = eps; p.max_iters = max_iters; p.v0 = v0;
+    p.workspace = workspace; p.workspace_bytes = workspace_bytes; p.stream = stream;
+    p.flags = BTARD_FLAG_GEOMETRIC_MEDIAN; p.preclip = 0.0f; p.tau_schedule = nullptr;
+    int rc = check_problem(&p);
+    if (rc != BTARD_OK) return rc;
+    if (!v || !iters || overlaps(v, v0, d)) return BTARD_ERR_INVALID_ARG;
+    rc = btard_cc_begin(&p);
+    if (rc != BTARD_OK) return rc;
+    rc = btard_cc_iterate(&p, 0, max_iters);
+    if (rc != BTARD_OK) return rc;
+    return btard_cc_finish(&p, max_iters, v, iters, last_step_norm);
+}
+
+int btard_coordinate_median(const float *g, int64_t ldg, int32_t n, int64_t d, float *v,
+                            void *stream)
+{
+    if (n < 1 || n > kMaxPeers || d < 0 || ldg < d) return BTARD_ERR_INVALID_ARG;
+    if (d == 0) return BTARD_OK;                       // nothing to read or write
+    if (!g || !v) return BTARD_ERR_INVALID_ARG;
+    const Variant var = pick_variant(n);
+    const int ragged = n < variant_peers(var) ? 1 : 0;
+    const MedianFn fn = kMedian[var][ragged];
+    const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
+    if (resident <= 0) return BTARD_ERR_DEVICE;
+    const int64_t whole[2] = {0, d};
+    const int B = blocks_per_partition(resident, 1, whole, variant_tile_width(var));
+    MedianArgs a;
+    a.g = g; a.ld = ldg; a.n = n; a.d = d; a.v = v;
+    hipLaunchKernelGGL(fn, dim3(B), dim3(kBlock), 0, static_cast<hipStream_t>(stream), a);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
 int btard_tau_schedule(double delta, double sigma, double b0, int32_t count, float *tau_host)

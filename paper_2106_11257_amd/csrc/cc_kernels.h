@@ -61,8 +61,17 @@ struct CcArgs {
     int32_t pass;            // index l of this pass (0-based)
     int32_t prev_blocks;     // workgroups per partition of the previous pass
     int32_t scaled;          // rows are taken times st.scale (pre-clipping)
+    int32_t rule;            // kRuleCenteredClip or kRuleGeometricMedian
     CcState st;
 };
+
+// What the control step does with the norms (the passes are the same for both):
+//   CenteredClip      w_i = min{1, tau / N_i},  c += (w - W c) / n       (eq. (CenteredClip))
+//   geometric median  w_i = 1 / max(N_i, tau),  c  = w / W               (Weiszfeld's iteration
+//                     for the minimiser of sum_i ||g_i - v||, the tau -> 0 end of CenteredClip
+//                     and one of the baselines of Sec. 4.1; tau is the floor under the norms)
+constexpr int kRuleCenteredClip = 0;
+constexpr int kRuleGeometricMedian = 1;
 
 // ---------------------------------------------------------------------------
 // begin: upload offsets (through the kernel arguments), set c^0, clear state
@@ -133,7 +142,8 @@ __global__ __launch_bounds__(kOffChunk) void cc_begin_kernel(CcState st, int32_t
 __device__ __forceinline__ bool control_step(const CcState &st, int j, int n, double tau,
                                              double eps, int max_iters, int pass, int prev_blocks,
                                              bool mark_done, double *s_c, double *s_a,
-                                             double *s_red, int *s_flags, int *iters_out)
+                                             double *s_red, int *s_flags, int *iters_out,
+                                             int rule = kRuleCenteredClip)
 {
     const int R = st.R, P = st.P;
     const int t = threadIdx.x;
@@ -167,7 +177,8 @@ __device__ __forceinline__ bool control_step(const CcState &st, int j, int n, do
     if (t < n) {
         const double N = sqrt(tot);
         if (!isfinite(N)) s_flags[1] = 1;
-        w = (N <= tau) ? 1.0 : tau / N;
+        if (rule == kRuleGeometricMedian) w = 1.0 / fmax(N, tau);
+        else w = (N <= tau) ? 1.0 : tau / N;
     }
     __syncthreads();
     s_red[t] = w;
@@ -180,8 +191,14 @@ __device__ __forceinline__ bool control_step(const CcState &st, int j, int n, do
         double W = 0.0;
         for (int i = 0; i < n; ++i) W += s_red[i];
         if (t < R) {
-            aq = ((t < n ? w : 0.0) - W * cq) / (double)n;
-            cq = cq + aq;
+            if (rule == kRuleGeometricMedian) {
+                const double cn = (t < n) ? w / W : 0.0;
+                aq = cn - cq;
+                cq = cn;
+            } else {
+                aq = ((t < n ? w : 0.0) - W * cq) / (double)n;
+                cq = cq + aq;
+            }
         }
         it = it + 1;
         if (it >= max_iters) dn = 1;
@@ -326,7 +343,7 @@ __global__ __launch_bounds__(kBlock, (LG == 1 && !SCALED ? 4 : 2)) void cc_pass_
 
     int iters_now;
     if (control_step(a.st, j, n, a.tau, a.eps, a.max_iters, a.pass, a.prev_blocks, true, s_c, s_a,
-                     s_red, s_flags, &iters_now))
+                     s_red, s_flags, &iters_now, a.rule))
         return;                                     // uniform: this partition stops now
 
     double c[NP], dl[NP], cb, db;
@@ -409,6 +426,7 @@ struct CcFinishArgs {
     int32_t pass;            // number of passes that were enqueued
     int32_t prev_blocks;
     int32_t scaled;          // rows are taken times st.scale (pre-clipping)
+    int32_t rule;            // as in CcArgs
     CcState st;
 };
 
@@ -479,7 +497,7 @@ __global__ __launch_bounds__(kBlock, 3) void cc_finish_kernel(CcFinishArgs a)
         // still running: apply the update the last pass prepared (this kernel does not
         // publish a stop: nothing runs after it that would need to skip the partition)
         control_step(a.st, j, n, a.tau, a.eps, a.max_iters, a.pass, a.prev_blocks, false, s_c, s_a,
-                     s_red, s_flags, &iters_now);
+                     s_red, s_flags, &iters_now, a.rule);
         if (blockIdx.x == 0 && threadIdx.x == 0) a.st.report_buf[j] = a.pass & 1;
     }
 

@@ -87,12 +87,26 @@ def test_argument_errors_are_caught_on_the_host_before_any_gpu_call():
     assert cc(o=(ctypes.c_int64 * 3)(1, 4, 8)) == -1
     assert cc(tau=0.0) == -1 and cc(tau=float("nan")) == -1
     assert cc(eps=-1.0) == -1 and cc(m=-1) == -1
-    assert cc(flags=7) == -1
+    assert cc(flags=8) == -1 and cc(flags=15) == -1
     assert cc(wsp=None) == -2
     assert cc(wsp=ctypes.c_void_p(0x10001)) == -2      # misaligned
     assert cc(wsb=16) == -2
     assert cc(v=None) == -1 and cc(iters=None) == -1
     assert cc(v0=fake, v=fake) == -1                   # v must not overlap v0
+
+    def gm(g=fake, n=2, nu=1e-6, eps=1e-6, m=5, v=fake, wsb=big):
+        return lib.btard_geometric_median(g, 8, n, 8, off, 2, nu, eps, m, None, v, fake, None, ws,
+                                          wsb, None)
+
+    assert gm(g=None) == -1 and gm(n=0) == -1 and gm(nu=0.0) == -1 and gm(m=-1) == -1
+    assert gm(v=None) == -1 and gm(wsb=16) == -2
+
+    def cm(g=fake, ld=8, n=2, d=8, v=fake):
+        return lib.btard_coordinate_median(g, ld, n, d, v, None)
+
+    assert cm(g=None) == -1 and cm(v=None) == -1 and cm(n=0) == -1 and cm(n=256) == -1
+    assert cm(ld=7) == -1 and cm(d=-1) == -1
+    assert cm(g=None, v=None, d=0, ld=0) == 0          # nothing to do
 
     def vp(g=fake, v=fake, norms=fake, tau=1.0, delta=None, ldd=0, wsb=big):
         return lib.btard_verify_projections(g, 8, 2, 8, off, 2, v, tau, 1, norms, fake, fake, None,

@@ -1,0 +1,163 @@
+"""GPU parity of the baseline aggregators of Sec. 4.1 (coordinate-wise median, geometric
+median by Weiszfeld's iteration) against the fp64 oracle.
+
+The coordinate-wise median selects input values (or the exact fp64 mean of two of them,
+rounded once to fp32), so it is compared bit for bit with the oracle's value rounded to
+fp32.  The geometric median is held to the CenteredClip bar: iteration counts identical,
+relative L2 error <= 1e-5 on v.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2106_11257_amd as btard
+from paper_2106_11257_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+V_TOL = 1e-5
+SCALAR_TOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch.device("cuda:0")
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = np.linalg.norm(b)
+    return np.linalg.norm(a - b) / den if den > 0 else np.linalg.norm(a - b)
+
+
+def check_median(G, label=""):
+    say(f"[median] {label} n={G.shape[0]} d={G.shape[1]} ld={G.stride(0)}")
+    v = btard.coordinate_median(G)
+    torch.cuda.synchronize()
+    got = v.cpu().numpy()
+    want = oracle.coordinate_median(G.cpu().numpy()).astype(np.float32)
+    bad = np.flatnonzero(got != want)
+    assert bad.size == 0, f"{bad.size} differ, first at {bad[:5]}: {got[bad[:5]]} vs {want[bad[:5]]}"
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 100,
+                               128, 129, 200, 255])
+def test_coordinate_median_every_peer_count(dev, n):
+    d = 5003 if n <= 64 else 2051
+    G, _ = workloads.generic_case(n, d, 1, seed=4000 + n, device=dev, ld=d + 5, outliers=n // 3)
+    check_median(G, "peer counts")
+
+
+@pytest.mark.parametrize("n,d", [(16, 1), (16, 3), (5, 255), (16, 256), (16, 257), (40, 64),
+                                 (40, 17), (130, 5), (7, 70001), (48, 30011)])
+def test_coordinate_median_widths_and_tails(dev, n, d):
+    G, _ = workloads.generic_case(n, d, 1, seed=5000 + n + d, device=dev)
+    check_median(G, "widths")
+
+
+@pytest.mark.parametrize("n", [6, 16, 21, 64, 90])
+def test_coordinate_median_with_ties_signs_and_zeros(dev, n):
+    """Few distinct values (many equal keys around the middle), both signs, both zeros,
+    denormals and infinities of one sign per coordinate."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(6000 + n)
+    d = 3001
+    G = torch.randint(-3, 4, (n, d), generator=gen, device=dev).to(torch.float32) * 0.25
+    G[0, ::7] = -0.0
+    G[1 % n, ::11] = 1e-42                     # denormal
+    G[2 % n, ::13] = -1e-42
+    G[3 % n, ::17] = float("inf")
+    G[4 % n, 5::17] = float("-inf")
+    check_median(G, "ties")
+
+
+def test_coordinate_median_empty_and_bad_arguments(dev):
+    G = torch.zeros((4, 0), device=dev)
+    assert btard.coordinate_median(G).numel() == 0
+    with pytest.raises(btard.BtardError):
+        btard.coordinate_median(torch.zeros((256, 8), device=dev))
+
+
+def test_coordinate_median_full_size_resnet18(dev):
+    wl = workloads.make_workload(2, device=dev)
+    G = wl.G
+    check_median(G, "cfg2")
+
+
+def check_gm(G, off, nu, eps, M, v0=None, label=""):
+    say(f"[gm] {label} n={G.shape[0]} d={G.shape[1]} P={len(off) - 1} nu={nu} eps={eps} M={M} "
+        f"v0={'yes' if v0 is not None else 'mean'}")
+    v, iters, sn = btard.geometric_median(G, off, nu, eps, M, v0=v0)
+    torch.cuda.synchronize()
+    v0h = None if v0 is None else v0.cpu().numpy().astype(np.float64)
+    vo, ito, sno = oracle.geometric_median(G.cpu().numpy(), off, float(np.float32(nu)),
+                                           float(np.float32(eps)), M, v0=v0h)
+    np.testing.assert_array_equal(iters.cpu().numpy(), ito)
+    vh = v.cpu().numpy()
+    for j in range(len(off) - 1):
+        lo, hi = off[j], off[j + 1]
+        assert rel_l2(vh[lo:hi], vo[lo:hi]) <= V_TOL, f"partition {j}"
+    np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=SCALAR_TOL, atol=1e-11)
+    return ito
+
+
+@pytest.mark.parametrize("n,d,P", [(1, 100, 2), (2, 77, 1), (3, 1000, 3), (8, 4099, 4),
+                                   (13, 9001, 5), (16, 20011, 7), (17, 6007, 3), (40, 8009, 4),
+                                   (64, 5003, 2), (100, 3001, 3)])
+def test_geometric_median_small_shapes(dev, n, d, P):
+    G, off = workloads.generic_case(n, d, P, seed=7000 + n, device=dev, ld=d + 3,
+                                    outliers=n // 4)
+    it = check_gm(G, off, 1e-6, 1e-6, 200, label="shapes")
+    assert n < 3 or it.max() > 2
+
+
+def test_geometric_median_iteration_cap_and_start_vector(dev):
+    G, off = workloads.generic_case(12, 9001, 5, seed=71, device=dev, ld=9003, outliers=4)
+    it = check_gm(G, off, 1e-6, 0.0, 7, label="cap")
+    assert (it == 7).all()
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(72)
+    v0 = torch.randn(9001, generator=gen, device=dev)
+    check_gm(G, off, 1e-6, 1e-5, 100, v0=v0, label="start vector")
+    check_gm(G, off, 1e-6, 1e-5, 0, v0=v0, label="no iterations")
+
+
+def test_geometric_median_with_a_large_floor_is_the_mean(dev):
+    """nu above every norm: all weights are 1/nu, one step from the mean stays at the mean."""
+    G, off = workloads.generic_case(9, 3000, 3, seed=73, device=dev)
+    it = check_gm(G, off, 1e6, 1e-6, 50, label="floor")
+    assert (it == 1).all()
+    v, _, _ = btard.geometric_median(G, off, 1e6, 1e-6, 50)
+    mean = G.double().mean(dim=0)
+    assert rel_l2(v.cpu().numpy(), mean.cpu().numpy()) <= V_TOL
+
+
+def test_geometric_median_resnet18_partitions(dev):
+    """Full-size slab of configuration 2; the oracle runs on three partitions."""
+    wl = workloads.make_workload(2, device=dev)
+    G, off = wl.G, wl.offsets
+    M = 30
+    say(f"[gm] cfg2 n={G.shape[0]} d={G.shape[1]} M={M}")
+    v, iters, sn = btard.geometric_median(G, off, 1e-6, 1e-6, M)
+    torch.cuda.synchronize()
+    vh, ih, sh = v.cpu().numpy(), iters.cpu().numpy(), sn.cpu().numpy()
+    for j in (0, 7, 15):
+        lo, hi = off[j], off[j + 1]
+        sub = G[:, lo:hi].contiguous().cpu().numpy()
+        vo, ito, sno = oracle.geometric_median(sub, [0, hi - lo], float(np.float32(1e-6)),
+                                               float(np.float32(1e-6)), M)
+        assert ih[j] == ito[0]
+        assert rel_l2(vh[lo:hi], vo) <= V_TOL
+        assert sh[j] == pytest.approx(sno[0], rel=SCALAR_TOL, abs=1e-11)
+        say(f"    partition {j}: iters={ito[0]} ok")
