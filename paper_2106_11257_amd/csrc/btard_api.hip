@@ -391,8 +391,9 @@ typedef void (*GramFn)(GramArgs);
 static int gram_peer_blocks(const btard_cc_problem *p) { return (p->n + 15) / 16; }
 static GramFn gram_kernel(const btard_cc_problem *p)
 {
-    if (p->n <= kGramPeers / 2) return gram_pass_kernel<true>;
-    if (p->n <= kGramPeers) return gram_pass_kernel<false>;
+    if (p->n < 8) return gram_pass_band_kernel<8, true>;
+    if (p->n == 8) return gram_pass_band_kernel<8, false>;
+    if (p->n <= kGramPeers) return gram_pass_kernel;
     switch (gram_peer_blocks(p)) {
         case 2: return gram_pass_wide_kernel<2>;
         case 3: return gram_pass_wide_kernel<3>;
@@ -404,7 +405,8 @@ static int gram_blocks(const btard_cc_problem *p)
 {
     const int resident = resident_blocks(reinterpret_cast<const void *>(gram_kernel(p)));
     if (resident <= 0) return 0;
-    const int tile = p->n <= kGramPeers / 2 ? 512 : (p->n <= kGramPeers ? 256 : 64);
+    // n <= 8: a workgroup's wavefronts share its 256-coordinate tiles, i.e. 64 per wavefront
+    const int tile = p->n <= 8 ? 64 : (p->n <= kGramPeers ? 256 : 64);
     return blocks_per_partition(resident, p->parts, p->offsets_host, tile);
 }
 

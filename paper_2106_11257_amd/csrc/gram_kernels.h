@@ -49,26 +49,17 @@ __device__ __forceinline__ int gram_entry(int lane, int r) { return ((lane >> 4)
 // transposing through LDS, and prefetching the next tile, were tried: the kernel stays at
 // the fp64 MFMA issue rate either way -- measured 105 cycles per instruction -- so the
 // simple form is kept.)
-//
-// HALF (n <= 8): the 16 rows of the MFMA block are the n peers at TWO coordinates at once.
-// Lanes p < 8 read peer p in the first 256 coordinates of a 512-wide tile, lanes p >= 8
-// read peer p - 8 in the second 256; the product then holds X1 X1^T and X2 X2^T in its two
-// diagonal 8 x 8 blocks (and X1 X2^T, unused, off the diagonal), whose sum is this tile's
-// contribution to Gamma: half the MFMA instructions per coordinate.
-template <bool HALF>
 __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
 {
-    constexpr int kW = HALF ? 512 : 256;
+    constexpr int kW = 256;
     const int j = blockIdx.y;
     const int n = a.n;
     const int64_t lo = a.off[j], hi = a.off[j + 1];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int p = lane & 15, q = lane >> 4;
-    const int peer = HALF ? (p & 7) : p;
-    const int shift = (HALF && p >= 8) ? 256 : 0;                // this lane's half of the tile
-    const bool have = peer < n;
-    global_f32 row = (global_f32)a.g + (int64_t)(have ? peer : n - 1) * a.ld + shift;
+    const bool have = p < n;
+    global_f32 row = (global_f32)a.g + (int64_t)(have ? p : n - 1) * a.ld;
 
     // four independent accumulators: consecutive MFMAs do not wait for each other
     f64x4 acc[4];
@@ -91,8 +82,8 @@ __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
             for (int s = 0; s < 16; ++s) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int64_t x = xu + 16 * s + 4 * q + e;    // (row already carries shift)
-                    val[s][e] = (x + shift >= lo && x + shift < hi) ? row[x] : 0.0f;
+                    const int64_t x = xu + 16 * s + 4 * q + e;
+                    val[s][e] = (x >= lo && x < hi) ? row[x] : 0.0f;
                 }
             }
         }
@@ -114,15 +105,220 @@ __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
     __syncthreads();
     const int t = threadIdx.x;
     double s = 0.0;
-    if (!HALF) {
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) s += sh[w][t];
-    } else if ((t >> 4) < 8 && (t & 15) < 8) {
-        // entry (i, k), i, k < 8: the two diagonal blocks added; the rest of the matrix is 0
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) s += sh[w][t] + sh[w][t + 8 * kGramPeers + 8];
-    }
+    for (int w = 0; w < kWaves; ++w) s += sh[w][t];
     a.gpart[((int64_t)j * gridDim.x + blockIdx.x) * kGramEntries + t] = s;
+}
+
+// ---------------------------------------------------------------------------
+// n <= 8 on the vector ALU.  Gamma is symmetric, so only the pairs (i, i + dl mod NP),
+// dl = 0 .. NP/2, are needed: NP (NP/2 + 1) products per coordinate, where a 16 x 16 matrix
+// instruction forms 256 of which at most 64 are wanted.  The four wavefronts of a workgroup
+// walk the SAME 256-coordinate tiles (a lane holds 4 coordinates) and split the pairs:
+// wavefront w takes base rows i = (NP/4) w + k, k < NP/4, for which it needs the
+// NP/4 + NP/2 rows i .. i + NP/2 (mod NP) and keeps (NP/4)(NP/2 + 1) accumulators per lane.
+// Every row is needed by three of the four wavefronts, so a tile goes through LDS: each
+// wavefront loads NP/4 rows of the next tile from memory while the workgroup multiplies the
+// current one; two tiles in LDS, one barrier per tile.
+// Measured on an 8.6 GB slab with n = 8: 1.38 ms against 1.61 ms for the MFMA form with two
+// coordinates per 16-row block.  The template also works for NP = 16, where it was measured
+// level with the MFMA kernel (140 against 142-147 us on an 0.7 GB slab) and is not used.
+// Two other forms of the same split were slower than the MFMA kernel: every wavefront
+// reading its rows from memory (each row three times, twice from the caches), and the four
+// rows of 16 lanes of one wavefront taking the four sets of base rows on 64 coordinates.
+// ---------------------------------------------------------------------------
+template <int NP>
+struct GramBand {
+    static constexpr int kBase = NP / 4;             // base rows per wavefront = rows it loads
+    static constexpr int kDeltas = NP / 2 + 1;       // row distances 0 .. NP/2
+    static constexpr int kRows = kBase + NP / 2;     // rows a wavefront multiplies
+    static constexpr int kW = 64 * kVec;             // coordinates per tile
+};
+
+// Waits for this wavefront's LDS traffic only (loads from memory stay in flight), then the
+// workgroup barrier.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// The wavefront's own rows of the tile at xu: row[m] + xu is wavefront-uniform (a scalar
+// base), lane_bytes the lane's 32-bit byte offset.  The compiler must not fold lane_bytes
+// into per-row vector addresses outside the loop (two registers and an add per row): the
+// value is "changed" in place.
+template <int NP>
+__device__ __forceinline__ void band_fetch(const global_f32 (&row)[GramBand<NP>::kBase], int64_t xu,
+                                           uint32_t &lane_bytes, f32x4_u (&g)[GramBand<NP>::kBase])
+{
+#pragma unroll
+    for (int m = 0; m < GramBand<NP>::kBase; ++m) {
+        const char __attribute__((address_space(1))) *base =
+            (const char __attribute__((address_space(1))) *)(row[m] + xu);
+        g[m] = *(global_f32x4)(base + lane_bytes);
+    }
+}
+
+template <int NP, bool RAGGED>
+__device__ __forceinline__ void band_stage(float (&tile)[NP][GramBand<NP>::kW], int first_row,
+                                           const bool (&have)[GramBand<NP>::kBase], int lane,
+                                           const f32x4_u (&g)[GramBand<NP>::kBase])
+{
+#pragma unroll
+    for (int m = 0; m < GramBand<NP>::kBase; ++m) {
+        f32x4_u t = g[m];
+        if (RAGGED && !have[m]) { t.x = 0.0f; t.y = 0.0f; t.z = 0.0f; t.w = 0.0f; }   // absent peer
+        *reinterpret_cast<f32x4_u *>(&tile[first_row + m][lane * kVec]) = t;
+    }
+}
+
+template <int NP>
+__device__ __forceinline__ void band_read(const float (&tile)[NP][GramBand<NP>::kW],
+                                          const int (&peer)[GramBand<NP>::kRows], int lane,
+                                          float (&val)[GramBand<NP>::kRows][4])
+{
+#pragma unroll
+    for (int r = 0; r < GramBand<NP>::kRows; ++r) {
+        const f32x4_u t = *reinterpret_cast<const f32x4_u *>(&tile[peer[r]][lane * kVec]);
+        val[r][0] = t.x; val[r][1] = t.y; val[r][2] = t.z; val[r][3] = t.w;
+    }
+}
+
+template <int NP, bool MASKED, int E>
+__device__ __forceinline__ void band_accumulate(const float (&val)[GramBand<NP>::kRows][E],
+                                                const bool (&have)[GramBand<NP>::kRows],
+                                                double (&acc)[GramBand<NP>::kBase][GramBand<NP>::kDeltas])
+{
+    using B = GramBand<NP>;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        double d[B::kRows];
+#pragma unroll
+        for (int r = 0; r < B::kRows; ++r) d[r] = (!MASKED || have[r]) ? (double)val[r][e] : 0.0;
+#pragma unroll
+        for (int k = 0; k < B::kBase; ++k) {
+#pragma unroll
+            for (int dl = 0; dl < B::kDeltas; ++dl) acc[k][dl] = fma(d[k], d[k + dl], acc[k][dl]);
+        }
+    }
+}
+
+template <int NP, bool RAGGED>
+__global__ __launch_bounds__(kBlock, 2) void gram_pass_band_kernel(GramArgs a)
+{
+    using B = GramBand<NP>;
+    __shared__ float tile[2][NP][B::kW];
+    __shared__ double sh[kGramEntries];
+    const int j = blockIdx.y;
+    const int n = a.n;
+    const int64_t lo = a.off[j], hi = a.off[j + 1];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    sh[threadIdx.x] = 0.0;                           // entries nobody forms (NP < 16) stay 0
+
+    // wavefront-uniform: the rows this wavefront multiplies, and the first kBase of them,
+    // which it also loads
+    global_f32 row[B::kRows], own[B::kBase];
+    bool have[B::kRows], have_own[B::kBase];
+    int peer[B::kRows];
+#pragma unroll
+    for (int r = 0; r < B::kRows; ++r) {
+        peer[r] = (B::kBase * wave + r) % NP;
+        have[r] = peer[r] < n;
+        row[r] = (global_f32)a.g + (int64_t)(have[r] ? peer[r] : n - 1) * a.ld;
+    }
+#pragma unroll
+    for (int m = 0; m < B::kBase; ++m) { own[m] = row[m]; have_own[m] = have[m]; }
+    double acc[B::kBase][B::kDeltas];
+#pragma unroll
+    for (int k = 0; k < B::kBase; ++k) {
+#pragma unroll
+        for (int dl = 0; dl < B::kDeltas; ++dl) acc[k][dl] = 0.0;
+    }
+
+    // the workgroup's interior tiles: begin, begin + stride, ... (count of them; the same
+    // for its four wavefronts, which meet at a barrier per tile)
+    const int64_t xa = tile_origin(lo);
+    const int64_t units = (hi > lo) ? (hi - xa + B::kW - 1) / B::kW : 0;
+    const int64_t stride = gridDim.x;
+    int64_t begin = blockIdx.x, end = units;
+    if (units > 0 && !tile_is_interior<B::kW>(xa + (units - 1) * B::kW, lo, hi)) end = units - 1;
+    if (begin == 0 && units > 0 && !tile_is_interior<B::kW>(xa, lo, hi)) begin = stride;
+    const int64_t count = (begin < end) ? (end - begin + stride - 1) / stride : 0;
+    uint32_t lane_bytes = (uint32_t)lane * (kVec * (uint32_t)sizeof(float));
+    if (count > 0) {
+        // Tile t of the walk (t >= count: the last one again -- loads without a condition
+        // keep the loop free of joins that would wait for everything in flight).
+        const int64_t step = stride * B::kW;
+        const int64_t x_first = xa + begin * B::kW, x_last = x_first + (count - 1) * step;
+        f32x4_u g[B::kBase];
+        float val[B::kRows][4];
+        band_fetch<NP>(own, x_first, lane_bytes, g);
+        band_stage<NP, RAGGED>(tile[0], B::kBase * wave, have_own, lane, g);
+        lds_barrier();
+        // here: tile t is in LDS half t % 2; tile t + 1 is loaded while tile t is multiplied
+        int64_t x1 = x_first + step;                 // tile t + 1
+        for (int64_t t = 0;; t += 2) {
+            band_fetch<NP>(own, x1 <= x_last ? x1 : x_last, lane_bytes, g);
+            __builtin_amdgcn_sched_barrier(0);
+            band_read<NP>(tile[0], peer, lane, val);
+            band_accumulate<NP, false, 4>(val, have, acc);
+            band_stage<NP, RAGGED>(tile[1], B::kBase * wave, have_own, lane, g);
+            lds_barrier();
+            if (t + 1 >= count) break;
+            x1 += step;
+            band_fetch<NP>(own, x1 <= x_last ? x1 : x_last, lane_bytes, g);
+            __builtin_amdgcn_sched_barrier(0);
+            band_read<NP>(tile[1], peer, lane, val);
+            band_accumulate<NP, false, 4>(val, have, acc);
+            band_stage<NP, RAGGED>(tile[0], B::kBase * wave, have_own, lane, g);
+            lds_barrier();
+            if (t + 2 >= count) break;
+            x1 += step;
+        }
+    }
+    // the partition's first and last tile where they are not interior: straight from memory
+    const int64_t xl = xa + (int64_t)lane * kVec;
+#pragma unroll 1
+    for (int t = 0; t < 2; ++t) {
+        const int64_t u = (t == 0) ? 0 : units - 1;
+        if ((t == 1 && units < 2) || u < 0) continue;
+        if (u < blockIdx.x || (u - blockIdx.x) % stride != 0) continue;
+        if (tile_is_interior<B::kW>(xa + u * B::kW, lo, hi)) continue;
+        float ve[B::kRows][4];
+#pragma unroll
+        for (int r = 0; r < B::kRows; ++r) {
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) {
+                const int64_t x = xl + u * B::kW + e;
+                ve[r][e] = (x >= lo && x < hi) ? row[r][x] : 0.0f;
+            }
+        }
+        band_accumulate<NP, RAGGED, 4>(ve, have, acc);
+    }
+
+    // sums over the wavefront's lanes, then entry (i, i + dl) and its mirror image
+#pragma unroll
+    for (int k = 0; k < B::kBase; ++k) sum_within_group_all<64, B::kDeltas>(acc[k]);
+    __syncthreads();                                 // sh is zeroed
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < B::kBase; ++k) {
+            const int i = B::kBase * wave + k;
+#pragma unroll
+            for (int dl = 0; dl < B::kDeltas; ++dl) {
+                // distance NP/2 pairs are formed twice (from i and from i + NP/2) with the
+                // same products in the same order: the lower wavefronts write them
+                if (dl == NP / 2 && i >= NP / 2) continue;
+                const int k2 = (i + dl) % NP;
+                sh[i * kGramPeers + k2] = acc[k][dl];
+                sh[k2 * kGramPeers + i] = acc[k][dl];
+            }
+        }
+    }
+    __syncthreads();
+    a.gpart[((int64_t)j * gridDim.x + blockIdx.x) * kGramEntries + threadIdx.x] = sh[threadIdx.x];
 }
 
 // ---------------------------------------------------------------------------
