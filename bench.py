@@ -83,6 +83,9 @@ def main() -> int:
     ap.add_argument("--preclip", type=float, default=0.0,
                     help="pre-clipping radius lambda of BTARD-Clipped-SGD as a multiple of the "
                          "median row norm of partition 0 (0: none, the headline configuration)")
+    ap.add_argument("--baselines", action="store_true",
+                    help="also time the baseline aggregators of Sec. 4.1 on the same slab "
+                         "(coordinate-wise median; geometric median, 20 Weiszfeld iterations)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of known size (1 GiB read + 1 GiB "
@@ -317,6 +320,35 @@ def main() -> int:
                 "value": round(agg_bytes / (ms2 * 1e-3) / 1e9, 1), "unit": "GB/s",
                 "ms_per_step": round(ms2, 4),
                 "segments_ms": {k: round(x, 4) for k, x in zip(seg_h, seg2)}}
+
+    # ---- the baseline aggregators on the same slab (not part of the headline step)
+    if args.baselines:
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        vm = torch.empty(d, dtype=torch.float32, device=dev)
+        t_med = timed(lambda: btard.coordinate_median(G, vm), 5)
+        gm_iters = 20
+        t_gm = timed(lambda: btard.geometric_median(G, off, 1e-6, 0.0, gm_iters, workspace=ws), 2)
+        med_bytes = slab_bytes + 4.0 * d
+        out["baselines"] = {
+            "coordinate_median": {
+                "us": round(t_med * 1e3, 2), "algorithmic_bytes": med_bytes,
+                "achieved_GBps": round(med_bytes / (t_med * 1e-3) / 1e9, 1),
+                "frac_of_hbm_peak": round(med_bytes / (t_med * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+            "geometric_median": {
+                "iterations": gm_iters, "ms": round(t_gm, 4),
+                # gm_iters passes and the pass that writes v
+                "us_per_pass": round(t_gm * 1e3 / (gm_iters + 1), 2),
+                "achieved_GBps": round(slab_bytes * (gm_iters + 1) / (t_gm * 1e-3) / 1e9, 1)},
+        }
 
     # ---- the oracle on the host cores, as a baseline only
     if not args.no_cpu_baseline:

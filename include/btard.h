@@ -296,6 +296,22 @@ int btard_verification3(const double *norms, int32_t n, int32_t parts, double de
                         uint8_t *check, int32_t *votes, uint8_t *trigger, void *stream);
 
 /*
+ * Verifications 1 and 2 of Alg. 6 as comparisons (all arrays DEVICE, [i * parts + j]):
+ * claimed_norms / claimed_proj are what the peers broadcast (norm_ij, s_i^j), norms / proj
+ * what btard_verify_projections recomputed.  bad_norm_ij = 1 when the broadcast norm does not
+ * match (Verification 1), bad_proj_ij = 1 when the broadcast projection does not match
+ * (Verification 2, first test), bad_sum_j = 1 when the broadcast projections of partition j
+ * do not sum to zero (Verification 2, second test).  The algorithm states the tests in exact
+ * arithmetic; here "a matches b" means |a - b| <= atol + rtol |b| (b recomputed; NaN never
+ * matches) and "sums to zero" means |sum_i s_ij| <= atol + rtol sum_i |s_ij|, rtol, atol >= 0.
+ * What follows a failed test (Accuse) is the caller's.  Enqueued on `stream`.
+ */
+int btard_verification12(const double *claimed_norms, const double *claimed_proj,
+                         const double *norms, const double *proj, int32_t n, int32_t parts,
+                         double rtol, double atol, uint8_t *bad_norm, uint8_t *bad_proj,
+                         uint8_t *bad_sum, void *stream);
+
+/*
  * The pre-clipping factors of a run: factors[i * parts + j] = alpha_ij (DEVICE, n * parts
  * doubles; all 1 without pre-clipping).  Valid after btard_cc_begin, with BTARD_FLAG_GRAM
  * after btard_cc_gram.  Enqueued on the problem's stream.

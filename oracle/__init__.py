@@ -14,6 +14,7 @@ from .oracle import (  # noqa: F401
     split,
     tau_schedule,
     verification3,
+    verification12,
     verify,
     z_hat,
     z_norm,

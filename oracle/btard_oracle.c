@@ -362,6 +362,38 @@ int oracle_verification3(const double *norms, int32_t n, int32_t P, double delta
 }
 
 /* ------------------------------------------------------------------------ */
+/* Verifications 1 and 2 of Alg. 6 as comparisons.  The algorithm tests       */
+/* "norm_ji != ||g_j(i) - g^(i)||", "s_j^i != <z[j], Delta_j^i>" and          */
+/* "sum_i s_i^j != 0" in exact arithmetic; in floating point a broadcast      */
+/* value matches the recomputed one b when |a - b| <= atol + rtol |b| (NaN    */
+/* never matches), and the broadcast projections of partition j sum to zero   */
+/* when |sum_i s_ij| <= atol + rtol sum_i |s_ij|.  All arrays n x P row-major. */
+/* ------------------------------------------------------------------------ */
+int oracle_verification12(const double *claimed_norms, const double *claimed_proj,
+                          const double *norms, const double *proj, int32_t n, int32_t P,
+                          double rtol, double atol, uint8_t *bad_norm, uint8_t *bad_proj,
+                          uint8_t *bad_sum)
+{
+    if (!claimed_norms || !claimed_proj || !norms || !proj || n <= 0 || P <= 0 ||
+        !(rtol >= 0.0) || !(atol >= 0.0) || !bad_norm || !bad_proj || !bad_sum)
+        return -1;
+    for (int32_t j = 0; j < P; ++j) {
+        double sum = 0.0, mag = 0.0;
+        for (int32_t i = 0; i < n; ++i) {
+            const int64_t q = (int64_t)i * P + j;
+            const double dn = fabs(claimed_norms[q] - norms[q]);
+            const double dp = fabs(claimed_proj[q] - proj[q]);
+            bad_norm[q] = (dn <= atol + rtol * fabs(norms[q])) ? 0 : 1;
+            bad_proj[q] = (dp <= atol + rtol * fabs(proj[q])) ? 0 : 1;
+            sum += claimed_proj[q];
+            mag += fabs(claimed_proj[q]);
+        }
+        bad_sum[j] = (fabs(sum) <= atol + rtol * mag) ? 0 : 1;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
 /* Pre-clipping of BTARD-Clipped-SGD (App. E.3, Alg. 9 line 3 and the text   */
 /* after it): every peer clips each PARTITION of its gradient to radius      */
 /* lambda:  g~_i(l) = min{1, lambda / ||g_i(l)||_2} g_i(l).  This returns the */

@@ -67,6 +67,10 @@ def _load():
     lib.oracle_verification3.argtypes = [c.c_void_p, c.c_int32, c.c_int32, c.c_double,
                                          c.c_void_p, c.c_void_p, c.c_void_p]
     lib.oracle_verification3.restype = c.c_int
+    lib.oracle_verification12.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
+                                          c.c_int32, c.c_double, c.c_double, c.c_void_p,
+                                          c.c_void_p, c.c_void_p]
+    lib.oracle_verification12.restype = c.c_int
     lib.oracle_preclip_scales.argtypes = [
         c.c_void_p, c.c_int64, c.c_int32, P(c.c_int64), c.c_int32, c.c_double, c.c_void_p,
         c.c_void_p]
@@ -185,6 +189,23 @@ def verification3(norms, delta_max: float):
                                     votes.ctypes.data, trigger.ctypes.data) != 0:
         raise ValueError("oracle_verification3: bad arguments")
     return check, votes, trigger
+
+
+def verification12(claimed_norms, claimed_proj, norms, proj, rtol: float, atol: float):
+    """Verifications 1 and 2 of Alg. 6 as comparisons: (bad_norm [n, P], bad_proj [n, P],
+    bad_sum [P]), all uint8."""
+    arrs = [np.ascontiguousarray(a, dtype=np.float64) for a in (claimed_norms, claimed_proj, norms, proj)]
+    n, Pn = arrs[2].shape
+    assert all(a.shape == (n, Pn) for a in arrs)
+    bad_norm = np.zeros((n, Pn), dtype=np.uint8)
+    bad_proj = np.zeros((n, Pn), dtype=np.uint8)
+    bad_sum = np.zeros(Pn, dtype=np.uint8)
+    if _load().oracle_verification12(arrs[0].ctypes.data, arrs[1].ctypes.data, arrs[2].ctypes.data,
+                                     arrs[3].ctypes.data, n, Pn, float(rtol), float(atol),
+                                     bad_norm.ctypes.data, bad_proj.ctypes.data,
+                                     bad_sum.ctypes.data) != 0:
+        raise ValueError("oracle_verification12: bad arguments")
+    return bad_norm, bad_proj, bad_sum
 
 
 def centered_clip(G, off, tau: float, eps: float, max_iters: int,

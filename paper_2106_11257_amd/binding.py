@@ -112,6 +112,10 @@ def load_library():
     lib.btard_verification3.argtypes = [c.c_void_p, c.c_int32, c.c_int32, c.c_double, c.c_void_p,
                                         c.c_void_p, c.c_void_p, c.c_void_p]
     lib.btard_verification3.restype = c.c_int
+    lib.btard_verification12.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
+                                         c.c_int32, c.c_double, c.c_double, c.c_void_p,
+                                         c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.btard_verification12.restype = c.c_int
     lib.btard_cc_preclip_factors.argtypes = [c.POINTER(_Problem), c.c_void_p]
     lib.btard_cc_preclip_factors.restype = c.c_int
     lib.btard_centered_clip_verify_preclipped.argtypes = [
@@ -391,6 +395,24 @@ def verification3(norms: torch.Tensor, delta_max: float):
     return check, votes, trigger
 
 
+def verification12(claimed_norms: torch.Tensor, claimed_proj: torch.Tensor, norms: torch.Tensor,
+                   proj: torch.Tensor, rtol: float, atol: float):
+    """btard_verification12.  All inputs [n, parts] fp64 on the device.  Returns (bad_norm
+    [n, parts] uint8, bad_proj [n, parts] uint8, bad_sum [parts] uint8)."""
+    n, P = int(norms.shape[0]), int(norms.shape[1])
+    for t in (claimed_norms, claimed_proj, norms, proj):
+        assert t.dtype == torch.float64 and t.is_contiguous() and tuple(t.shape) == (n, P)
+    dev = norms.device
+    bad_norm = torch.empty((n, P), dtype=torch.uint8, device=dev)
+    bad_proj = torch.empty((n, P), dtype=torch.uint8, device=dev)
+    bad_sum = torch.empty(P, dtype=torch.uint8, device=dev)
+    _check(load_library().btard_verification12(
+        _ptr(claimed_norms), _ptr(claimed_proj), _ptr(norms), _ptr(proj), n, P, float(rtol),
+        float(atol), _ptr(bad_norm), _ptr(bad_proj), _ptr(bad_sum), _stream_ptr(dev)),
+        "btard_verification12")
+    return bad_norm, bad_proj, bad_sum
+
+
 def cc_preclip_factors(p: Problem, out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """btard_cc_preclip_factors.  Returns the [n, parts] fp64 factors alpha_ij."""
     n = int(p.g.shape[0])
@@ -486,5 +508,6 @@ btard_tau_schedule = tau_schedule
 btard_geometric_median = geometric_median
 btard_coordinate_median = coordinate_median
 btard_verification3 = verification3
+btard_verification12 = verification12
 btard_centered_clip_verify_preclipped = centered_clip_verify_preclipped
 btard_debug_zhat = debug_zhat

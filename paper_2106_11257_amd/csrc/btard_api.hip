@@ -737,6 +737,21 @@ int btard_verification3(const double *norms, int32_t n, int32_t parts, double de
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 
+int btard_verification12(const double *claimed_norms, const double *claimed_proj,
+                         const double *norms, const double *proj, int32_t n, int32_t parts,
+                         double rtol, double atol, uint8_t *bad_norm, uint8_t *bad_proj,
+                         uint8_t *bad_sum, void *stream)
+{
+    if (!claimed_norms || !claimed_proj || !norms || !proj || !bad_norm || !bad_proj || !bad_sum ||
+        n < 1 || n > kMaxPeers || parts < 1 || parts > kMaxParts || !(rtol >= 0.0) ||
+        !(atol >= 0.0))
+        return BTARD_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(verification12_kernel, dim3((parts + 63) / 64), dim3(64), 0,
+                       static_cast<hipStream_t>(stream), claimed_norms, claimed_proj, norms, proj,
+                       n, parts, rtol, atol, bad_norm, bad_proj, bad_sum);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
 int btard_cc_preclip_factors(const btard_cc_problem *p, double *factors)
 {
     const int rc = check_problem(p);

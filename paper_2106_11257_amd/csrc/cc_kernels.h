@@ -620,4 +620,27 @@ __global__ void verification3_kernel(const double *norms, int32_t n, int32_t P, 
     trigger[j] = (2 * cnt > n) ? 1 : 0;
 }
 
+// Verifications 1 and 2 of Alg. 6 as comparisons of what peers broadcast with what was
+// recomputed: a value "does not match" when it differs by more than atol + rtol |recomputed|
+// (or is NaN); the broadcast projections of a partition "do not sum to zero" when
+// |sum_i s_ij| > atol + rtol sum_i |s_ij| (summed over i = 0 .. n-1 in order).  One thread per
+// partition.
+__global__ void verification12_kernel(const double *claimed_norms, const double *claimed_proj,
+                                      const double *norms, const double *proj, int32_t n,
+                                      int32_t P, double rtol, double atol, uint8_t *bad_norm,
+                                      uint8_t *bad_proj, uint8_t *bad_sum)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= P) return;
+    double sum = 0.0, mag = 0.0;
+    for (int i = 0; i < n; ++i) {
+        const int64_t q = (int64_t)i * P + j;
+        bad_norm[q] = (fabs(claimed_norms[q] - norms[q]) <= atol + rtol * fabs(norms[q])) ? 0 : 1;
+        bad_proj[q] = (fabs(claimed_proj[q] - proj[q]) <= atol + rtol * fabs(proj[q])) ? 0 : 1;
+        sum += claimed_proj[q];
+        mag += fabs(claimed_proj[q]);
+    }
+    bad_sum[j] = (fabs(sum) <= atol + rtol * mag) ? 0 : 1;
+}
+
 }  // namespace btard

@@ -108,6 +108,13 @@ def test_argument_errors_are_caught_on_the_host_before_any_gpu_call():
     assert cm(ld=7) == -1 and cm(d=-1) == -1
     assert cm(g=None, v=None, d=0, ld=0) == 0          # nothing to do
 
+    def v12(a=fake, n=2, parts=2, rtol=1e-6, atol=0.0, out=fake):
+        return lib.btard_verification12(a, fake, fake, fake, n, parts, rtol, atol, out, fake, fake,
+                                        None)
+
+    assert v12(a=None) == -1 and v12(out=None) == -1 and v12(n=0) == -1 and v12(parts=0) == -1
+    assert v12(rtol=-1.0) == -1 and v12(atol=float("nan")) == -1
+
     def vp(g=fake, v=fake, norms=fake, tau=1.0, delta=None, ldd=0, wsb=big):
         return lib.btard_verify_projections(g, 8, 2, 8, off, 2, v, tau, 1, norms, fake, fake, None,
                                             delta, ldd, ws, wsb, None, 0)

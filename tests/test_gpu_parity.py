@@ -541,6 +541,34 @@ def test_verification3_flags(dev):
     assert 0 < int(votes.sum()) < nh.size
 
 
+def test_verifications_1_and_2_flags(dev):
+    G, off = workloads.generic_case(9, 4000, 6, seed=78, device=dev, spread=0.05, outliers=3,
+                                    outlier_scale=3.0)
+    v, iters, sn = btard.centered_clip(G, off, 1.0, 1e-9, 400)
+    out = btard.verify_projections(G, off, v, 1.0, 5)
+    norms, proj = out["norms"], out["proj"]
+    torch.cuda.synchronize()
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    # broadcasts with relative errors spread around the tolerance, and a few gross lies
+    cn = norms * (1 + 1e-7 * torch.randn(norms.shape, generator=gen, device=dev, dtype=torch.float64))
+    cp = proj * (1 + 1e-7 * torch.randn(proj.shape, generator=gen, device=dev, dtype=torch.float64))
+    cn[2, 3] = float("nan")
+    cp[4, 1] += 0.3
+    cp[0, 5] = -cp[0, 5]
+    for rtol, atol in ((1e-7, 0.0), (0.0, 0.0), (1e-3, 1e-12), (0.0, 1e-9)):
+        got = btard.verification12(cn, cp, norms, proj, rtol, atol)
+        torch.cuda.synchronize()
+        ref = oracle.verification12(cn.cpu().numpy(), cp.cpu().numpy(), norms.cpu().numpy(),
+                                    proj.cpu().numpy(), rtol, atol)
+        for g, r in zip(got, ref):
+            assert np.array_equal(g.cpu().numpy(), r)
+    bn, bp, bs = btard.verification12(cn, cp, norms, proj, 1e-7, 0.0)
+    assert 0 < int(bn.sum()) < bn.numel() and int(bp[4, 1]) == 1 and int(bs[1]) == 1
+    bn, bp, bs = btard.verification12(norms, proj, norms, proj, 0.0, 1e-6)
+    assert int(bn.sum()) == 0 and int(bp.sum()) == 0 and int(bs.sum()) == 0
+
+
 # --------------------------------------------------------------------------
 # the five benchmark configurations: reduced length (whole oracle) and full size
 # --------------------------------------------------------------------------

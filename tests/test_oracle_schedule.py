@@ -98,3 +98,56 @@ def test_verification3_counts_and_strict_majority():
     r = rng(4).random((9, 6)) * 3
     check, votes, trigger = oracle.verification3(r, 1.5)
     assert np.array_equal(votes, (r > 1.5).sum(axis=0)) and np.array_equal(trigger, votes * 2 > 9)
+
+
+def test_verifications_1_and_2_on_an_honest_run_and_on_planted_lies():
+    """The comparisons of Alg. 6 (Verification 1: broadcast norm vs recomputed; Verification 2:
+    broadcast projection vs recomputed, and the column sums) on the oracle's own verification
+    quantities at a CenteredClip fixed point: an honest broadcast raises no flag (the column
+    sums vanish there, eq. (2)); a lie about one norm, one projection, or a wrong aggregate
+    raises exactly the flags the algorithm describes."""
+    rng = np.random.default_rng(12)
+    n, d, P = 7, 240, 4
+    G = rng.standard_normal((n, d)).astype(np.float32)
+    G[5:] *= np.float32(9.0)
+    off = [int(x) for x in oracle.split(d, P)]
+    tau, seed = 1.5, 99
+    v, iters, _, _ = oracle.centered_clip(G, off, tau, 1e-13, 20000)
+    assert (iters < 20000).all()
+    out = oracle.verify(G, off, v, tau, seed)
+    norms, proj = out["norms"], out["proj"]
+    rtol, atol = 1e-9, 1e-9
+    bn, bp, bs = oracle.verification12(norms, proj, norms, proj, rtol, atol)
+    assert not bn.any() and not bp.any() and not bs.any()
+    # tolerance: a relative change below rtol passes, above it fails (checked by hand here)
+    cn = norms.copy(); cn[2, 1] *= 1 + 5e-10; cn[3, 0] *= 1 + 5e-9
+    # ... and a projection moved to between the two thresholds: beyond atol + rtol |s_42|
+    # (it does not match) but within atol + rtol sum_i |s_i2| (the column still sums to zero)
+    col = np.abs(proj[:, 2]).sum()
+    assert col > 2 * abs(proj[4, 2])
+    cp = proj.copy(); cp[4, 2] += atol + rtol * abs(proj[4, 2]) + 0.5 * rtol * (col - abs(proj[4, 2]))
+    bn, bp, bs = oracle.verification12(cn, cp, norms, proj, rtol, atol)
+    assert bn.sum() == 1 and bn[3, 0] == 1
+    assert bp.sum() == 1 and bp[4, 2] == 1
+    assert not bs.any()
+    # a peer that misreports its projection by a visible amount breaks the sum of its column
+    cp = proj.copy(); cp[1, 3] += 0.5
+    bn, bp, bs = oracle.verification12(norms, cp, norms, proj, rtol, atol)
+    assert bp.sum() == 1 and bp[1, 3] == 1 and bs.tolist() == [0, 0, 0, 1]
+    # a wrong aggregate for partition 2: honest peers' recomputed projections no longer sum to 0
+    v_bad = v.copy(); v_bad[off[2]:off[3]] += 0.05
+    out_bad = oracle.verify(G, off, v_bad, tau, seed)
+    bn, bp, bs = oracle.verification12(out_bad["norms"], out_bad["proj"], out_bad["norms"],
+                                       out_bad["proj"], rtol, atol)
+    assert not bn.any() and not bp.any() and bs.tolist() == [0, 0, 1, 0]
+    # NaN never matches; zero tolerances demand equality
+    cn = norms.copy(); cn[0, 0] = np.nan
+    bn, _, _ = oracle.verification12(cn, proj, norms, proj, rtol, atol)
+    assert bn[0, 0] == 1 and bn.sum() == 1
+    bn, bp, bs = oracle.verification12(norms, proj, norms, proj, 0.0, 0.0)
+    assert not bn.any() and not bp.any()
+    ones = np.array([[1.0], [-1.0], [0.25], [-0.25]])
+    assert oracle.verification12(ones, ones, ones, ones, 0.0, 0.0)[2].tolist() == [0]
+    ones[3, 0] = -0.5
+    assert oracle.verification12(ones, ones, ones, ones, 0.0, 0.0)[2].tolist() == [1]
+    assert oracle.verification12(ones, ones, ones, ones, 0.2, 0.0)[2].tolist() == [0]   # 0.25 <= 0.2 * 2.75
