@@ -24,6 +24,10 @@
  *   - Calls that share a workspace must be ordered on one stream.  Results are
  *     bit-reproducible from run to run on the same device (no atomics; every
  *     reduction in a fixed order).
+ *   - Every entry point that neither takes BTARD_FLAG_HOST_SYNC nor reads a
+ *     result back (btard_cc_remaining) only launches kernels -- state is cleared
+ *     by kernels, never by memset operations -- so a sequence of calls may be
+ *     captured into a HIP graph on `stream` and replayed.
  *   - Limits: 1 <= n <= 255, 1 <= parts <= 65535, 0 <= d <= ldg.
  */
 #ifndef BTARD_H_

@@ -541,6 +541,60 @@ def test_verification3_flags(dev):
     assert 0 < int(votes.sum()) < nh.size
 
 
+def test_headline_step_replayed_as_a_hip_graph(dev):
+    """The unsynchronised headline step (begin, Gram matrix, Gram iteration, fused last pass)
+    captured once and replayed several times, with eager work and synchronisations between
+    the replays: every replay must give exactly what the eager launches give."""
+    wl = workloads.make_workload(2, device=dev, d=300_007)
+    G, off, n, P = wl.G, wl.offsets, wl.n, wl.parts
+    ws = btard.alloc_workspace(n, P, dev)
+
+    def buffers():
+        b = {k: torch.zeros((n, P), dtype=torch.float64, device=dev) for k in ("norms", "weights", "proj")}
+        b["colsum"] = torch.zeros(P, dtype=torch.float64, device=dev)
+        return (torch.zeros(wl.d, dtype=torch.float32, device=dev),
+                torch.zeros(P, dtype=torch.int32, device=dev),
+                torch.zeros(P, dtype=torch.float64, device=dev), b)
+
+    def step(prob, bufs):
+        v, iters, sn, out = bufs
+        btard.cc_begin(prob)
+        btard.cc_gram_matrix(prob)
+        btard.cc_gram_iterate(prob)
+        btard.cc_finish_verify(prob, 0, wl.seed_z, v, iters, sn, out=out)
+
+    eager = buffers()
+    prob_e = btard.make_problem(G, off, wl.tau, wl.eps, wl.max_iters, workspace=ws,
+                                flags=btard.BTARD_FLAG_GRAM)
+    step(prob_e, eager)
+    torch.cuda.synchronize()
+    assert btard.cc_remaining(prob_e) == 0
+    want = [eager[0].clone(), eager[1].clone(), eager[2].clone()] + [eager[3][k].clone() for k in sorted(eager[3])]
+
+    replayed = buffers()
+    step(btard.make_problem(G, off, wl.tau, wl.eps, wl.max_iters, workspace=ws,
+                            flags=btard.BTARD_FLAG_GRAM), replayed)      # warm-up outside capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        prob_g = btard.make_problem(G, off, wl.tau, wl.eps, wl.max_iters, workspace=ws,
+                                    flags=btard.BTARD_FLAG_GRAM)
+        step(prob_g, replayed)
+    for k in range(4):
+        say(f"[graph] replay {k}")
+        for t in [replayed[0], replayed[1], replayed[2]] + list(replayed[3].values()):
+            t.zero_()
+        # eager work on the same workspace between the replays (another problem's state)
+        btard.centered_clip(G, off, 0.5 * wl.tau, wl.eps, 3 + k, workspace=ws)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert btard.cc_remaining(prob_g) == 0
+        got = [replayed[0], replayed[1], replayed[2]] + [replayed[3][k2] for k2 in sorted(replayed[3])]
+        for a, b in zip(got, want):
+            assert torch.equal(a, b)
+
+
 def test_verifications_1_and_2_flags(dev):
     G, off = workloads.generic_case(9, 4000, 6, seed=78, device=dev, spread=0.05, outliers=3,
                                     outlier_scale=3.0)
