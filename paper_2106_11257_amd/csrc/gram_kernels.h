@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
 // Every row is needed by three of the four wavefronts, so a tile goes through LDS: each
 // wavefront loads NP/4 rows of the next tile from memory while the workgroup multiplies the
 // current one; two tiles in LDS, one barrier per tile.
-// Measured on an 8.6 GB slab with n = 8: 1.38 ms against 1.61 ms for the MFMA form with two
+// Measured on an 8.6 GB slab with n = 8: 1.24 ms against 1.61 ms for the MFMA form with two
 // coordinates per 16-row block.  The template also works for NP = 16, where it was measured
 // level with the MFMA kernel (140 against 142-147 us on an 0.7 GB slab) and is not used.
 // Two other forms of the same split were slower than the MFMA kernel: every wavefront
@@ -156,7 +156,7 @@ __device__ __forceinline__ void band_fetch(const global_f32 (&row)[GramBand<NP>:
     for (int m = 0; m < GramBand<NP>::kBase; ++m) {
         const char __attribute__((address_space(1))) *base =
             (const char __attribute__((address_space(1))) *)(row[m] + xu);
-        g[m] = *(global_f32x4)(base + lane_bytes);
+        g[m] = stream_load((global_f32x4)(base + lane_bytes));
     }
 }
 
