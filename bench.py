@@ -88,6 +88,8 @@ def main() -> int:
     ap.add_argument("--baselines", action="store_true",
                     help="also time the baseline aggregators of Sec. 4.1 on the same slab "
                          "(coordinate-wise median; geometric median, 20 Weiszfeld iterations)")
+    ap.add_argument("--hashes", action="store_true",
+                    help="also time the partition hashes (SHA-256 tree) of the slab and of v")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of known size (1 GiB read + 1 GiB "
@@ -380,6 +382,49 @@ def main() -> int:
                 # gm_iters passes and the pass that writes v
                 "us_per_pass": round(t_gm * 1e3 / (gm_iters + 1), 2),
                 "achieved_GBps": round(slab_bytes * (gm_iters + 1) / (t_gm * 1e-3) / 1e9, 1)},
+        }
+
+    # ---- the commitments hash(g_i[j]) and hash(v[j]) (not part of the headline step)
+    if args.hashes:
+        hws = torch.empty(max(btard.hash_workspace_bytes(n, off), 256), dtype=torch.uint8, device=dev)
+        dig = torch.empty((n, P, 32), dtype=torch.uint8, device=dev)
+        dig_v = torch.empty((1, P, 32), dtype=torch.uint8, device=dev)
+
+        def timed_ms(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        t_h = timed_ms(lambda: btard.partition_hashes(G, off, hws, dig), 3)
+        t_v = timed_ms(lambda: btard.partition_hashes(v, off, hws, dig_v), 3)
+        # 1402 vector instructions per 64-byte SHA-256 block (counted in the kernel's code);
+        # blocks by the tree's rule: chunks of 1024 bytes, then runs of 32 digests
+        def sha_blocks(nbytes):
+            return (nbytes + 8) // 64 + 1
+
+        def tree_blocks(words):
+            nbytes = 4 * words
+            cnt = max(1, -(-nbytes // 1024))
+            total = (cnt - 1) * sha_blocks(1024) + sha_blocks(nbytes - (cnt - 1) * 1024)
+            while cnt > 1:
+                groups = -(-cnt // 32)
+                total += (groups - 1) * sha_blocks(32 * 32) + sha_blocks((cnt - (groups - 1) * 32) * 32)
+                cnt = groups
+            return total
+        blocks = n * sum(tree_blocks(w) for w in sizes)
+        lane_ops = blocks * 1402.0
+        alu_peak = 256 * 4 * 16 * 2.4e9          # lanes x clock: one 32-bit instruction per lane and cycle
+        out["hashes"] = {
+            "slab_ms": round(t_h, 4), "slab_GBps": round(slab_bytes / (t_h * 1e-3) / 1e9, 1),
+            "aggregate_ms": round(t_v, 4),
+            "roofline": {"bound": "alu", "achieved": round(lane_ops / (t_h * 1e-3) / 1e12, 2),
+                         "peak": round(alu_peak / 1e12, 2), "unit": "T lane-instructions/s",
+                         "frac": round(lane_ops / (t_h * 1e-3) / alu_peak, 4)},
         }
 
     # ---- the oracle on the host cores, as a baseline only

@@ -283,6 +283,24 @@ int btard_coordinate_median(const float *g, int64_t ldg, int32_t n, int64_t d, f
                             void *stream);
 
 /*
+ * The commitments of Alg. 2 (lines 2 and 6): digests[(i * parts + j) * 32 .. + 31] (DEVICE,
+ * 4-byte aligned) = hash(g_i[j]), the hash of the bytes of row i's columns
+ * [offsets_host[j], offsets_host[j+1]) as they lie in memory (fp32, little-endian).  With
+ * n = 1 and g = the aggregate this is hash(g^[j]).  The paper names no hash function; this one
+ * is SHA-256 (FIPS 180-4) arranged as a tree: the bytes are cut into chunks of 1024 (an empty
+ * partition is one empty chunk), each chunk's SHA-256 is a node; while a partition has more
+ * than one node, every run of 32 consecutive node digests (the last may be shorter) is
+ * replaced by the SHA-256 of their concatenation; the remaining node is the hash.  A
+ * partition of at most 1024 bytes is hashed by plain SHA-256.
+ * workspace: DEVICE, 256-byte aligned, btard_hash_workspace_bytes(n, offsets_host, parts)
+ * bytes (0 for bad arguments).  Enqueued on `stream`.
+ */
+size_t btard_hash_workspace_bytes(int32_t n, const int64_t *offsets_host, int32_t parts);
+int btard_partition_hashes(const float *g, int64_t ldg, int32_t n, int64_t d,
+                           const int64_t *offsets_host, int32_t parts, uint8_t *digests,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * tau_l of App. D.2, eq. (5), for l = 0 .. count - 1 (HOST out):
  *   tau_l = 4 sqrt((1 - delta)(B_l^2 / 3 + sigma^2) / (sqrt(3) delta)),
  *   B_{l+1}^2 = 6.45 delta B_l^2 + 5 sigma^2,  B_0 = b0.

@@ -15,6 +15,7 @@ from .oracle import (  # noqa: F401
     tau_schedule,
     verification3,
     verification12,
+    partition_hashes,
     verify,
     z_hat,
     z_norm,

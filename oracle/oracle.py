@@ -169,6 +169,30 @@ def coordinate_median(G) -> np.ndarray:
     return v[:d]
 
 
+def partition_hashes(G, off, chunk_bytes: int = 1024, fanout: int = 32) -> np.ndarray:
+    """hash(g_i[j]) of Alg. 2 (lines 2 and 6) with the hash function this build fixes, since
+    the paper names none: SHA-256 (the library's) over a tree.  The partition's bytes (fp32,
+    little-endian, as stored) are cut into chunks of `chunk_bytes` (an empty partition is one
+    empty chunk) and every chunk is hashed; while more than one digest remains, every run of
+    `fanout` consecutive digests (the last may be shorter) is replaced by the SHA-256 of
+    their concatenation.  Returns uint8 [n, P, 32]."""
+    import hashlib
+    G = _as_G(G)
+    n = G.shape[0]
+    Pn = len(off) - 1
+    out = np.zeros((n, Pn, 32), dtype=np.uint8)
+    for i in range(n):
+        for j in range(Pn):
+            data = np.ascontiguousarray(G[i, int(off[j]):int(off[j + 1])]).astype("<f4").tobytes()
+            nodes = [hashlib.sha256(data[k:k + chunk_bytes]).digest()
+                     for k in range(0, max(len(data), 1), chunk_bytes)]
+            while len(nodes) > 1:
+                nodes = [hashlib.sha256(b"".join(nodes[k:k + fanout])).digest()
+                         for k in range(0, len(nodes), fanout)]
+            out[i, j] = np.frombuffer(nodes[0], dtype=np.uint8)
+    return out
+
+
 def tau_schedule(delta: float, sigma: float, B0: float, count: int):
     """The clipping radii tau_l of eq. (5): (tau [count], B_l^2 [count])."""
     tau = np.zeros(max(count, 1)); b2 = np.zeros(max(count, 1))

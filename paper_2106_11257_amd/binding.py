@@ -106,6 +106,12 @@ def load_library():
     lib.btard_coordinate_median.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int64,
                                             c.c_void_p, c.c_void_p]
     lib.btard_coordinate_median.restype = c.c_int
+    lib.btard_hash_workspace_bytes.argtypes = [c.c_int32, c.POINTER(c.c_int64), c.c_int32]
+    lib.btard_hash_workspace_bytes.restype = c.c_size_t
+    lib.btard_partition_hashes.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int64,
+                                           c.POINTER(c.c_int64), c.c_int32, c.c_void_p,
+                                           c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.btard_partition_hashes.restype = c.c_int
     lib.btard_tau_schedule.argtypes = [c.c_double, c.c_double, c.c_double, c.c_int32,
                                        c.POINTER(c.c_float)]
     lib.btard_tau_schedule.restype = c.c_int
@@ -372,6 +378,33 @@ def coordinate_median(g: torch.Tensor, v: Optional[torch.Tensor] = None) -> torc
     return v
 
 
+def hash_workspace_bytes(n: int, offsets: Sequence[int]) -> int:
+    return int(load_library().btard_hash_workspace_bytes(int(n), _off_array(offsets),
+                                                         len(offsets) - 1))
+
+
+def partition_hashes(g: torch.Tensor, offsets: Sequence[int],
+                     workspace: Optional[torch.Tensor] = None,
+                     digests: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """btard_partition_hashes.  g: [n, d] fp32 (a 1-D tensor counts as one row).  Returns the
+    digests, uint8 [n, parts, 32]."""
+    if g.dim() == 1:
+        g = g.unsqueeze(0)
+    n, d = int(g.shape[0]), int(g.shape[1])
+    P = len(offsets) - 1
+    dev = g.device
+    if workspace is None:
+        workspace = torch.empty(max(hash_workspace_bytes(n, offsets), 256), dtype=torch.uint8,
+                                device=dev)
+    if digests is None:
+        digests = torch.empty((n, P, 32), dtype=torch.uint8, device=dev)
+    rc = load_library().btard_partition_hashes(
+        _ptr(g), _row_stride(g), n, d, _off_array(offsets), P, _ptr(digests), _ptr(workspace),
+        workspace.numel(), _stream_ptr(dev))
+    _check(rc, "btard_partition_hashes")
+    return digests
+
+
 def tau_schedule(delta: float, sigma: float, b0: float, count: int) -> List[float]:
     """btard_tau_schedule: the radii tau_l of eq. (5), as the fp32 values the library uses."""
     out = (ctypes.c_float * max(count, 1))()
@@ -505,6 +538,8 @@ btard_cc_finish_verify = cc_finish_verify
 btard_centered_clip_verify = centered_clip_verify
 btard_cc_preclip_factors = cc_preclip_factors
 btard_tau_schedule = tau_schedule
+btard_hash_workspace_bytes = hash_workspace_bytes
+btard_partition_hashes = partition_hashes
 btard_geometric_median = geometric_median
 btard_coordinate_median = coordinate_median
 btard_verification3 = verification3

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbtard.so")
 SOURCES = ["btard_api.hip"]
-HEADERS = ["kernels_common.h", "cc_kernels.h", "verify_kernels.h", "fused_kernels.h", "gram_kernels.h", "median_kernels.h",
+HEADERS = ["kernels_common.h", "cc_kernels.h", "verify_kernels.h", "fused_kernels.h", "gram_kernels.h", "median_kernels.h", "hash_kernels.h",
            os.path.join("..", "..", "include", "btard.h")]
 
 HIPCC_FLAGS = [

@@ -15,6 +15,7 @@
 #include "cc_kernels.h"
 #include "fused_kernels.h"
 #include "gram_kernels.h"
+#include "hash_kernels.h"
 #include "median_kernels.h"
 #include "verify_kernels.h"
 
@@ -708,6 +709,119 @@ int btard_coordinate_median(const float *g, int64_t ldg, int32_t n, int64_t d, f
     MedianArgs a;
     a.g = g; a.ld = ldg; a.n = n; a.d = d; a.v = v;
     hipLaunchKernelGGL(fn, dim3(B), dim3(kBlock), 0, static_cast<hipStream_t>(stream), a);
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+// ---- partition hashes: the tree's shape, on the host
+namespace {
+struct HashPlan {
+    std::vector<std::vector<int64_t>> node;      // per level: [P + 1] prefix sums of node counts
+    size_t off_bytes = 0;                        // [P + 1] offsets
+    size_t tables_bytes = 0;                     // all node tables
+    size_t total = 0;                            // workspace bytes
+    std::vector<size_t> table_at, digest_at;     // byte offsets per level
+};
+
+bool hash_plan(int32_t n, const int64_t *off, int32_t P, HashPlan &h)
+{
+    std::vector<int64_t> cnt((size_t)P);
+    for (int32_t j = 0; j < P; ++j) {
+        const int64_t bytes = (off[j + 1] - off[j]) * 4;
+        cnt[(size_t)j] = bytes > 0 ? (bytes + kHashChunkBytes - 1) / kHashChunkBytes : 1;
+    }
+    for (;;) {
+        std::vector<int64_t> pre((size_t)P + 1, 0);
+        bool single = true;
+        for (int32_t j = 0; j < P; ++j) {
+            pre[(size_t)j + 1] = pre[(size_t)j] + cnt[(size_t)j];
+            if (cnt[(size_t)j] > 1) single = false;
+        }
+        h.node.push_back(pre);
+        if (single) break;
+        for (int32_t j = 0; j < P; ++j)
+            if (cnt[(size_t)j] > 1) cnt[(size_t)j] = (cnt[(size_t)j] + kHashFanout - 1) / kHashFanout;
+    }
+    size_t at = 0;
+    h.off_bytes = align_up(sizeof(int64_t) * ((size_t)P + 1));
+    at += h.off_bytes;
+    for (size_t k = 0; k < h.node.size(); ++k) {
+        h.table_at.push_back(at);
+        at += align_up(sizeof(int64_t) * ((size_t)P + 1));
+    }
+    // the last level's digests go to the caller's array; the others live in the workspace
+    for (size_t k = 0; k + 1 < h.node.size(); ++k) {
+        h.digest_at.push_back(at);
+        at += align_up((size_t)n * (size_t)h.node[k][(size_t)P] * kDigestBytes);
+    }
+    h.total = at;
+    return true;
+}
+
+int upload_int64(const std::vector<int64_t> &src, int64_t *dst, hipStream_t s)
+{
+    const int32_t count_all = (int32_t)src.size();
+    for (int32_t first = 0; first < count_all; first += kOffChunk) {
+        OffChunk chunk;
+        const int32_t count = (count_all - first < kOffChunk) ? (count_all - first) : kOffChunk;
+        for (int32_t t = 0; t < kOffChunk; ++t) chunk.v[t] = (t < count) ? src[(size_t)(first + t)] : 0;
+        hipLaunchKernelGGL(upload_offsets_kernel, dim3(1), dim3(kOffChunk), 0, s, dst, first, count,
+                           chunk);
+    }
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+}  // namespace
+
+size_t btard_hash_workspace_bytes(int32_t n, const int64_t *offsets_host, int32_t parts)
+{
+    if (n < 1 || n > kMaxPeers || parts < 1 || parts > kMaxParts || !offsets_host) return 0;
+    for (int32_t j = 0; j < parts; ++j)
+        if (offsets_host[j] > offsets_host[j + 1]) return 0;
+    HashPlan h;
+    hash_plan(n, offsets_host, parts, h);
+    return h.total < kAlign ? kAlign : h.total;
+}
+
+int btard_partition_hashes(const float *g, int64_t ldg, int32_t n, int64_t d,
+                           const int64_t *offsets_host, int32_t parts, uint8_t *digests,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    // (with d = 0 there is nothing to read and g may be NULL: every digest is that of the
+    // empty message)
+    static const float nothing = 0.0f;
+    if (!basic_args_ok((d == 0 && !g) ? &nothing : g, ldg, n, d, offsets_host, parts) || !digests)
+        return BTARD_ERR_INVALID_ARG;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0) return BTARD_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(digests) % 4) != 0) return BTARD_ERR_INVALID_ARG;
+    HashPlan h;
+    hash_plan(n, offsets_host, parts, h);
+    if (workspace_bytes < h.total) return BTARD_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    int64_t *off_dev = reinterpret_cast<int64_t *>(ws);
+    std::vector<int64_t> off_vec(offsets_host, offsets_host + parts + 1);
+    int rc = upload_int64(off_vec, off_dev, s);
+    if (rc != BTARD_OK) return rc;
+    const size_t levels = h.node.size();
+    for (size_t k = 0; k < levels; ++k) {
+        rc = upload_int64(h.node[k], reinterpret_cast<int64_t *>(ws + h.table_at[k]), s);
+        if (rc != BTARD_OK) return rc;
+    }
+    for (size_t k = 0; k < levels; ++k) {
+        HashArgs a;
+        a.g = g; a.ld = ldg; a.off = off_dev;
+        a.in = k > 0 ? reinterpret_cast<const uint32_t *>(ws + h.digest_at[k - 1]) : nullptr;
+        a.node_in = k > 0 ? reinterpret_cast<const int64_t *>(ws + h.table_at[k - 1]) : nullptr;
+        a.total_in = k > 0 ? h.node[k - 1][(size_t)parts] : 0;
+        a.out = (k + 1 < levels) ? reinterpret_cast<uint32_t *>(ws + h.digest_at[k])
+                                 : reinterpret_cast<uint32_t *>(digests);
+        a.node_out = reinterpret_cast<const int64_t *>(ws + h.table_at[k]);
+        a.total_out = h.node[k][(size_t)parts];
+        a.n = n; a.P = parts; a.level = (int32_t)k;
+        const int64_t lanes = (int64_t)n * a.total_out;
+        const int64_t blocks = (lanes + kBlock - 1) / kBlock;
+        if (blocks > 0x7fffffffLL) return BTARD_ERR_INVALID_ARG;
+        hipLaunchKernelGGL(hash_level_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
+    }
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 

@@ -1,0 +1,96 @@
+"""GPU parity of the partition hashes (SHA-256 tree, the commitments of Alg. 2) against the
+oracle: byte for byte."""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2106_11257_amd as btard
+from paper_2106_11257_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch.device("cuda:0")
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def check(G, off, label=""):
+    say(f"[hash] {label} shape={tuple(G.shape)} P={len(off) - 1}")
+    H = btard.partition_hashes(G, off)
+    torch.cuda.synchronize()
+    Gh = G.cpu().numpy()
+    want = oracle.partition_hashes(Gh if Gh.ndim == 2 else Gh[None, :], off)
+    got = H.cpu().numpy()
+    assert got.shape == want.shape
+    bad = np.argwhere((got != want).any(axis=2))
+    assert bad.size == 0, f"digests differ at (peer, partition) {bad[:5].tolist()}"
+    return got
+
+
+def test_known_answers_of_the_standard(dev, golden_dir):
+    for line in open(os.path.join(golden_dir, "sha256_kat.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        msg, want = line.split()
+        msg = b"" if msg == "-" else msg.encode("ascii")
+        words = np.frombuffer(msg, dtype="<f4")
+        G = torch.from_numpy(words.copy()).to(dev).reshape(1, -1)
+        H = btard.partition_hashes(G, [0, G.shape[1]])
+        torch.cuda.synchronize()
+        assert bytes(H.cpu().numpy()[0, 0]).hex() == want
+
+
+@pytest.mark.parametrize("words", [0, 1, 13, 14, 15, 16, 17, 29, 30, 31, 32, 255, 256, 257, 512,
+                                   5000, 8191, 8192, 8193, 70001])
+def test_one_partition_of_every_length_class(dev, words):
+    """Padding cases (13/14/15 words left in the last block), chunk boundaries, one and two
+    levels above the chunks."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(100 + words)
+    G = torch.randn((3, words + 3), generator=gen, device=dev)[:, :words]
+    check(G, [0, words], "length classes")
+
+
+def test_many_partitions_empty_and_ragged(dev):
+    G, _ = workloads.generic_case(20, 300_007, 1, seed=5, device=dev, ld=300_011)
+    off = [0, 0, 1, 257, 257, 70_000, 70_001, 140_000, 299_000, 300_007]
+    got = check(G, off, "ragged")
+    assert (got[:, 0] == got[:, 3]).all()              # two empty partitions
+    off16 = workloads.split_offsets(300_007, 16)
+    check(G, off16, "split")
+
+
+def test_three_levels_and_the_aggregate_as_one_row(dev):
+    words = 32 * 32 * 256 * 3 + 5                      # 3073 chunks: 97 nodes, 4 nodes, 1 node
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(9)
+    v = torch.randn(words, generator=gen, device=dev)
+    check(v, [0, words], "three levels, 1-D input")
+    check(v, [0, 5, words], "three levels, two partitions")
+
+
+def test_full_size_resnet18_slab(dev):
+    wl = workloads.make_workload(2, device=dev)
+    check(wl.G, wl.offsets, "cfg2")
+
+
+def test_bad_arguments(dev):
+    G = torch.zeros((2, 64), device=dev)
+    with pytest.raises(btard.BtardError):
+        btard.partition_hashes(G, [0, 32, 63])                         # offsets must end at d
+    with pytest.raises(btard.BtardError):
+        btard.partition_hashes(G, [0, 64], workspace=torch.empty(256, dtype=torch.uint8, device=dev)[:16])
+    assert btard.hash_workspace_bytes(0, [0, 64]) == 0
