@@ -222,7 +222,7 @@ int blocks_per_partition(int resident, int32_t P, const int64_t *off, int tile_w
     int64_t max_units = 1;
     for (int32_t j = 0; j < P; ++j) {
         const int64_t lo = off[j], hi = off[j + 1];
-        const int64_t units = hi > lo ? (hi - (lo & ~int64_t(kVec - 1)) + tile_w - 1) / tile_w : 0;
+        const int64_t units = hi > lo ? (hi - tile_origin_for(lo, tile_w) + tile_w - 1) / tile_w : 0;
         if (units > max_units) max_units = units;
     }
     int64_t B = resident / P;

@@ -239,7 +239,7 @@ __global__ __launch_bounds__(kBlock, 2) void gram_pass_band_kernel(GramArgs a)
 
     // the workgroup's interior tiles: begin, begin + stride, ... (count of them; the same
     // for its four wavefronts, which meet at a barrier per tile)
-    const int64_t xa = tile_origin(lo);
+    const int64_t xa = tile_origin<B::kW>(lo);
     const int64_t units = (hi > lo) ? (hi - xa + B::kW - 1) / B::kW : 0;
     const int64_t stride = gridDim.x;
     int64_t begin = blockIdx.x, end = units;

@@ -68,9 +68,24 @@ struct Geo {
 };
 
 // Coordinates are tiled from the partition start rounded DOWN to a multiple of
-// 4 in the global numbering, so that a lane's 4 coordinates are always one
-// Philox block (floor(x/4)); coordinates outside [lo, hi) are masked.
-__device__ __forceinline__ int64_t tile_origin(int64_t lo) { return lo & ~int64_t(kVec - 1); }
+// 32 in the global numbering: a lane's 4 coordinates are then always one Philox
+// block (floor(x/4)), and a wavefront's 1 KiB of v starts on a 128-byte boundary
+// when v itself does (whole cache lines are written).  Coordinates outside
+// [lo, hi) are masked.
+// (Tiles narrower than 32 coordinates start at a multiple of their own width: the
+// partition must begin inside tile 0.)
+constexpr int kOriginAlign = 32;
+__host__ __device__ __forceinline__ int64_t tile_origin_for(int64_t lo, int tile_w)
+{
+    const int align = tile_w < kOriginAlign ? tile_w : kOriginAlign;
+    return lo & ~int64_t(align - 1);
+}
+template <int W>
+__device__ __forceinline__ int64_t tile_origin(int64_t lo)
+{
+    static_assert(W >= kVec && (W & (W - 1)) == 0, "tile widths are powers of two");
+    return tile_origin_for(lo, W);
+}
 
 // Which tiles of partition [lo, hi) a wavefront visits.
 struct TileRange {
@@ -84,7 +99,7 @@ template <int W>
 __device__ __forceinline__ TileRange tile_range(int64_t lo, int64_t hi)
 {
     TileRange t;
-    t.xa = tile_origin(lo);
+    t.xa = tile_origin<W>(lo);
     t.units = (hi > lo) ? (hi - t.xa + W - 1) / W : 0;
     t.first = (int64_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     t.stride = (int64_t)gridDim.x * kWaves;

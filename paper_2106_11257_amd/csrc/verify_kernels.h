@@ -340,7 +340,7 @@ __global__ __launch_bounds__(kBlock) void delta_kernel(DeltaArgs a)
 {
     const int j = blockIdx.y;
     const int64_t lo = a.off[j], hi = a.off[j + 1];
-    const int64_t xa = tile_origin(lo);
+    const int64_t xa = tile_origin<kVec>(lo);
     const int64_t units = (hi > lo) ? (hi - xa + kVec - 1) / kVec : 0;
     for (int64_t u = (int64_t)blockIdx.x * kBlock + threadIdx.x; u < units;
          u += (int64_t)gridDim.x * kBlock) {
