@@ -102,9 +102,10 @@ def _mean_rows(G: torch.Tensor, rows: List[int]) -> torch.Tensor:
 
 
 def make_workload(cfg: int, device="cuda", d: Optional[int] = None,
-                  parts: Optional[int] = None) -> Workload:
+                  parts: Optional[int] = None, row_align: int = 32) -> Workload:
     """Builds configuration `cfg` (1..5).  `d` overrides the vector length (for
-    reduced-size test cases with the same recipe); `parts` defaults to n."""
+    reduced-size test cases with the same recipe); `parts` defaults to n; `row_align` is the
+    multiple of floats the row stride of G is rounded up to (1: dense rows)."""
     name, n, d_full, tau, max_iters = _SHAPES[cfg]
     d = d_full if d is None else int(d)
     parts = n if parts is None else int(parts)
@@ -115,7 +116,10 @@ def make_workload(cfg: int, device="cuda", d: Optional[int] = None,
     wl.offsets = split_offsets(d, parts)
     dev = torch.device(device)
     gen = _gen(dev, seed_inputs)
-    G = torch.empty((n, d), dtype=torch.float32, device=dev)
+    # rows start on 128-byte boundaries (row stride = d rounded up to a multiple of row_align
+    # floats): every 1 KiB a wavefront reads of a row is then 8 whole cache lines
+    ld = (d + row_align - 1) // row_align * row_align
+    G = torch.zeros((n, ld), dtype=torch.float32, device=dev)[:, :d]
 
     if cfg == 1:
         # g_i = mu + N(0,1); the last 3 peers send -10 * (their own gradient)
