@@ -34,6 +34,7 @@ struct GramArgs {
     int32_t n;               // <= 16
     const int64_t *off;
     double *gpart;           // [P][B][256] per-workgroup partial Gram matrices
+    int32_t stream_permille; // gram_pass_kernel: share of every partition read with non-temporal loads
 };
 
 // Gamma entry held by register r of lane `lane` in the 16x16x4 fp64 MFMA accumulator: row
@@ -41,17 +42,115 @@ struct GramArgs {
 // matrix is symmetric, so which of the two is "row" is immaterial).
 __device__ __forceinline__ int gram_entry(int lane, int r) { return ((lane >> 4) + 4 * r) * kGramPeers + (lane & 15); }
 
-// Lane (p = lane % 16, q = lane / 16) reads peer p's row.  A tile is 256 coordinates = 16
-// groups of 16; in group s the lane loads coordinates 16 s + 4 q .. + 3 (one 128-bit load)
-// and feeds them, one at a time, to v_mfma_f64_16x16x4_f64 as BOTH operands: in MFMA k-slot
-// q the 16 lanes that share q hold the 16 peers' values of one coordinate, which is what
-// A (16 x 4) and B (4 x 16) of Gamma += X_tile X_tile^T look like.  (Loading row-wise and
-// transposing through LDS, and prefetching the next tile, were tried: the kernel stays at
-// the fp64 MFMA issue rate either way -- measured 105 cycles per instruction -- so the
-// simple form is kept.)
-__global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
+// x of the lane 4 s positions to the left in the same row of 16 lanes, cyclically
+// (DPP row_ror: lane t receives from lane (t - 4 s) mod 16).
+template <int S>
+__device__ __forceinline__ double row_rotate4(double x)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    // (every lane receives a value, so there is no "old" register to preserve)
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)b, 0x120 + 4 * S, 0xf, 0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(b >> 32), 0x120 + 4 * S, 0xf, 0xf, false);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+// 8 < n <= 16.  In the matrix instructions' operands lane (p = lane % 16, q = lane / 16)
+// holds peer p's value of one coordinate: in the 16 coordinates 16 s .. 16 s + 15 of a tile
+// the lane owns 4 q .. 4 q + 3 and feeds them, one at a time, to v_mfma_f64_4x4x4_4b_f64.
+// That instruction multiplies four independent 4 x 4 blocks: block b's first operand is
+// held by lanes 16 k + 4 b + i (row i, k-slot k), its second by lanes 16 k + 4 b + j, and its
+// result D[b][i][j] by lane 16 i + 4 b + j (checked on the device; the tests compare the
+// matrix with a plain product).  With the lane's value as BOTH operands, block b is the
+// 4 x 4 diagonal block of Gamma for peers 4 b .. 4 b + 3; with the second operand rotated by
+// 4 or 8 lanes within the 16, block b pairs peers 4 b .. with peers 4 (b - 1) .. or
+// 4 (b - 2) ..: three instructions per 4 coordinates form the 10 distinct 4 x 4 blocks of the
+// symmetric matrix (and 2 of them twice), 768 multiply-adds where one 16 x 16 x 4
+// instruction spends 1024 -- and the small instruction issues every 17 cycles (75 TFLOP/s
+// over the chip) against 105 for the large one (48 TFLOP/s), so the pass is no longer bound
+// by the matrix unit (measured with the 16 x 16 x 4 form: 143-148 us on the 0.7 GB slab).
+// The slab is read row by row (a wavefront's load instruction covers 1 KiB of one peer's
+// row, the pattern that reaches the highest bandwidth) and turned into the operand layout
+// (16 peers across the lanes) through the wavefront's own LDS area: written row-wise,
+// read back as 16 coordinates x 16 peers.  No barrier is involved.  Rows of the LDS copy
+// are 16 bytes longer than 1 KiB so that the 16 peers' reads fall into different banks.
+constexpr int kGramLdsRow = 256 + 4;                 // floats per LDS row
+
+// `stream` (wavefront-uniform): non-temporal loads, for the part of the slab that will not
+// survive in the memory-side cache until the last pass reads it again anyway.
+template <bool RAGGED>
+__device__ __forceinline__ void gram_fetch_rows(const float *__restrict__ g, int64_t ld, int n, int lane,
+                                                int64_t xu, int64_t lo, int64_t hi, bool interior,
+                                                bool stream, f32x4_u (&v)[16])
+{
+    if (interior) {
+        // one scalar row base walking from peer to peer (rows beyond n re-read the last one)
+        global_bytes row = (global_bytes)(g + xu);
+        const uint32_t lane_bytes = (uint32_t)lane * 16u;
+        if (stream) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                asm volatile("" : "+s"(row));
+                v[r] = __builtin_nontemporal_load((global_f32x4)(row + lane_bytes));
+                if (!RAGGED || r + 1 < n) row += ld * 4;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                asm volatile("" : "+s"(row));
+                v[r] = *(global_f32x4)(row + lane_bytes);
+                if (!RAGGED || r + 1 < n) row += ld * 4;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float *rowp = g + (int64_t)((!RAGGED || r < n) ? r : n - 1) * ld;
+            float t[4];
+            load_row4_guarded(rowp, xu + 4 * lane, lo, hi, t);
+            v[r].x = t[0]; v[r].y = t[1]; v[r].z = t[2]; v[r].w = t[3];
+        }
+    }
+}
+
+// One tile: the wavefront's registers -> its LDS area, row-wise ...
+__device__ __forceinline__ void gram_stage(float (&tile)[16][kGramLdsRow], int lane, const f32x4_u (&rows)[16])
+{
+#pragma unroll
+    for (int r = 0; r < 16; ++r) *reinterpret_cast<f32x4_u *>(&tile[r][4 * lane]) = rows[r];
+}
+
+// ... and read back peer-wise into the matrix instructions.
+template <bool RAGGED>
+__device__ __forceinline__ void gram_multiply(const float (&tile)[16][kGramLdsRow], int p, int q, bool have,
+                                              double (&acc)[3][2])
+{
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+        const f32x4_u t = *reinterpret_cast<const f32x4_u *>(&tile[p][16 * s + 4 * q]);
+        const float val[4] = {t.x, t.y, t.z, t.w};
+        // the operands of the group's 12 instructions first, each in registers of its own
+        double d[4], d1[4], d2[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            d[e] = (double)(RAGGED && !have ? 0.0f : val[e]);
+            d1[e] = row_rotate4<1>(d[e]);
+            d2[e] = row_rotate4<2>(d[e]);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc[0][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(d[e], d[e], acc[0][e & 1], 0, 0, 0);
+            acc[1][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(d[e], d1[e], acc[1][e & 1], 0, 0, 0);
+            acc[2][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(d[e], d2[e], acc[2][e & 1], 0, 0, 0);
+        }
+    }
+}
+
+template <bool RAGGED>
+__global__ __launch_bounds__(kBlock, 2) void gram_pass_kernel(GramArgs a)
 {
     constexpr int kW = 256;
+    __shared__ float tile[kWaves][16][kGramLdsRow];
+    __shared__ double sh[kWaves][kGramEntries];
     const int j = blockIdx.y;
     const int n = a.n;
     const int64_t lo = a.off[j], hi = a.off[j + 1];
@@ -59,49 +158,49 @@ __global__ __launch_bounds__(kBlock) void gram_pass_kernel(GramArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int p = lane & 15, q = lane >> 4;
     const bool have = p < n;
-    global_f32 row = (global_f32)a.g + (int64_t)(have ? p : n - 1) * a.ld;
 
-    // four independent accumulators: consecutive MFMAs do not wait for each other
-    f64x4 acc[4];
+    // [rotation 0, 1, 2][two independent sets: consecutive MFMAs do not wait for each other]
+    double acc[3][2];
 #pragma unroll
-    for (int m = 0; m < 4; ++m) acc[m] = f64x4{0.0, 0.0, 0.0, 0.0};
+    for (int s = 0; s < 3; ++s) { acc[s][0] = 0.0; acc[s][1] = 0.0; }
     const TileRange tr = tile_range<kW>(lo, hi);
+    // the partition's first stream_permille thousandths are read with non-temporal loads
+    const int64_t stream_units = tr.units * a.stream_permille / 1000;
+
+    // One register set: while a tile is multiplied out of LDS, the next one's loads travel.
+    // (Two sets, loaded two tiles ahead, were slower: the pass is not short of requests in
+    // flight.)
+    f32x4_u rows[16];
+    if (tr.first < tr.units) {
+        const int64_t xu = tr.xa + tr.first * kW;
+        gram_fetch_rows<RAGGED>(a.g, a.ld, n, lane, xu, lo, hi, tile_is_interior<kW>(xu, lo, hi),
+                                tr.first < stream_units, rows);
+    }
     for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
-        const int64_t xu = tr.xa + u * kW;
-        const bool interior = (xu >= lo) && (xu + kW <= hi);     // wavefront-uniform
-        float val[16][4];
-        if (interior) {
-            global_f32 p0 = row + xu + 4 * q;
-#pragma unroll
-            for (int s = 0; s < 16; ++s) {
-                const f32x4_u t = *(global_f32x4)(p0 + 16 * s);
-                val[s][0] = t.x; val[s][1] = t.y; val[s][2] = t.z; val[s][3] = t.w;
-            }
-        } else {
-#pragma unroll
-            for (int s = 0; s < 16; ++s) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int64_t x = xu + 16 * s + 4 * q + e;
-                    val[s][e] = (x >= lo && x < hi) ? row[x] : 0.0f;
-                }
-            }
+        gram_stage(tile[wave], lane, rows);
+        const int64_t un = u + tr.stride;
+        if (un < tr.units) {
+            const int64_t xn = tr.xa + un * kW;
+            gram_fetch_rows<RAGGED>(a.g, a.ld, n, lane, xn, lo, hi, tile_is_interior<kW>(xn, lo, hi),
+                                    un < stream_units, rows);
         }
-#pragma unroll
-        for (int s = 0; s < 16; ++s) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const double d = have ? (double)val[s][e] : 0.0;
-                acc[e] = __builtin_amdgcn_mfma_f64_16x16x4f64(d, d, acc[e], 0, 0, 0);
-            }
-        }
+        gram_multiply<RAGGED>(tile[wave], p, q, have, acc);
     }
 
-    // workgroup partial: the 4 wavefronts' matrices added in order
-    __shared__ double sh[kWaves][kGramEntries];
+    // Workgroup partial: the 4 wavefronts' matrices added in order.  Lane 16 i + 4 b + jj holds
+    // entry (4 b + i, 4 ((b - s) mod 4) + jj) of rotation s; rotation 1 forms the blocks
+    // (b, b - 1) only, whose transposes are written as well.
+    {
+        const int i = lane >> 4, b = (lane >> 2) & 3, jj = lane & 3;
+        const int r = 4 * b + i;
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-        sh[wave][gram_entry(lane, r)] = (acc[0][r] + acc[1][r]) + (acc[2][r] + acc[3][r]);
+        for (int s = 0; s < 3; ++s) {
+            const int c = 4 * ((b - s + 4) & 3) + jj;
+            const double x = acc[s][0] + acc[s][1];
+            sh[wave][r * kGramPeers + c] = x;
+            if (s == 1) sh[wave][c * kGramPeers + r] = x;
+        }
+    }
     __syncthreads();
     const int t = threadIdx.x;
     double s = 0.0;
