@@ -68,6 +68,10 @@ __device__ __forceinline__ double row_rotate4(double x)
 // instruction spends 1024 -- and the small instruction issues every 17 cycles (75 TFLOP/s
 // over the chip) against 105 for the large one (48 TFLOP/s), so the pass is no longer bound
 // by the matrix unit (measured with the 16 x 16 x 4 form: 143-148 us on the 0.7 GB slab).
+// Vector and fp64 matrix instructions of a SIMD do not overlap on this chip (a tile's
+// arithmetic takes the sum of the two: 5500 cycles, 3500 of them matrix instructions), and
+// the instruction's operand-broadcast controls are not honoured for fp64; reading the
+// rotated operands from LDS instead of moving them between lanes changed nothing.
 // The slab is read row by row (a wavefront's load instruction covers 1 KiB of one peer's
 // row, the pattern that reaches the highest bandwidth) and turned into the operand layout
 // (16 peers across the lanes) through the wavefront's own LDS area: written row-wise,
