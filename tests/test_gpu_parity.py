@@ -634,6 +634,16 @@ def test_configs_reduced_length(dev, cfg, d):
     check_verify(wl.G, wl.offsets, v, wl.tau, wl.seed_z, want_delta=(cfg in (1, 2)), label=wl.name)
 
 
+@pytest.mark.parametrize("cfg,d", [(2, 400_003), (3, 300_001)])
+def test_configs_with_dense_rows(dev, cfg, d):
+    """The same recipe with row stride = d (rows on 4-byte boundaries only), both paths."""
+    wl = workloads.make_workload(cfg, device=dev, d=d, row_align=1)
+    assert wl.G.stride(0) == d
+    v, iters, sn = check_cc(wl.G, wl.offsets, wl.tau, wl.eps, wl.max_iters, label=wl.name)
+    check_verify(wl.G, wl.offsets, v, wl.tau, wl.seed_z, label=wl.name)
+    check_cc(wl.G, wl.offsets, wl.tau, wl.eps, wl.max_iters, label=wl.name, flags=btard.BTARD_FLAG_GRAM)
+
+
 FULL = [
     # cfg, partitions the oracle recomputes (None = all)
     (1, None),
