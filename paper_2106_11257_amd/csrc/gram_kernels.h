@@ -624,14 +624,57 @@ __device__ __forceinline__ double lane_value_at(double x, int k)
     return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
 }
 
+// Value of lane K of the same row of 16 lanes, for every lane (DPP row_newbcast: no scalar
+// register in between, so no wait states before the value is used).
+template <int K>
+__device__ __forceinline__ double row_value(double x)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)b, 0x150 + K, 0xf, 0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(b >> 32), 0x150 + K, 0xf, 0xf, false);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+template <int K, int N>
+struct RowDot {
+    static __device__ __forceinline__ double run(const double (&row)[N], double x, double y)
+    {
+        return RowDot<K + 1, N>::run(row, x, fma(row[K], row_value<K>(x), y));
+    }
+};
+template <int N>
+struct RowDot<16, N> {
+    static __device__ __forceinline__ double run(const double (&)[N], double, double y) { return y; }
+};
+
+// 1 / sqrt(x) for finite x > 0 to within a few units in the last place: the hardware
+// estimate and two Newton steps (a dozen dependent instructions where a square root
+// followed by a division takes several times as many; the iteration is a chain of
+// dependent instructions in a single wavefront).
+__device__ __forceinline__ double rsqrt_newton(double x)
+{
+    double r = __builtin_amdgcn_rsq(x);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const double e = fma(-x * r, 0.5 * r, 0.5);      // (1 - x r^2) / 2
+        r = fma(r, e, r);
+    }
+    return r;
+}
+
 // sum_k row[k] * (value of x in lane k)
 template <int N>
 __device__ __forceinline__ double row_dot(const double (&row)[N], double x)
 {
-    double y = 0.0;
+    if constexpr (N == 16) {
+        // (the peers are replicated in the four rows of 16 lanes)
+        return RowDot<0, N>::run(row, x, 0.0);
+    } else {
+        double y = 0.0;
 #pragma unroll
-    for (int k = 0; k < N; ++k) y = fma(row[k], lane_value_at(x, k), y);
-    return y;
+        for (int k = 0; k < N; ++k) y = fma(row[k], lane_value_at(x, k), y);
+        return y;
+    }
 }
 
 // Sum over all 64 lanes (one peer per lane): DPP within the rows of 16, then the four row
@@ -761,11 +804,13 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         // norms, weights and how wrong the weights may be
         const double N2 = fmax(diag - 2.0 * y + qv, 0.0);
         const double eN2 = kGramUnit * (rt + Sc) * (rt + Sc);
-        const double Nn = sqrt(N2);
+        // ||g_i - v|| = N2 / sqrt(N2) and tau / ||g_i - v|| from one reciprocal square root
+        const double rs = rsqrt_newton(N2);
+        const double Nn = (N2 > 0.0) ? N2 * rs : N2;              // (0, or NaN as it comes)
         if (__any(peer && !isfinite(Nn))) { it = -1; dn = 1; break; }
         double w = 0.0, err_w = 0.0;
         if (peer) {
-            w = (Nn <= tau) ? 1.0 : tau / Nn;
+            w = (Nn <= tau) ? 1.0 : tau * rs;
             // a weight that is (or may be) tau/N inherits half the relative error of N^2;
             // its contribution to v is w * N <= tau
             if (N2 + eN2 > tau * tau) {
@@ -785,7 +830,7 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         double yn = y + u;
         double Tn2, Sa, Scn, qvn;
         peers_sum4<N>(q, an * u, fabs(an) * rt, fabs(cn) * rt, cn * yn, Tn2, Sa, Scn, qvn);
-        const double T = sqrt(fmax(Tn2, 0.0));
+        const double T = (Tn2 > 0.0) ? Tn2 * rsqrt_newton(Tn2) : 0.0;
         // error budget: the (generously bounded, never discounted) error put into v must
         // stay a small fraction of ||v|| and of the step itself (whose norm is compared
         // with eps below)
