@@ -308,6 +308,19 @@ def main() -> int:
             "traffic": recorded_traffic(dominant, args.config),
             "bytes_per_launch": table[dominant]["algorithmic_bytes"], "launches_per_step": 1,
             "avg_launch_us": table[dominant]["us"]}
+        if dominant == "gram_pass_kernel" and 16 < n <= 64:
+            # 16 < n <= 64: the Gram pass is a dense fp64 contraction bound by the matrix unit:
+            # one 16 x 16 x 4 instruction (2048 flop) per pair of 16-peer groups and 4 coordinates
+            nb = (n + 15) // 16
+            flops = nb * (nb + 1) // 2 * 512.0 * d
+            t_s = kernels[dominant][0] * 1e-3
+            out["roofline"] = {
+                "bound": "mfma", "kernel": dominant, "achieved": round(flops / t_s / 1e12, 2),
+                "peak": 78.6, "unit": "TFLOP/s", "frac": round(flops / t_s / 1e12 / 78.6, 4),
+                "traffic": recorded_traffic(dominant, args.config),
+                "flops_per_launch": flops, "launches_per_step": 1,
+                "avg_launch_us": table[dominant]["us"],
+                "hbm_frac": table[dominant]["frac_of_hbm_peak"]}
         out["config"].update({
             "iters_min": min(it), "iters_max": max(it),
             "mode": "headline: Gram-matrix iteration (streaming fallback), "
