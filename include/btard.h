@@ -370,6 +370,16 @@ int btard_debug_zhat(uint64_t seed, int64_t x_begin, int64_t count, float *out,
  */
 int btard_debug_gram(const btard_cc_problem *p, double *gram_out);
 
+/*
+ * Measurement hook: launches only the first of the two kernels of btard_cc_finish_verify,
+ * the fused last pass over g (v is written; the verification quantities stay behind as
+ * per-workgroup partial sums in the workspace), so that this kernel can be timed by
+ * itself.  Same preconditions as btard_cc_finish_verify, and v0 must be NULL; calling it
+ * again, or btard_cc_finish_verify after it, repeats the same work on the same state.
+ */
+int btard_debug_last_pass(const btard_cc_problem *p, int32_t iterations, float *v,
+                          uint64_t seed);
+
 #ifdef __cplusplus
 }
 #endif

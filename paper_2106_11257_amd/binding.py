@@ -83,6 +83,8 @@ def load_library():
     lib.btard_cc_remaining.restype = c.c_int
     lib.btard_debug_gram.argtypes = [c.POINTER(_Problem), c.c_void_p]
     lib.btard_debug_gram.restype = c.c_int
+    lib.btard_debug_last_pass.argtypes = [c.POINTER(_Problem), c.c_int32, c.c_void_p, c.c_uint64]
+    lib.btard_debug_last_pass.restype = c.c_int
     lib.btard_cc_iterate.argtypes = [c.POINTER(_Problem), c.c_int32, c.c_int32]
     lib.btard_cc_iterate.restype = c.c_int
     lib.btard_cc_finish.argtypes = [c.POINTER(_Problem), c.c_int32, c.c_void_p, c.c_void_p,
@@ -302,6 +304,13 @@ def _verify_outputs(n: int, P: int, dev, out: Optional[dict]) -> dict:
     if "colsum" not in out:
         out["colsum"] = torch.empty(P, dtype=torch.float64, device=dev)
     return out
+
+
+def debug_last_pass(p: Problem, iterations: int, seed: int, v: torch.Tensor) -> None:
+    """btard_debug_last_pass: the fused last pass kernel alone (for timing it)."""
+    _check(load_library().btard_debug_last_pass(ctypes.byref(p.c), int(iterations), _ptr(v),
+                                                int(seed) & 0xFFFFFFFFFFFFFFFF),
+           "btard_debug_last_pass")
 
 
 def cc_finish_verify(p: Problem, iterations: int, seed: int, v: Optional[torch.Tensor] = None,
@@ -531,6 +540,7 @@ btard_cc_gram_matrix = cc_gram_matrix
 btard_cc_gram_iterate = cc_gram_iterate
 btard_cc_remaining = cc_remaining
 btard_debug_gram = debug_gram
+btard_debug_last_pass = debug_last_pass
 btard_cc_iterate = cc_iterate
 btard_cc_finish = cc_finish
 btard_verify_projections = verify_projections

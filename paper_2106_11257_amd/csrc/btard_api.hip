@@ -609,23 +609,10 @@ int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
     return btard_cc_finish(&p, passes, v, iters, last_step_norm);
 }
 
-int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float *v, int32_t *iters,
-                           double *last_step_norm, uint64_t seed, double *norms, double *weights,
-                           double *proj, double *colsum)
+// The fused last pass (cc_finish_verify_kernel) alone; *blocks = its workgroups per partition.
+static int launch_fused_pass(const btard_cc_problem *p, int32_t iterations, float *v,
+                             uint64_t seed, int *blocks)
 {
-    const int rc = check_problem(p);
-    if (rc != BTARD_OK) return rc;
-    if (!v || !iters || iterations < 0 || !norms || !weights || !proj) return BTARD_ERR_INVALID_ARG;
-    if ((p->flags & BTARD_FLAG_GEOMETRIC_MEDIAN) != 0) return BTARD_ERR_INVALID_ARG;
-    if (p->v0) {
-        // with a caller-supplied start vector: the two separate passes
-        const int r1 = btard_cc_finish(p, iterations, v, iters, last_step_norm);
-        if (r1 != BTARD_OK) return r1;
-        return btard_verify_projections(p->g, p->ldg, p->n, p->d, p->offsets_host, p->parts, v,
-                                        p->tau, seed, norms, weights, proj, colsum, nullptr, 0,
-                                        p->workspace, p->workspace_bytes, p->stream,
-                                        BTARD_FLAG_NONE);
-    }
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     const Variant var = pick_variant(p->n);
     const int ragged = p->n < variant_peers(var) ? 1 : 0;
@@ -644,15 +631,50 @@ int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float 
     a.scaled = preclip_on(p) ? 1 : 0;
     a.st = carve_problem(p);
     hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
+    *blocks = B;
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
 
-    const double *part = a.st.partial + (iterations & 1) * a.st.partial_stride;
+int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float *v, int32_t *iters,
+                           double *last_step_norm, uint64_t seed, double *norms, double *weights,
+                           double *proj, double *colsum)
+{
+    const int rc = check_problem(p);
+    if (rc != BTARD_OK) return rc;
+    if (!v || !iters || iterations < 0 || !norms || !weights || !proj) return BTARD_ERR_INVALID_ARG;
+    if ((p->flags & BTARD_FLAG_GEOMETRIC_MEDIAN) != 0) return BTARD_ERR_INVALID_ARG;
+    if (p->v0) {
+        // with a caller-supplied start vector: the two separate passes
+        const int r1 = btard_cc_finish(p, iterations, v, iters, last_step_norm);
+        if (r1 != BTARD_OK) return r1;
+        return btard_verify_projections(p->g, p->ldg, p->n, p->d, p->offsets_host, p->parts, v,
+                                        p->tau, seed, norms, weights, proj, colsum, nullptr, 0,
+                                        p->workspace, p->workspace_bytes, p->stream,
+                                        BTARD_FLAG_NONE);
+    }
+    hipStream_t s = static_cast<hipStream_t>(p->stream);
+    int B = 0;
+    const int r1 = launch_fused_pass(p, iterations, v, seed, &B);
+    if (r1 != BTARD_OK) return r1;
+    const CcState st = carve_problem(p);
     VerifyFinishArgs f;
-    f.partial = part; f.n = p->n; f.P = p->parts; f.B = B; f.S = a.S; f.tau = (double)p->tau;
+    f.partial = st.partial + (iterations & 1) * st.partial_stride;
+    f.n = p->n; f.P = p->parts; f.B = B; f.S = 2 * p->n + 2; f.tau = (double)p->tau;
     f.norms = norms; f.weights = weights; f.proj = proj; f.colsum = colsum;
-    f.report = 1; f.state_iters = a.st.iters; f.report_buf = a.st.report_buf;
+    f.report = 1; f.state_iters = st.iters; f.report_buf = st.report_buf;
     f.iters_out = iters; f.step_norm_out = last_step_norm;
     hipLaunchKernelGGL(verify_finish_kernel, dim3(p->parts), dim3(kFinishThreads), 0, s, f);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
+int btard_debug_last_pass(const btard_cc_problem *p, int32_t iterations, float *v, uint64_t seed)
+{
+    const int rc = check_problem(p);
+    if (rc != BTARD_OK) return rc;
+    if (!v || iterations < 0 || p->v0 || (p->flags & BTARD_FLAG_GEOMETRIC_MEDIAN) != 0)
+        return BTARD_ERR_INVALID_ARG;
+    int B = 0;
+    return launch_fused_pass(p, iterations, v, seed, &B);
 }
 
 int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d,
