@@ -150,6 +150,25 @@ def test_cc_and_verify_small_shapes(dev, n, d, P, pad, outliers):
         check_verify(G, off, v, tv, seed=0xABCDEF0123 + n, want_delta=(d <= 5000))
 
 
+@pytest.mark.parametrize("n,d,P", [(3, 70_001, 5_000), (16, 131_070, 65_535), (40, 9_000, 4_097)])
+def test_many_partitions(dev, n, d, P):
+    """More partitions than the partial-sum area has workgroup slots (one workgroup per
+    partition then), up to the largest count the interface takes; most partitions hold one
+    or two coordinates, some none."""
+    G, off = workloads.generic_case(n, d, P, seed=31 + P, device=dev, spread=0.05, outliers=n // 4)
+    # (the oracle takes a moment per partition: a sample of them when there are very many)
+    sample = None if P <= 5_000 else [0, 1, 2, 4_095, 4_096, 4_097, 30_000, 31_337, P - 2, P - 1]
+    v, iters, sn = check_cc(G, off, 0.5, 1e-6, 12, parts_to_check=sample, label="many partitions")
+    check_verify(G, off, v, 0.5, seed=99, parts_to_check=sample, label="many partitions")
+    if n <= 64:
+        v2, iters2, _ = btard.centered_clip(G, off, 0.5, 1e-6, 12, flags=btard.BTARD_FLAG_GRAM)
+        torch.cuda.synchronize()
+        assert torch.equal(iters2, iters)
+        assert rel_l2(v2.cpu().numpy(), v.cpu().numpy()) <= 1e-6
+    with pytest.raises(btard.BtardError):
+        btard.centered_clip(G[:, :65_536], list(range(65_537)), 0.5, 1e-6, 3)      # one too many
+
+
 def test_cc_with_caller_start_vector_and_zero_iterations(dev):
     G, off = workloads.generic_case(12, 9001, 5, seed=77, device=dev, ld=9003, spread=0.1,
                                     outliers=3)
