@@ -4,12 +4,14 @@
 // values of its 4 coordinates for the NP peers of its lane group.
 //   one lane group (n <= 16): a sorting network in registers (Batcher's odd-even merge sort,
 //     v_min_f32 / v_max_f32 pairs); absent peers are +inf and sort to the end;
-//   several lane groups (n <= 255): the values of a coordinate are spread over LG lanes, so
-//     the k-th smallest is found bit by bit on order-preserving integer keys: for each of
-//     the 32 bits, count the keys below the candidate prefix (a count per lane, summed over
-//     the lane groups with the 4 coordinates' counts packed into one 32-bit word) and keep
-//     the bit if the count does not exceed k.  This variant is bound by the integer ALU
-//     (about 40 instructions per bit and coordinate), not by HBM.
+//   several lane groups (n <= 255): the values of a coordinate are spread over LG lanes.
+//     Every lane sorts its 16 values with the same network, then the lanes' runs are merged
+//     pairwise by bitonic merges whose exchanges across lanes are wavefront shuffles (one
+//     shuffle and one v_med3_f32 per value and exchange); the middle ranks are then read
+//     from the lane and register they have come to rest in.  About 350 instructions per
+//     coordinate at n = 64 (a rank selection bit by bit on integer keys, the first form of
+//     this variant, took about 1300): closer to, but still above, the time of reading the
+//     rows.
 #pragma once
 
 #include "kernels_common.h"
@@ -23,19 +25,6 @@ struct MedianArgs {
     int64_t d;
     float *v;
 };
-
-// order-preserving map of IEEE-754 binary32 to unsigned integers
-__device__ __forceinline__ uint32_t float_key(float x)
-{
-    const uint32_t b = __float_as_uint(x);
-    return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
-}
-
-__device__ __forceinline__ float key_float(uint32_t k)
-{
-    const uint32_t b = k ^ ((k >> 31) ? 0x80000000u : 0xFFFFFFFFu);
-    return __uint_as_float(b);
-}
 
 // Batcher's odd-even merge sort of N = 2^m values (ascending), fully unrolled.
 template <int N>
@@ -95,52 +84,101 @@ __global__ __launch_bounds__(kBlock) void coordinate_median_kernel(MedianArgs a)
                 med[e] = (float)(0.5 * ((double)m0 + (double)m1));
             }
         } else {
-            uint32_t key[NP][4];
-#pragma unroll
-            for (int k = 0; k < NP; ++k) {
-                const bool have = !RAGGED || lg * NP + k < n;
-#pragma unroll
-                for (int e = 0; e < kVec; ++e) key[k][e] = have ? float_key(val[k][e]) : 0xFFFFFFFFu;
-            }
-            // the key of rank klo of each of the 4 coordinates
-            uint32_t prefix[4] = {0u, 0u, 0u, 0u};
-#pragma unroll 1
-            for (int bit = 31; bit >= 0; --bit) {
-                uint32_t packed = 0;
-#pragma unroll
-                for (int e = 0; e < kVec; ++e) {
-                    const uint32_t cand = prefix[e] | (1u << bit);
-                    uint32_t cnt = 0;
-#pragma unroll
-                    for (int k = 0; k < NP; ++k) cnt += key[k][e] < cand ? 1u : 0u;
-                    packed |= cnt << (8 * e);
-                }
-                // counts of all lane groups (each field stays below 256: n <= 255)
-#pragma unroll
-                for (int m = G::kLanes; m < 64; m <<= 1) packed += (uint32_t)__shfl_xor((int)packed, m, 64);
-#pragma unroll
-                for (int e = 0; e < kVec; ++e) {
-                    const uint32_t below = (packed >> (8 * e)) & 0xFFu;
-                    if (below <= (uint32_t)klo) prefix[e] |= (1u << bit);
-                }
-            }
-            // rank khi: the same value if enough keys are <= it, else the smallest key above
+            static_assert(NP == 16, "the merge steps below are written for 16 values per lane");
+            // Every lane sorts its 16 values; then runs of 1, 2, 4, .. lane groups are merged
+            // pairwise (bitonic merge: the first exchange pairs rank r of the lower run with
+            // rank 2R - 1 - r of the upper one, the following ones are half-cleaners at
+            // distances R/2 .. 1 lane groups and 8 .. 1 elements).  Afterwards rank r of a
+            // coordinate is element r % 16 of lane group r / 16.
 #pragma unroll
             for (int e = 0; e < kVec; ++e) {
-                uint32_t le = 0, next = 0xFFFFFFFFu;
+                float col[NP];
 #pragma unroll
-                for (int k = 0; k < NP; ++k) {
-                    le += key[k][e] <= prefix[e] ? 1u : 0u;
-                    if (key[k][e] > prefix[e] && key[k][e] < next) next = key[k][e];
-                }
+                for (int k = 0; k < NP; ++k)
+                    col[k] = (!RAGGED || lg * NP + k < n) ? val[k][e] : INFINITY;
+                sort_network<NP>(col);
 #pragma unroll
-                for (int m = G::kLanes; m < 64; m <<= 1) {
-                    le += (uint32_t)__shfl_xor((int)le, m, 64);
-                    const uint32_t other = (uint32_t)__shfl_xor((int)next, m, 64);
-                    next = other < next ? other : next;
+                for (int k = 0; k < NP; ++k) val[k][e] = col[k];
+            }
+#pragma unroll
+            for (int R = 1; R < LG; R <<= 1) {
+                // the first exchange, with the mirrored lane group and the mirrored element
+                {
+                    const int mask = (2 * R - 1) * G::kLanes;
+                    // median of (a, b, -inf) is min(a, b), of (a, b, +inf) max(a, b)
+                    const float keep = (lg & R) ? INFINITY : -INFINITY;
+#pragma unroll
+                    for (int e = 0; e < kVec; ++e) {
+                        float other[NP];
+#pragma unroll
+                        for (int k = 0; k < NP; ++k) other[k] = __shfl_xor(val[NP - 1 - k][e], mask, 64);
+#pragma unroll
+                        for (int k = 0; k < NP; ++k)
+                            val[k][e] = __builtin_amdgcn_fmed3f(val[k][e], other[k], keep);
+                    }
                 }
-                const uint32_t upper = (le > (uint32_t)khi) ? prefix[e] : next;
-                med[e] = (float)(0.5 * ((double)key_float(prefix[e]) + (double)key_float(upper)));
+                if (!RAGGED && 2 * R == LG) break;     // (the last merge is finished below)
+                // half-cleaners across lane groups
+#pragma unroll
+                for (int s2 = R >> 1; s2 >= 1; s2 >>= 1) {
+                    const int mask = s2 * G::kLanes;
+                    const float keep = (lg & s2) ? INFINITY : -INFINITY;
+#pragma unroll
+                    for (int e = 0; e < kVec; ++e)
+#pragma unroll
+                        for (int k = 0; k < NP; ++k) {
+                            const float other = __shfl_xor(val[k][e], mask, 64);
+                            val[k][e] = __builtin_amdgcn_fmed3f(val[k][e], other, keep);
+                        }
+                }
+                // and within the lane
+#pragma unroll
+                for (int e = 0; e < kVec; ++e)
+#pragma unroll
+                    for (int s2 = NP / 2; s2 >= 1; s2 >>= 1)
+#pragma unroll
+                        for (int k = 0; k < NP; ++k)
+                            if ((k & s2) == 0) {
+                                const float lo2 = fminf(val[k][e], val[k + s2][e]);
+                                const float hi2 = fmaxf(val[k][e], val[k + s2][e]);
+                                val[k][e] = lo2;
+                                val[k + s2][e] = hi2;
+                            }
+            }
+            if constexpr (!RAGGED) {
+                // n = 16 LG: after the first exchange of the last merge the lower half of the
+                // lane groups holds the n / 2 smallest values, and the two middle ranks are
+                // the largest of those and the smallest of the others; the halves need not
+                // be sorted any further.
+                const float keep = (lg & (LG / 2)) ? -INFINITY : INFINITY;    // max below, min above
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) {
+                    float t = val[0][e];
+#pragma unroll
+                    for (int k = 1; k < NP; ++k) t = __builtin_amdgcn_fmed3f(t, val[k][e], keep);
+#pragma unroll
+                    for (int s2 = LG / 4; s2 >= 1; s2 >>= 1)
+                        t = __builtin_amdgcn_fmed3f(t, __shfl_xor(t, s2 * G::kLanes, 64), keep);
+                    const float m0 = __shfl(t, sub, 64);
+                    const float m1 = __shfl(t, (LG / 2) * G::kLanes + sub, 64);
+                    med[e] = (float)(0.5 * ((double)m0 + (double)m1));
+                }
+            } else {
+            // the two middle ranks (wavefront-uniform): element, then lane group
+            const int elo = klo % NP, ehi = khi % NP;
+            const int src_lo = (klo / NP) * G::kLanes + sub, src_hi = (khi / NP) * G::kLanes + sub;
+#pragma unroll
+            for (int e = 0; e < kVec; ++e) {
+                float m0 = val[0][e], m1 = val[0][e];
+#pragma unroll
+                for (int k = 1; k < NP; ++k) {
+                    if (k == elo) m0 = val[k][e];
+                    if (k == ehi) m1 = val[k][e];
+                }
+                m0 = __shfl(m0, src_lo, 64);
+                m1 = __shfl(m1, src_hi, 64);
+                med[e] = (float)(0.5 * ((double)m0 + (double)m1));
+            }
             }
         }
         if (lg == 0) {
