@@ -108,7 +108,8 @@ template <int NP, int LG, bool INTERIOR>
 __device__ __forceinline__ void project_rows(float *__restrict__ v, uint64_t seed, int lg, int sub,
                                              int64_t xu, int64_t lo, int64_t hi,
                                              float (&val)[NP][4], const double (&c)[NP],
-                                             double (&accR)[NP], double &zv, double &z2)
+                                             double (&accR)[NP], double &zv, double &z2,
+                                             TileStage *stage = nullptr, int64_t u_tile = 0)
 {
     const int64_t x0 = xu + (int64_t)sub * kVec;
     float zf[4];
@@ -140,7 +141,9 @@ __device__ __forceinline__ void project_rows(float *__restrict__ v, uint64_t see
         if (INTERIOR) {
             f32x4_u o;
             o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
-            stream_store(v + x0, o);
+            // (one lane group when staged: sub is the lane, x0 = xa + u W + 4 lane)
+            if (stage) stage->put(u_tile, sub, o);
+            else stream_store(v + x0, o);
         } else {
 #pragma unroll
             for (int e = 0; e < kVec; ++e) {
@@ -159,7 +162,8 @@ __device__ __forceinline__ void project_rows(float *__restrict__ v, uint64_t see
 template <int NP, int LG, bool RAGGED>
 __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, double *s_c,
                                                   double *s_a,
-                                                  double (&sh)[kWaves][2 * NP * LG + 2])
+                                                  double (&sh)[kWaves][2 * NP * LG + 2],
+                                                  f32x4_u *stage_area)
 {
     using G = Geo<NP, LG>;
     const int n = a.n, S = a.S, R = a.st.R;
@@ -201,26 +205,31 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
         float va[NP][4], vb[NP][4];
         int64_t u = iw.begin;
         bool last_in_b = false;
-        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u * G::kW, lo, hi, true, va);
+        TileStage stage;
+        stage.template begin<G::kW>(stage_area, wave, a.v, tr.xa, tr.stride);
+        uint32_t lane_off = (uint32_t)sub * (uint32_t)(kVec * sizeof(float));
+        load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u * G::kW, lane_off, va);
         for (;;) {
+            stage.template flush_if_due<G::kW>(lane, 3);     // (two tiles per round, one after the loop)
             const int64_t u1 = u + tr.stride;
             if (u1 >= iw.end) break;                 // the last tile is in va
-            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u1 * G::kW, lo, hi, true, vb);
-            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
+            load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u1 * G::kW, lane_off, vb);
+            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2, &stage, u);
             const int64_t u2 = u1 + tr.stride;
             if (u2 >= iw.end) {                      // the last tile is in vb
                 u = u1;
                 last_in_b = true;
                 break;
             }
-            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u2 * G::kW, lo, hi, true, va);
-            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, accR, zv, z2);
+            load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u2 * G::kW, lane_off, va);
+            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, accR, zv, z2, &stage, u1);
             u = u2;
         }
         if (last_in_b)
-            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, vb, c, accR, zv, z2);
+            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, vb, c, accR, zv, z2, &stage, u);
         else
-            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2);
+            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2, &stage, u);
+        stage.template flush<G::kW>(lane);
     }
     // ... then the partition's first and last tile where they are not interior
 #pragma unroll 1
@@ -276,13 +285,15 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
     __shared__ double s_c[kBlock], s_a[kBlock], s_red[kBlock];
     __shared__ int s_flags[2];
     __shared__ double sh[kWaves][2 * G::kPeers + 2];
+    // (tiles of v parked before they are written; with one lane group only)
+    __shared__ f32x4_u s_stage[LG == 1 ? kStageSlots : 1];
 
     const int j = blockIdx.y;
     const int n = a.n, S = a.S;
     if constexpr (LG <= 4) {
         // (the Gram formulation serves n <= 64: up to four lane groups)
         if (a.use_gram_norms && a.st.gram_ok[j]) {   // uniform
-            project_partition<NP, LG, RAGGED>(a, j, s_c, s_a, sh);
+            project_partition<NP, LG, RAGGED>(a, j, s_c, s_a, sh, s_stage);
             return;
         }
     }

@@ -259,6 +259,90 @@ __device__ __forceinline__ void load_tile(const float *__restrict__ g, int64_t l
     }
 }
 
+// Interior tile with one lane group, for loops that keep the lane's byte offset in one
+// register for their whole life (lane_off = 16 * sub, handed back unchanged): every load is
+// scalar row base + that 32-bit offset.  The offset is re-declared opaque before each load so
+// that it is neither widened to 64 bits nor copied; a register that lives as long as the
+// loop is never reused for loaded data, so nothing at the head of the loop has to wait for
+// loads still in flight.
+template <int NP, bool RAGGED>
+__device__ __forceinline__ void load_tile_interior(const float *__restrict__ g, int64_t ld, int n,
+                                                   int64_t xu, uint32_t &lane_off,
+                                                   float (&val)[NP][4])
+{
+    global_bytes row = (global_bytes)(g + xu);
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        asm volatile("" : "+s"(row), "+v"(lane_off));
+        const f32x4_u t = stream_load((global_f32x4)(row + lane_off));
+        if (!RAGGED || k + 1 < n) row += ld * 4;
+        val[k][0] = t.x; val[k][1] = t.y; val[k][2] = t.z; val[k][3] = t.w;
+    }
+}
+
+// Writes of v in bursts.  A few stores sprinkled into a stream of loads cost several times
+// their share of the bytes (the memory turns around between reading and writing for every
+// handful of them): a pass that writes 4 bytes per coordinate next to 64 read took 30 %
+// longer than the same pass without the store.  So a wavefront parks the tiles of v it
+// produces in its own LDS area and writes them out together -- when the area is full and,
+// which is what keeps the bursts of all wavefronts of the device together however long the
+// pass runs, whenever the real-time counter that all of them read (s_memrealtime, 100 MHz)
+// enters a new epoch.  What is written and where does not depend on the clock, only when.
+constexpr int kStageTiles = 16;              // 16 KiB per wavefront, 64 KiB per workgroup
+constexpr uint32_t kEpochTicks = 6000;       // 60 us
+constexpr int kStageSlots = kWaves * kStageTiles * 64;
+
+struct TileStage {
+    // wavefront-uniform state (scalar registers); the lane's addresses are formed when used
+    f32x4_u *area;        // this wavefront's kStageTiles x 64 slots
+    float *base;          // v + the first coordinate of the wavefront's tile 0 (tile u: + u W)
+    int64_t first;        // index u of the oldest staged tile; the others follow at `stride`
+    int64_t stride;
+    int count;
+    uint32_t epoch;
+
+    // W: coordinates per tile
+    template <int W>
+    __device__ __forceinline__ void begin(f32x4_u *block_area, int wave, float *v, int64_t xa,
+                                          int64_t tile_stride)
+    {
+        area = block_area + wave * (kStageTiles * 64);
+        base = v + xa;
+        first = 0;
+        stride = tile_stride;
+        count = 0;
+        epoch = (uint32_t)__builtin_amdgcn_s_memrealtime() / kEpochTicks;
+    }
+
+    template <int W>
+    __device__ __forceinline__ void flush(int lane)
+    {
+#pragma unroll 1
+        for (int t = 0; t < count; ++t)
+            stream_store(base + (first + t * stride) * W + lane * kVec, area[t * 64 + lane]);
+        count = 0;
+    }
+
+    // the lane's 4 values of interior tile u; consecutive calls are `stride` tiles apart.
+    // The caller makes room first (flush_if_due) at a point of its loop of its choosing.
+    __device__ __forceinline__ void put(int64_t u, int lane, f32x4_u o)
+    {
+        if (count == 0) first = u;
+        area[count * 64 + lane] = o;
+        ++count;
+    }
+
+    // to be called at least once per `room` calls of put: writes the staged tiles out if fewer
+    // than `room` more would fit, or if the clock has entered a new epoch
+    template <int W>
+    __device__ __forceinline__ void flush_if_due(int lane, int room)
+    {
+        const uint32_t now = (uint32_t)__builtin_amdgcn_s_memrealtime() / kEpochTicks;
+        if (count + room > kStageTiles || now != epoch) flush<W>(lane);
+        epoch = now;
+    }
+};
+
 // Makes the compiler forget what it knows about a register value (no instruction is
 // emitted).  Used between the two sweeps over a tile so that the fp32 values are
 // converted to fp64 again in the second sweep instead of keeping 2x the registers live.
