@@ -438,7 +438,8 @@ __device__ __forceinline__ void finish_tile(const float *__restrict__ g, int64_t
                                             const float *__restrict__ v0, float *__restrict__ v,
                                             int lg, int sub, int64_t xu, int64_t lo, int64_t hi,
                                             const double (&c)[NP], const double (&dl)[NP],
-                                            double cb, double db, double &t2)
+                                            double cb, double db, double &t2,
+                                            TileStage *stage = nullptr, int64_t u_tile = 0)
 {
     const int64_t x0 = xu + (int64_t)sub * kVec;
     float val[NP][4];
@@ -460,7 +461,8 @@ __device__ __forceinline__ void finish_tile(const float *__restrict__ g, int64_t
         if (INTERIOR) {
             f32x4_u o;
             o.x = (float)vv[0]; o.y = (float)vv[1]; o.z = (float)vv[2]; o.w = (float)vv[3];
-            stream_store(v + x0, o);
+            if (stage) stage->put(u_tile, sub, o);        // (one lane group when staged)
+            else stream_store(v + x0, o);
         } else {
 #pragma unroll
             for (int e = 0; e < kVec; ++e) {
@@ -480,6 +482,8 @@ __global__ __launch_bounds__(kBlock, 3) void cc_finish_kernel(CcFinishArgs a)
     __shared__ double s_c[kBlock], s_a[kBlock], s_red[kBlock];
     __shared__ int s_flags[2];
     __shared__ double sh[kWaves];
+    // (tiles of v parked before they are written in bursts; with one lane group only)
+    __shared__ f32x4_u s_stage[LG == 1 ? kStageSlots : 1];
 
     const int j = blockIdx.y;
     const int n = a.n;
@@ -519,9 +523,16 @@ __global__ __launch_bounds__(kBlock, 3) void cc_finish_kernel(CcFinishArgs a)
     // common one no registers
     const TileRange tr = tile_range<G::kW>(lo, hi);
     const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
-    for (int64_t u = iw.begin; u < iw.end; u += tr.stride)
+    TileStage stage;
+    TileStage *const staged = (LG == 1) ? &stage : nullptr;
+    stage.template begin<G::kW>(s_stage, wave, a.v, tr.xa, tr.stride);
+    for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
+        if constexpr (LG == 1) stage.template flush_if_due<G::kW>(lane, 1);
         finish_tile<NP, LG, RAGGED, HAS_BASE, true>(a.g, a.ld, n, a.v0, a.v, lg, sub,
-                                                    tr.xa + u * G::kW, lo, hi, c, dl, cb, db, t2);
+                                                    tr.xa + u * G::kW, lo, hi, c, dl, cb, db, t2,
+                                                    staged, u);
+    }
+    if constexpr (LG == 1) stage.template flush<G::kW>(lane);
 #pragma unroll 1
     for (int t = 0; t < 2; ++t) {
         const int64_t u = (t == 0) ? 0 : tr.units - 1;

@@ -35,7 +35,7 @@ __device__ __forceinline__ void fused_rows(float *__restrict__ v, uint64_t seed,
                                            const double (&c)[NP], const double (&dl)[NP],
                                            const double (&al)[NP],
                                            double (&accN)[NP], double (&accR)[NP], double &t2,
-                                           double &z2)
+                                           double &z2, TileStage *stage = nullptr, int64_t u_tile = 0)
 {
     const int64_t x0 = xu + (int64_t)sub * kVec;
     // nothing below moves ahead of loads issued before this call (the next tile's)
@@ -56,7 +56,8 @@ __device__ __forceinline__ void fused_rows(float *__restrict__ v, uint64_t seed,
         if (INTERIOR) {
             f32x4_u o;
             o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
-            stream_store(v + x0, o);
+            if (stage) stage->put(u_tile, sub, o);        // (one lane group when staged)
+            else stream_store(v + x0, o);
         } else {
 #pragma unroll
             for (int e = 0; e < kVec; ++e) {
@@ -335,43 +336,53 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
     // the factors do, and a second register set does not fit: one set then.)
     const TileRange tr = tile_range<G::kW>(lo, hi);
     const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
+    // (v is staged where the registers allow it: with 16 peers per lane this body has none
+    // to spare for it)
+    constexpr bool kStaged = LG == 1 && NP <= 8;
+    TileStage stage;
+    TileStage *const staged = kStaged ? &stage : nullptr;
+    stage.template begin<G::kW>(s_stage, wave, a.v, tr.xa, tr.stride);
     if constexpr (LG > 1 || SCALED) {
         for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
+            if constexpr (kStaged) stage.template flush_if_due<G::kW>(lane, 1);
             const int64_t xu = tr.xa + u * G::kW;
             float val[NP][4];
             load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, true, val);
             fused_rows<NP, LG, true, SCALED>(a.v, a.seed, lg, sub, xu, lo, hi, val, c, dl, al, accN, accR, t2,
-                                     z2);
+                                     z2, staged, u);
         }
     } else if (iw.begin < iw.end) {
         float va[NP][4], vb[NP][4];
         int64_t u = iw.begin;
         bool last_in_b = false;
-        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u * G::kW, lo, hi, true, va);
+        uint32_t lane_off = (uint32_t)sub * (uint32_t)(kVec * sizeof(float));
+        load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u * G::kW, lane_off, va);
         for (;;) {
+            if constexpr (kStaged) stage.template flush_if_due<G::kW>(lane, 3);   // (two tiles per round, one after)
             const int64_t u1 = u + tr.stride;
             if (u1 >= iw.end) break;                 // the last tile is in va
-            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u1 * G::kW, lo, hi, true, vb);
+            load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u1 * G::kW, lane_off, vb);
             fused_rows<NP, LG, true, SCALED>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, dl, al,
-                                     accN, accR, t2, z2);
+                                     accN, accR, t2, z2, staged, u);
             const int64_t u2 = u1 + tr.stride;
             if (u2 >= iw.end) {                      // the last tile is in vb
                 u = u1;
                 last_in_b = true;
                 break;
             }
-            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u2 * G::kW, lo, hi, true, va);
+            load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u2 * G::kW, lane_off, va);
             fused_rows<NP, LG, true, SCALED>(a.v, a.seed, lg, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, dl, al,
-                                     accN, accR, t2, z2);
+                                     accN, accR, t2, z2, staged, u1);
             u = u2;
         }
         if (last_in_b)
             fused_rows<NP, LG, true, SCALED>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, vb, c, dl, al,
-                                     accN, accR, t2, z2);
+                                     accN, accR, t2, z2, staged, u);
         else
             fused_rows<NP, LG, true, SCALED>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, dl, al,
-                                     accN, accR, t2, z2);
+                                     accN, accR, t2, z2, staged, u);
     }
+    if constexpr (kStaged) stage.template flush<G::kW>(lane);
     sum_within_group_all<G::kLanes, NP>(accN);
     sum_within_group_all<G::kLanes, NP>(accR);
     z2 = sum_within_group<G::kLanes>(z2);
