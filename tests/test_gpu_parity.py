@@ -169,6 +169,39 @@ def test_many_partitions(dev, n, d, P):
         btard.centered_clip(G[:, :65_536], list(range(65_537)), 0.5, 1e-6, 3)      # one too many
 
 
+@pytest.mark.parametrize("n,d,P", [(4, 12_600_011, 2), (16, 8_400_019, 1), (8, 10_000_003, 3)])
+def test_many_tiles_per_wavefront(dev, n, d, P):
+    """Long partitions: every wavefront walks more tiles than its staging area for v holds,
+    so v is written in several bursts (when the area fills and when the clock epoch turns).
+    All three kernels that stage v, element by element against the oracle."""
+    G, off = workloads.generic_case(n, d, P, seed=41 + n, device=dev, ld=d + 3, spread=0.05,
+                                    outliers=n // 4)
+    Gh = G.cpu().numpy()
+    # the per-iteration passes and cc_finish_kernel
+    v, iters, sn = btard.centered_clip(G, off, 0.7, 0.0, 2)
+    torch.cuda.synchronize()
+    vo, ito, sno, _ = oracle.centered_clip(Gh, off, 0.7, 0.0, 2)
+    np.testing.assert_array_equal(iters.cpu().numpy(), ito)
+    vh = v.cpu().numpy()
+    assert rel_l2(vh, vo) <= V_TOL
+    assert np.abs(vh - vo).max() <= 1e-5 * np.abs(vo).max()          # no tile missing or misplaced
+    # Gram path: the fused last pass (light body)
+    v2, iters2, sn2, out2 = btard.centered_clip_verify(G, off, 0.7, 0.0, 2, 5,
+                                                       flags=btard.BTARD_FLAG_GRAM)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(iters2.cpu().numpy(), ito)
+    v2h = v2.cpu().numpy()
+    assert rel_l2(v2h, vo) <= V_TOL
+    assert np.abs(v2h - vo).max() <= 1e-5 * np.abs(vo).max()
+    ref = oracle.verify(Gh, off, v2h.astype(np.float64), 0.7, 5)
+    assert rel_l2(out2["proj"].cpu().numpy(), ref["proj"]) <= PROJ_TOL
+    # coordinate-wise median
+    m = btard.coordinate_median(G)
+    torch.cuda.synchronize()
+    want = oracle.coordinate_median(Gh).astype(np.float32)
+    assert np.array_equal(m.cpu().numpy(), want)
+
+
 def test_cc_with_caller_start_vector_and_zero_iterations(dev):
     G, off = workloads.generic_case(12, 9001, 5, seed=77, device=dev, ld=9003, spread=0.1,
                                     outliers=3)
