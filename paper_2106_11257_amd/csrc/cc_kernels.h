@@ -461,7 +461,7 @@ __device__ __forceinline__ void finish_tile(const float *__restrict__ g, int64_t
         if (INTERIOR) {
             f32x4_u o;
             o.x = (float)vv[0]; o.y = (float)vv[1]; o.z = (float)vv[2]; o.w = (float)vv[3];
-            if (stage) stage->put(u_tile, sub, o);        // (one lane group when staged)
+            if (stage) stage->template put<64>(u_tile, sub, o);   // (one lane group when staged)
             else stream_store(v + x0, o);
         } else {
 #pragma unroll
@@ -525,14 +525,14 @@ __global__ __launch_bounds__(kBlock, 3) void cc_finish_kernel(CcFinishArgs a)
     const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
     TileStage stage;
     TileStage *const staged = (LG == 1) ? &stage : nullptr;
-    stage.template begin<G::kW>(s_stage, wave, a.v, tr.xa, tr.stride);
+    stage.begin(s_stage, wave, a.v, tr.xa, tr.stride);
     for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
-        if constexpr (LG == 1) stage.template flush_if_due<G::kW>(lane, 1);
+        if constexpr (LG == 1) stage.template flush_if_due<64>(lane, 1);
         finish_tile<NP, LG, RAGGED, HAS_BASE, true>(a.g, a.ld, n, a.v0, a.v, lg, sub,
                                                     tr.xa + u * G::kW, lo, hi, c, dl, cb, db, t2,
                                                     staged, u);
     }
-    if constexpr (LG == 1) stage.template flush<G::kW>(lane);
+    if constexpr (LG == 1) stage.template flush<64>(lane);
 #pragma unroll 1
     for (int t = 0; t < 2; ++t) {
         const int64_t u = (t == 0) ? 0 : tr.units - 1;

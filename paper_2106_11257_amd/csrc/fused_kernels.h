@@ -56,7 +56,7 @@ __device__ __forceinline__ void fused_rows(float *__restrict__ v, uint64_t seed,
         if (INTERIOR) {
             f32x4_u o;
             o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
-            if (stage) stage->put(u_tile, sub, o);        // (one lane group when staged)
+            if (stage) stage->template put<64>(u_tile, sub, o);   // (one lane group when staged)
             else stream_store(v + x0, o);
         } else {
 #pragma unroll
@@ -138,13 +138,19 @@ __device__ __forceinline__ void project_rows(float *__restrict__ v, uint64_t see
         vv[e] = sum_across_groups<Geo<NP, LG>::kLanes>(vv[e]);   // (nothing to do with one group)
         vf[e] = (float)vv[e];
     }
+    if (INTERIOR && stage) {
+        // (every lane holds the sums; those of lane group 0 keep them for the burst)
+        f32x4_u o;
+        o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
+        stage->template put<Geo<NP, LG>::kLanes>(u_tile, sub, o, lg == 0);
+    }
     if (lg == 0) {
         if (INTERIOR) {
-            f32x4_u o;
-            o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
-            // (one lane group when staged: sub is the lane, x0 = xa + u W + 4 lane)
-            if (stage) stage->put(u_tile, sub, o);
-            else stream_store(v + x0, o);
+            if (!stage) {
+                f32x4_u o;
+                o.x = vf[0]; o.y = vf[1]; o.z = vf[2]; o.w = vf[3];
+                stream_store(v + x0, o);
+            }
         } else {
 #pragma unroll
             for (int e = 0; e < kVec; ++e) {
@@ -195,23 +201,24 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
     // with several lane groups, whose coefficients take vector registers) ...
     const TileRange tr = tile_range<G::kW>(lo, hi);
     const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
+    TileStage stage;
+    stage.begin(stage_area, wave, a.v, tr.xa, tr.stride);
     if constexpr (LG > 1) {
         for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
+            stage.template flush_if_due<G::kLanes>(sub, 1, lg == 0);
             const int64_t xu = tr.xa + u * G::kW;
             float val[NP][4];
             load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, true, val);
-            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, xu, lo, hi, val, c, accR, zv, z2);
+            project_rows<NP, LG, true>(a.v, a.seed, lg, sub, xu, lo, hi, val, c, accR, zv, z2, &stage, u);
         }
     } else if (iw.begin < iw.end) {
         float va[NP][4], vb[NP][4];
         int64_t u = iw.begin;
         bool last_in_b = false;
-        TileStage stage;
-        stage.template begin<G::kW>(stage_area, wave, a.v, tr.xa, tr.stride);
         uint32_t lane_off = (uint32_t)sub * (uint32_t)(kVec * sizeof(float));
         load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u * G::kW, lane_off, va);
         for (;;) {
-            stage.template flush_if_due<G::kW>(lane, 3);     // (two tiles per round, one after the loop)
+            stage.template flush_if_due<64>(lane, 3);        // (two tiles per round, one after the loop)
             const int64_t u1 = u + tr.stride;
             if (u1 >= iw.end) break;                 // the last tile is in va
             load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u1 * G::kW, lane_off, vb);
@@ -230,8 +237,8 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
             project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, vb, c, accR, zv, z2, &stage, u);
         else
             project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, accR, zv, z2, &stage, u);
-        stage.template flush<G::kW>(lane);
     }
+    stage.template flush<G::kLanes>(sub, lg == 0);
     // ... then the partition's first and last tile where they are not interior
 #pragma unroll 1
     for (int t = 0; t < 2; ++t) {
@@ -286,8 +293,8 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
     __shared__ double s_c[kBlock], s_a[kBlock], s_red[kBlock];
     __shared__ int s_flags[2];
     __shared__ double sh[kWaves][2 * G::kPeers + 2];
-    // (tiles of v parked before they are written; with one lane group only)
-    __shared__ f32x4_u s_stage[LG == 1 ? kStageSlots : 1];
+    // (tiles of v parked before they are written in bursts)
+    __shared__ f32x4_u s_stage[LG <= 4 ? kStageSlots : 1];
 
     const int j = blockIdx.y;
     const int n = a.n, S = a.S;
@@ -341,10 +348,10 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
     constexpr bool kStaged = LG == 1 && NP <= 8;
     TileStage stage;
     TileStage *const staged = kStaged ? &stage : nullptr;
-    stage.template begin<G::kW>(s_stage, wave, a.v, tr.xa, tr.stride);
+    stage.begin(s_stage, wave, a.v, tr.xa, tr.stride);
     if constexpr (LG > 1 || SCALED) {
         for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
-            if constexpr (kStaged) stage.template flush_if_due<G::kW>(lane, 1);
+            if constexpr (kStaged) stage.template flush_if_due<64>(lane, 1);
             const int64_t xu = tr.xa + u * G::kW;
             float val[NP][4];
             load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, true, val);
@@ -358,7 +365,7 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
         uint32_t lane_off = (uint32_t)sub * (uint32_t)(kVec * sizeof(float));
         load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u * G::kW, lane_off, va);
         for (;;) {
-            if constexpr (kStaged) stage.template flush_if_due<G::kW>(lane, 3);   // (two tiles per round, one after)
+            if constexpr (kStaged) stage.template flush_if_due<64>(lane, 3);   // (two tiles per round, one after)
             const int64_t u1 = u + tr.stride;
             if (u1 >= iw.end) break;                 // the last tile is in va
             load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u1 * G::kW, lane_off, vb);
@@ -382,7 +389,7 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
             fused_rows<NP, LG, true, SCALED>(a.v, a.seed, lg, sub, tr.xa + u * G::kW, lo, hi, va, c, dl, al,
                                      accN, accR, t2, z2, staged, u);
     }
-    if constexpr (kStaged) stage.template flush<G::kW>(lane);
+    if constexpr (kStaged) stage.template flush<64>(lane);
     sum_within_group_all<G::kLanes, NP>(accN);
     sum_within_group_all<G::kLanes, NP>(accR);
     z2 = sum_within_group<G::kLanes>(z2);

@@ -301,8 +301,11 @@ struct TileStage {
     int count;
     uint32_t epoch;
 
-    // W: coordinates per tile
-    template <int W>
+    // LANES: lanes that hold a tile of v (those of lane group 0), 4 coordinates each; the
+    // area then takes 64 / LANES x kStageTiles tiles
+    template <int LANES>
+    static constexpr int capacity() { return kStageTiles * (64 / LANES); }
+
     __device__ __forceinline__ void begin(f32x4_u *block_area, int wave, float *v, int64_t xa,
                                           int64_t tile_stride)
     {
@@ -314,31 +317,37 @@ struct TileStage {
         epoch = (uint32_t)__builtin_amdgcn_s_memrealtime() / kEpochTicks;
     }
 
-    template <int W>
-    __device__ __forceinline__ void flush(int lane)
+    // (sub: the lane's index in its lane group; holds: it belongs to lane group 0)
+    template <int LANES>
+    __device__ __forceinline__ void flush(int sub, bool holds = true)
     {
+        if (holds) {
 #pragma unroll 1
-        for (int t = 0; t < count; ++t)
-            stream_store(base + (first + t * stride) * W + lane * kVec, area[t * 64 + lane]);
+            for (int t = 0; t < count; ++t)
+                stream_store(base + (first + t * stride) * (LANES * kVec) + sub * kVec,
+                             area[t * LANES + sub]);
+        }
         count = 0;
     }
 
-    // the lane's 4 values of interior tile u; consecutive calls are `stride` tiles apart.
-    // The caller makes room first (flush_if_due) at a point of its loop of its choosing.
-    __device__ __forceinline__ void put(int64_t u, int lane, f32x4_u o)
+    // The 4 values of interior tile u; to be called by the whole wavefront, consecutive calls
+    // `stride` tiles apart.  The caller makes room first (flush_if_due) at a point of its
+    // loop of its choosing.
+    template <int LANES>
+    __device__ __forceinline__ void put(int64_t u, int sub, f32x4_u o, bool holds = true)
     {
         if (count == 0) first = u;
-        area[count * 64 + lane] = o;
+        if (holds) area[count * LANES + sub] = o;
         ++count;
     }
 
     // to be called at least once per `room` calls of put: writes the staged tiles out if fewer
     // than `room` more would fit, or if the clock has entered a new epoch
-    template <int W>
-    __device__ __forceinline__ void flush_if_due(int lane, int room)
+    template <int LANES>
+    __device__ __forceinline__ void flush_if_due(int sub, int room, bool holds = true)
     {
         const uint32_t now = (uint32_t)__builtin_amdgcn_s_memrealtime() / kEpochTicks;
-        if (count + room > kStageTiles || now != epoch) flush<W>(lane);
+        if (count + room > capacity<LANES>() || now != epoch) flush<LANES>(sub, holds);
         epoch = now;
     }
 };

@@ -64,11 +64,10 @@ __global__ __launch_bounds__(kBlock) void coordinate_median_kernel(MedianArgs a)
     // (with one lane group the interior tiles of v are parked in LDS and written in bursts)
     __shared__ f32x4_u s_stage[LG == 1 ? kStageSlots : 1];
     TileStage stage;
-    stage.template begin<G::kW>(s_stage, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), a.v, tr.xa,
-                                tr.stride);
+    stage.begin(s_stage, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), a.v, tr.xa, tr.stride);
     int64_t staged_next = -1;                           // the tile that would continue the staged run
     for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
-        if constexpr (LG == 1) stage.template flush_if_due<G::kW>(lane, 1);
+        if constexpr (LG == 1) stage.template flush_if_due<64>(lane, 1);
         const int64_t xu = tr.xa + u * G::kW;
         const bool interior = tile_is_interior<G::kW>(xu, lo, hi);
         const int64_t x0 = xu + (int64_t)sub * kVec;
@@ -194,8 +193,8 @@ __global__ __launch_bounds__(kBlock) void coordinate_median_kernel(MedianArgs a)
                 o.x = med[0]; o.y = med[1]; o.z = med[2]; o.w = med[3];
                 if constexpr (LG == 1) {
                     // (the staged tiles must be `stride` apart: an edge tile in between ends the run)
-                    if (stage.count > 0 && u != staged_next) stage.template flush<G::kW>(lane);
-                    stage.put(u, lane, o);
+                    if (stage.count > 0 && u != staged_next) stage.template flush<64>(lane);
+                    stage.template put<64>(u, lane, o);
                     staged_next = u + tr.stride;
                 } else {
                     stream_store(a.v + x0, o);
@@ -209,7 +208,7 @@ __global__ __launch_bounds__(kBlock) void coordinate_median_kernel(MedianArgs a)
             }
         }
     }
-    if constexpr (LG == 1) stage.template flush<G::kW>(lane);
+    if constexpr (LG == 1) stage.template flush<64>(lane);
 }
 
 }  // namespace btard
