@@ -457,12 +457,19 @@ __device__ __forceinline__ void finish_tile(const float *__restrict__ g, int64_t
     }
     double vv[4], ss[4];
     combine_rows<NP, LG, HAS_BASE>(val, base, c, dl, cb, db, vv, ss);
+    if (INTERIOR && stage) {
+        // (every lane holds the sums; those of lane group 0 keep them for the burst)
+        f32x4_u o;
+        o.x = (float)vv[0]; o.y = (float)vv[1]; o.z = (float)vv[2]; o.w = (float)vv[3];
+        stage->template put<Geo<NP, LG>::kLanes>(u_tile, sub, o, lg == 0);
+    }
     if (lg == 0) {
         if (INTERIOR) {
-            f32x4_u o;
-            o.x = (float)vv[0]; o.y = (float)vv[1]; o.z = (float)vv[2]; o.w = (float)vv[3];
-            if (stage) stage->template put<64>(u_tile, sub, o);   // (one lane group when staged)
-            else stream_store(v + x0, o);
+            if (!stage) {
+                f32x4_u o;
+                o.x = (float)vv[0]; o.y = (float)vv[1]; o.z = (float)vv[2]; o.w = (float)vv[3];
+                stream_store(v + x0, o);
+            }
         } else {
 #pragma unroll
             for (int e = 0; e < kVec; ++e) {
@@ -482,8 +489,8 @@ __global__ __launch_bounds__(kBlock, 3) void cc_finish_kernel(CcFinishArgs a)
     __shared__ double s_c[kBlock], s_a[kBlock], s_red[kBlock];
     __shared__ int s_flags[2];
     __shared__ double sh[kWaves];
-    // (tiles of v parked before they are written in bursts; with one lane group only)
-    __shared__ f32x4_u s_stage[LG == 1 ? kStageSlots : 1];
+    // (tiles of v parked before they are written in bursts; up to four lane groups)
+    __shared__ f32x4_u s_stage[LG <= 4 ? kStageSlots : 1];
 
     const int j = blockIdx.y;
     const int n = a.n;
@@ -523,16 +530,17 @@ __global__ __launch_bounds__(kBlock, 3) void cc_finish_kernel(CcFinishArgs a)
     // common one no registers
     const TileRange tr = tile_range<G::kW>(lo, hi);
     const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
+    constexpr bool kStaged = LG <= 4;
     TileStage stage;
-    TileStage *const staged = (LG == 1) ? &stage : nullptr;
+    TileStage *const staged = kStaged ? &stage : nullptr;
     stage.begin(s_stage, wave, a.v, tr.xa, tr.stride);
     for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
-        if constexpr (LG == 1) stage.template flush_if_due<64>(lane, 1);
+        if constexpr (kStaged) stage.template flush_if_due<G::kLanes>(sub, 1, lg == 0);
         finish_tile<NP, LG, RAGGED, HAS_BASE, true>(a.g, a.ld, n, a.v0, a.v, lg, sub,
                                                     tr.xa + u * G::kW, lo, hi, c, dl, cb, db, t2,
                                                     staged, u);
     }
-    if constexpr (LG == 1) stage.template flush<64>(lane);
+    if constexpr (kStaged) stage.template flush<G::kLanes>(sub, lg == 0);
 #pragma unroll 1
     for (int t = 0; t < 2; ++t) {
         const int64_t u = (t == 0) ? 0 : tr.units - 1;
