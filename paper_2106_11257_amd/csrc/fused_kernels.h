@@ -218,7 +218,7 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
         uint32_t lane_off = (uint32_t)sub * (uint32_t)(kVec * sizeof(float));
         load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u * G::kW, lane_off, va);
         for (;;) {
-            stage.template flush_if_due<64>(lane, 3);        // (two tiles per round, one after the loop)
+            stage.template flush_if_due<64>(lane, 2);        // (one tile until the next check, one after the loop)
             const int64_t u1 = u + tr.stride;
             if (u1 >= iw.end) break;                 // the last tile is in va
             load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u1 * G::kW, lane_off, vb);
@@ -229,6 +229,7 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
                 last_in_b = true;
                 break;
             }
+            stage.template flush_if_due<64>(lane, 2);
             load_tile_interior<NP, RAGGED>(a.g, a.ld, n, tr.xa + u2 * G::kW, lane_off, va);
             project_rows<NP, LG, true>(a.v, a.seed, lg, sub, tr.xa + u1 * G::kW, lo, hi, vb, c, accR, zv, z2, &stage, u1);
             u = u2;
