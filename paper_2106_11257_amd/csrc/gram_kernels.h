@@ -734,9 +734,16 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
 {
     static_assert(N == 16 || N == 64, "one 16 x 16 block or 4 x 4 of them");
     __shared__ double G[N][N + 1];
+    // (the radii of a tau_l schedule, read once: a load from memory in every iteration would
+    // put its latency into the chain of dependent instructions)
+    __shared__ double s_tau[kMaxSchedule];
     const int j = blockIdx.x;
     const int t = threadIdx.x;
     const int n = a.n, R = a.st.R;
+    if (a.st.has_sched) {                                    // uniform
+        const int count = a.max_iters < kMaxSchedule ? a.max_iters : kMaxSchedule;
+        for (int e = t; e < count; e += kBlock) s_tau[e] = a.st.tau_sched[e];
+    }
 
     // Gamma = sum of the workgroups' partial matrices, in order
     if constexpr (N == 16) {
@@ -805,7 +812,7 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
 
     while (!dn) {                             // wavefront-uniform
         // (tau_l of eq. (5) if the caller gave a schedule)
-        const double tau = (a.st.has_sched && it < kMaxSchedule) ? a.st.tau_sched[it] : a.tau;
+        const double tau = (a.st.has_sched && it < kMaxSchedule) ? s_tau[it] : a.tau;
         // norms, weights and how wrong the weights may be
         const double N2 = fmax(diag - 2.0 * y + qv, 0.0);
         const double eN2 = kGramUnit * (rt + Sc) * (rt + Sc);
