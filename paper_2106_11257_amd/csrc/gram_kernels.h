@@ -748,9 +748,19 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
     // Gamma = sum of the workgroups' partial matrices, in order
     if constexpr (N == 16) {
         const double *pj = a.gpart + (int64_t)j * a.blocks * kGramEntries;
+        // (32 loads in flight at a time, added in order: otherwise the sum is a chain of
+        // memory latencies)
         double s = 0.0;
+        int b = 0;
+        for (; b + 32 <= a.blocks; b += 32) {
+            double x[32];
+#pragma unroll
+            for (int k = 0; k < 32; ++k) x[k] = pj[(int64_t)(b + k) * kGramEntries + t];
+#pragma unroll
+            for (int k = 0; k < 32; ++k) s += x[k];
+        }
 #pragma unroll 8
-        for (int b = 0; b < a.blocks; ++b) s += pj[(int64_t)b * kGramEntries + t];
+        for (; b < a.blocks; ++b) s += pj[(int64_t)b * kGramEntries + t];
         G[t / N][t % N] = s;
     } else {
         const double *pj = a.gpart + (int64_t)j * a.blocks * kWideEntries;
