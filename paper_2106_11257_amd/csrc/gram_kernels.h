@@ -764,18 +764,34 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         G[t / N][t % N] = s;
     } else {
         const double *pj = a.gpart + (int64_t)j * a.blocks * kWideEntries;
-        for (int e = t; e < N * N; e += kBlock) {
-            const int I = e / N, K = e % N;
-            const int bI = I >> 4, bK = K >> 4;
-            double s = 0.0;
-            if (bI < a.nb && bK < a.nb) {
+        // (four entries per thread at a time, so that 16 loads are in flight, each entry's
+        // partial sums added in order)
+        for (int e0 = t; e0 < N * N; e0 += 4 * kBlock) {
+            int src[4];
+            bool stored[4];
+            double s[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int e = e0 + q * kBlock;
+                const int I = e / N, K = e % N;
+                const int bI = I >> 4, bK = K >> 4;
+                stored[q] = bI < a.nb && bK < a.nb;
                 // stored on and above the diagonal of blocks; below it, the transpose
-                const int src = (bI <= bK) ? wide_pair(bI, bK) * kGramEntries + (I & 15) * 16 + (K & 15)
-                                           : wide_pair(bK, bI) * kGramEntries + (K & 15) * 16 + (I & 15);
-#pragma unroll 4
-                for (int b = 0; b < a.blocks; ++b) s += pj[(int64_t)b * kWideEntries + src];
+                src[q] = !stored[q] ? 0
+                         : (bI <= bK) ? wide_pair(bI, bK) * kGramEntries + (I & 15) * 16 + (K & 15)
+                                      : wide_pair(bK, bI) * kGramEntries + (K & 15) * 16 + (I & 15);
+                s[q] = 0.0;
             }
-            G[I][K] = s;
+#pragma unroll 4
+            for (int b = 0; b < a.blocks; ++b) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) s[q] += pj[(int64_t)b * kWideEntries + src[q]];
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int e = e0 + q * kBlock;
+                G[e / N][e % N] = stored[q] ? s[q] : 0.0;
+            }
         }
     }
     __syncthreads();
