@@ -66,6 +66,13 @@ typedef enum btard_status {
  * CenteredClip.  Not with BTARD_FLAG_GRAM (ignored), tau_schedule or
  * btard_cc_finish_verify (there are no clipped residuals to verify). */
 #define BTARD_FLAG_GEOMETRIC_MEDIAN 4u
+/* Phased interface with BTARD_FLAG_GRAM: the caller leaves out btard_cc_begin, and
+ * btard_cc_gram_matrix / btard_cc_gram_iterate do its work (the partition offsets travel as a
+ * kernel argument, the Gram iteration starts from the mean by itself): one kernel launch
+ * less.  Where that is not possible (no Gram formulation for this problem, more than 255
+ * partitions, a tau_schedule) btard_cc_gram_matrix calls btard_cc_begin itself.  The one-call
+ * entry points do this on their own. */
+#define BTARD_FLAG_GRAM_BEGINS 8u
 
 /* Human-readable name of a status code (static storage). */
 const char *btard_status_string(int status);

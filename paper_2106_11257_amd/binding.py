@@ -22,6 +22,7 @@ BTARD_FLAG_NONE = 0
 BTARD_FLAG_GRAM = 1
 BTARD_FLAG_HOST_SYNC = 2
 BTARD_FLAG_GEOMETRIC_MEDIAN = 4
+BTARD_FLAG_GRAM_BEGINS = 8
 
 
 class BtardError(RuntimeError):

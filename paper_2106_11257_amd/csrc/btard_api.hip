@@ -278,7 +278,7 @@ int check_problem(const btard_cc_problem *p)
         return BTARD_ERR_INVALID_ARG;
     if (!(p->tau > 0.0f) || !(p->eps >= 0.0f) || p->max_iters < 0) return BTARD_ERR_INVALID_ARG;
     if ((p->flags & ~(uint32_t)(BTARD_FLAG_GRAM | BTARD_FLAG_HOST_SYNC |
-                                BTARD_FLAG_GEOMETRIC_MEDIAN)) != 0)
+                                BTARD_FLAG_GEOMETRIC_MEDIAN | BTARD_FLAG_GRAM_BEGINS)) != 0)
         return BTARD_ERR_INVALID_ARG;
     if ((p->flags & BTARD_FLAG_GEOMETRIC_MEDIAN) != 0 && p->tau_schedule) return BTARD_ERR_INVALID_ARG;
     if (p->tau_schedule) {
@@ -386,6 +386,15 @@ static bool gram_applies(const btard_cc_problem *p)
            p->n <= kGramMaxPeers && p->v0 == nullptr && p->max_iters > 0;
 }
 
+// With BTARD_FLAG_GRAM_BEGINS the two Gram kernels also do what cc_begin_kernel does (the
+// offsets travel as a kernel argument): possible when the Gram formulation runs at all, the
+// offsets fit one argument block and no schedule of radii has to be uploaded.
+static bool gram_begins(const btard_cc_problem *p)
+{
+    return (p->flags & BTARD_FLAG_GRAM_BEGINS) != 0 && gram_applies(p) &&
+           p->parts + 1 <= kOffChunk && p->tau_schedule == nullptr;
+}
+
 // n <= 8: two coordinates per MFMA row block (512-wide tiles); n <= 16: one block (256-wide);
 // n <= 64: ceil(n / 16) blocks of peers, the block pairs on and above the diagonal (64-wide)
 typedef void (*GramFn)(GramArgs);
@@ -427,6 +436,11 @@ int btard_cc_gram_matrix(const btard_cc_problem *p)
 {
     const int rc = check_problem(p);
     if (rc != BTARD_OK) return rc;
+    if ((p->flags & BTARD_FLAG_GRAM_BEGINS) != 0 && !gram_begins(p)) {
+        // the caller left btard_cc_begin to this call, and the kernels cannot take it over
+        const int rb = btard_cc_begin(p);
+        if (rb != BTARD_OK) return rb;
+    }
     if (!gram_applies(p)) return BTARD_OK;               // nothing to do: streaming passes only
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     const int B = gram_blocks(p);
@@ -436,6 +450,11 @@ int btard_cc_gram_matrix(const btard_cc_problem *p)
     ga.g = p->g; ga.ld = p->ldg; ga.n = p->n;
     ga.stream_permille = gram_stream_permille(p);
     ga.off = carve_problem(p).off;
+    ga.from_args = gram_begins(p) ? 1 : 0;
+    ga.parts = p->parts;
+    ga.off_out = const_cast<int64_t *>(ga.off);
+    for (int32_t t = 0; t < kOffChunk; ++t)
+        ga.chunk.v[t] = (ga.from_args && t <= p->parts) ? p->offsets_host[t] : 0;
     ga.gpart = reinterpret_cast<double *>(static_cast<char *>(p->workspace) + L.gram);
     hipLaunchKernelGGL(gram_kernel(p), dim3(B, p->parts), dim3(kBlock), 0, s, ga);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
@@ -457,6 +476,7 @@ int btard_cc_gram_iterate(const btard_cc_problem *p)
     gi.tau = (double)p->tau; gi.eps = (double)p->eps; gi.max_iters = p->max_iters;
     gi.lambda = preclip_on(p) ? (double)p->preclip : 0.0;
     gi.nb = gram_peer_blocks(p);
+    gi.fresh = gram_begins(p) ? 1 : 0;
     if (p->n <= kGramPeers)
         hipLaunchKernelGGL(gram_iterate_kernel<16>, dim3(p->parts), dim3(kBlock), 0, s, gi);
     else
@@ -505,6 +525,7 @@ int btard_debug_gram(const btard_cc_problem *p, double *gram_out)
     GramArgs ga;
     ga.g = p->g; ga.ld = p->ldg; ga.n = p->n; ga.off = st.off;
     ga.stream_permille = gram_stream_permille(p);
+    ga.from_args = 0; ga.parts = p->parts; ga.off_out = nullptr;
     ga.gpart = reinterpret_cast<double *>(static_cast<char *>(p->workspace) + L.gram);
     hipLaunchKernelGGL(gram_kernel(p), dim3(B, p->parts), dim3(kBlock), 0, s, ga);
     if (p->n <= kGramPeers)
@@ -593,8 +614,8 @@ int btard_centered_clip(const float *g, int64_t ldg, int32_t n, int64_t d,
     int rc = check_problem(&p);
     if (rc != BTARD_OK) return rc;
     if (!v || !iters || overlaps(v, v0, d)) return BTARD_ERR_INVALID_ARG;
-    rc = btard_cc_begin(&p);
-    if (rc != BTARD_OK) return rc;
+    // (btard_cc_begin's work: done by the Gram kernels where they can, else by the call below)
+    p.flags |= BTARD_FLAG_GRAM_BEGINS;
     rc = btard_cc_gram(&p);
     if (rc != BTARD_OK) return rc;
     int32_t passes = max_iters;
@@ -693,8 +714,8 @@ int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d
     if (rc != BTARD_OK) return rc;
     if (!v || !iters || overlaps(v, v0, d) || !norms || !weights || !proj)
         return BTARD_ERR_INVALID_ARG;
-    rc = btard_cc_begin(&p);
-    if (rc != BTARD_OK) return rc;
+    // (btard_cc_begin's work: done by the Gram kernels where they can, else by the call below)
+    p.flags |= BTARD_FLAG_GRAM_BEGINS;
     rc = btard_cc_gram(&p);
     if (rc != BTARD_OK) return rc;
     int32_t passes = max_iters;
@@ -931,8 +952,8 @@ int btard_centered_clip_verify_preclipped(const float *g, int64_t ldg, int32_t n
     int rc = check_problem(&p);
     if (rc != BTARD_OK) return rc;
     if (!v || !iters || !norms || !weights || !proj) return BTARD_ERR_INVALID_ARG;
-    rc = btard_cc_begin(&p);
-    if (rc != BTARD_OK) return rc;
+    // (btard_cc_begin's work: done by the Gram kernels where they can, else by the call below)
+    p.flags |= BTARD_FLAG_GRAM_BEGINS;
     rc = btard_cc_gram(&p);
     if (rc != BTARD_OK) return rc;
     int32_t passes = max_iters;

@@ -35,7 +35,27 @@ struct GramArgs {
     const int64_t *off;
     double *gpart;           // [P][B][256] per-workgroup partial Gram matrices
     int32_t stream_permille; // gram_pass_kernel: share of every partition read with non-temporal loads
+    // The Gram pass as the first kernel of a call sequence (no cc_begin_kernel before it): the
+    // partition offsets come as an argument and workgroup (0, 0) stores them for the
+    // kernels that follow.
+    int32_t from_args;       // 0: read off[]; 1: read chunk, store it to off_out
+    int32_t parts;
+    int64_t *off_out;
+    OffChunk chunk;
 };
+
+__device__ __forceinline__ void gram_partition_range(const GramArgs &a, int j, int64_t &lo, int64_t &hi)
+{
+    if (a.from_args) {                                   // uniform
+        lo = a.chunk.v[j];
+        hi = a.chunk.v[j + 1];
+        if (blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x <= a.parts)
+            a.off_out[threadIdx.x] = a.chunk.v[threadIdx.x];
+    } else {
+        lo = a.off[j];
+        hi = a.off[j + 1];
+    }
+}
 
 // Gamma entry held by register r of lane `lane` in the 16x16x4 fp64 MFMA accumulator: row
 // lane/16 + 4 r, column lane % 16 (checked against a plain matrix product by the tests; the
@@ -157,7 +177,8 @@ __global__ __launch_bounds__(kBlock, 2) void gram_pass_kernel(GramArgs a)
     __shared__ double sh[kWaves][kGramEntries];
     const int j = blockIdx.y;
     const int n = a.n;
-    const int64_t lo = a.off[j], hi = a.off[j + 1];
+    int64_t lo, hi;
+    gram_partition_range(a, j, lo, hi);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int p = lane & 15, q = lane >> 4;
@@ -315,7 +336,8 @@ __global__ __launch_bounds__(kBlock, 2) void gram_pass_band_kernel(GramArgs a)
     __shared__ double sh[kGramEntries];
     const int j = blockIdx.y;
     const int n = a.n;
-    const int64_t lo = a.off[j], hi = a.off[j + 1];
+    int64_t lo, hi;
+    gram_partition_range(a, j, lo, hi);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     sh[threadIdx.x] = 0.0;                           // entries nobody forms (NP < 16) stay 0
@@ -448,7 +470,8 @@ __global__ __launch_bounds__(kBlock) void gram_pass_wide_kernel(GramArgs a)
     __shared__ double sh[kPairs * kGramEntries];
     const int j = blockIdx.y;
     const int n = a.n;
-    const int64_t lo = a.off[j], hi = a.off[j + 1];
+    int64_t lo, hi;
+    gram_partition_range(a, j, lo, hi);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int p = lane & 15, q = lane >> 4;
@@ -546,6 +569,7 @@ struct GramIterArgs {
     int32_t max_iters;
     double lambda;           // pre-clipping radius (BTARD-Clipped-SGD); <= 0: none
     int32_t nb;              // wide layout only: blocks of 16 peers that were formed
+    int32_t fresh;           // 1: no cc_begin_kernel ran: start from c = 1/n and set up what it would have
 };
 
 // Relative accuracy assumed for a Gram entry and for a quadratic form in it, in units of
@@ -823,10 +847,10 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
     const double inv_n = 1.0 / (double)n;
 
     const int q = t >> 4;                     // which of the four rows of 16 lanes
-    double c = peer ? a.st.coef[(int64_t)j * R + i] : 0.0;
+    double c = peer ? (a.fresh ? inv_n : a.st.coef[(int64_t)j * R + i]) : 0.0;
     double al = 0.0;
-    int it = a.st.iters[j];
-    int dn = a.st.done[j];
+    int it = a.fresh ? 0 : a.st.iters[j];
+    int dn = a.fresh ? 0 : a.st.done[j];
     double ev = 0.0;                          // bound on the error put into v so far
 
     // y = Gamma c, qv = c^T Gamma c and Sc = sum_i |c_i| ||g_i|| travel with c: after an
@@ -921,6 +945,14 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         a.st.coef[(int64_t)j * R + t] = c;
         a.st.delta[(int64_t)j * R + t] = al;
         a.st.gram_n2[(int64_t)j * R + t] = N2f;
+    }
+    if (a.fresh) {
+        // what cc_begin_kernel would have set and nothing above writes
+        if (t < n && !(a.lambda > 0.0)) a.st.scale[(int64_t)j * R + t] = 1.0;
+        if (t == 0) {
+            a.st.scale[(int64_t)j * R + n] = 1.0;
+            a.st.report_buf[j] = 0;
+        }
     }
     if (t == 0) {
         a.st.coef[(int64_t)j * R + n] = 0.0;      // the start vector's slot

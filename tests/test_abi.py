@@ -87,7 +87,7 @@ def test_argument_errors_are_caught_on_the_host_before_any_gpu_call():
     assert cc(o=(ctypes.c_int64 * 3)(1, 4, 8)) == -1
     assert cc(tau=0.0) == -1 and cc(tau=float("nan")) == -1
     assert cc(eps=-1.0) == -1 and cc(m=-1) == -1
-    assert cc(flags=8) == -1 and cc(flags=15) == -1
+    assert cc(flags=16) == -1 and cc(flags=31) == -1
     assert cc(wsp=None) == -2
     assert cc(wsp=ctypes.c_void_p(0x10001)) == -2      # misaligned
     assert cc(wsb=16) == -2

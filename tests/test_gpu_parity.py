@@ -647,6 +647,47 @@ def test_headline_step_replayed_as_a_hip_graph(dev):
             assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("n,d,P,lam", [(16, 300_007, 16, 0.0), (7, 40_003, 5, 0.0), (40, 90_001, 4, 0.0),
+                                         (16, 70_001, 255, 0.0), (9, 50_000, 300, 0.0),
+                                         (16, 300_007, 16, 1.5)])
+def test_gram_kernels_doing_the_work_of_cc_begin(dev, n, d, P, lam):
+    """BTARD_FLAG_GRAM_BEGINS: without a call of btard_cc_begin the phased calls must give,
+    bit for bit, what they give after one -- also where the Gram iteration hands partitions
+    over to the passes, with pre-clipping, on a workspace that holds another problem's state,
+    and (more than 255 partitions) where btard_cc_gram_matrix has to call btard_cc_begin."""
+    G, off = workloads.generic_case(n, d, P, seed=600 + n + P, device=dev, ld=d + 5, spread=0.05,
+                                    outliers=n // 4)
+    tau, eps, M, seed = 0.6, 1e-7, 40, 123
+    if lam > 0.0:
+        lam = lam * float(G.norm(dim=1).median()) / math.sqrt(P)
+    ws = btard.alloc_workspace(n, P, dev)
+
+    def run(flags, begin):
+        # (another problem's state in the workspace first)
+        btard.centered_clip(G, off, 2.0 * tau, eps, 3, workspace=ws)
+        prob = btard.make_problem(G, off, tau, eps, M, workspace=ws, flags=flags, preclip=lam)
+        if begin:
+            btard.cc_begin(prob)
+        btard.cc_gram_matrix(prob)
+        btard.cc_gram_iterate(prob)
+        left = btard.cc_remaining(prob)
+        btard.cc_iterate(prob, 0, left)
+        v, it, sn, out = btard.cc_finish_verify(prob, left, seed)
+        torch.cuda.synchronize()
+        return left, v, it, sn, out
+
+    want = run(btard.BTARD_FLAG_GRAM, True)
+    got = run(btard.BTARD_FLAG_GRAM | btard.BTARD_FLAG_GRAM_BEGINS, False)
+    assert got[0] == want[0]
+    for a, b in zip(got[1:4], want[1:4]):
+        assert torch.equal(a, b)
+    for k in want[4]:
+        assert torch.equal(got[4][k], want[4][k]), k
+    # and the one-call entry point (which sets the flag itself) against the oracle
+    if lam == 0.0:
+        check_cc(G, off, tau, eps, M, label="one call", flags=btard.BTARD_FLAG_GRAM)
+
+
 def test_verifications_1_and_2_flags(dev):
     G, off = workloads.generic_case(9, 4000, 6, seed=78, device=dev, spread=0.05, outliers=3,
                                     outlier_scale=3.0)
