@@ -406,9 +406,9 @@ static GramFn gram_kernel(const btard_cc_problem *p)
     if (p->n < kGramPeers) return gram_pass_kernel<true>;
     if (p->n == kGramPeers) return gram_pass_kernel<false>;
     switch (gram_peer_blocks(p)) {
-        case 2: return gram_pass_wide_kernel<2>;
-        case 3: return gram_pass_wide_kernel<3>;
-        default: return gram_pass_wide_kernel<4>;
+        case 2: return p->n < 32 ? gram_pass_wide_kernel<2, true> : gram_pass_wide_kernel<2, false>;
+        case 3: return p->n < 48 ? gram_pass_wide_kernel<3, true> : gram_pass_wide_kernel<3, false>;
+        default: return p->n < 64 ? gram_pass_wide_kernel<4, true> : gram_pass_wide_kernel<4, false>;
     }
 }
 

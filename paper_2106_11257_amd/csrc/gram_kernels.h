@@ -462,8 +462,9 @@ constexpr int kWidePairs = kWideBlocks * (kWideBlocks + 1) / 2;    // 10
 constexpr int kWideEntries = kWidePairs * kGramEntries;
 __host__ __device__ constexpr int wide_pair(int b, int c) { return b * kWideBlocks - b * (b - 1) / 2 + (c - b); }
 
-template <int NB>
-__global__ __launch_bounds__(kBlock) void gram_pass_wide_kernel(GramArgs a)
+// RAGGED: n < 16 NB (rows beyond n are read from row n - 1 and replaced by zero).
+template <int NB, bool RAGGED>
+__global__ __launch_bounds__(kBlock, 2) void gram_pass_wide_kernel(GramArgs a)
 {
     constexpr int kW = 64;
     constexpr int kPairs = NB * (NB + 1) / 2;
@@ -519,7 +520,7 @@ __global__ __launch_bounds__(kBlock) void gram_pass_wide_kernel(GramArgs a)
             for (int e = 0; e < 4; ++e) {
                 double d[NB];
 #pragma unroll
-                for (int b = 0; b < NB; ++b) d[b] = have[b] ? (double)val[b][s][e] : 0.0;
+                for (int b = 0; b < NB; ++b) d[b] = (RAGGED && !have[b]) ? 0.0 : (double)val[b][s][e];
                 int t = 0;
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
