@@ -214,6 +214,18 @@ int resident_blocks(const void *fn)
     return slot;
 }
 
+// Epoch of the write bursts of v (TileStage): about three quarters of the time in which a
+// wavefront fills its staging area, when `waves` wavefronts share ~6.5 TB/s and each tile
+// costs tile_bytes of traffic; between 10 and 80 us.  Returned as 2^32 / ticks (100 MHz).
+uint32_t stage_epoch_multiplier(int64_t waves, double tile_bytes, int capacity_tiles)
+{
+    const double tile_us = (double)waves * tile_bytes / 6.5e6;            // bytes / (6.5e12 B/s) in us
+    double us = 0.75 * (double)capacity_tiles * tile_us;
+    if (us < 10.0) us = 10.0;
+    if (us > 80.0) us = 80.0;
+    return epoch_multiplier((uint32_t)(us * 100.0));
+}
+
 // Workgroups per partition: fill the device once (all partitions run side by side; the
 // pass gains bandwidth up to full occupancy), but never more than the partial-sum area
 // holds or the work needs.
@@ -591,6 +603,13 @@ int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int
     a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
     a.pass = iterations; a.prev_blocks = Bpass; a.scaled = preclip_on(p) ? 1 : 0;
     a.rule = rule_of(p);
+    {
+        // (a tile: the n rows' and v's 4 bytes per coordinate; tiles staged: see TileStage)
+        const int W = variant_tile_width(var);
+        a.epoch_mult = stage_epoch_multiplier((int64_t)B * p->parts * kWaves,
+                                              4.0 * (p->n + 1 + (p->v0 ? 1 : 0)) * W,
+                                              kStageTiles * (256 / W));
+    }
     a.st = carve_problem(p);
     hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
     CcReportArgs r;
@@ -650,6 +669,11 @@ static int launch_fused_pass(const btard_cc_problem *p, int32_t iterations, floa
     // partitions the Gram iteration finished and vouches for take the kernel's light body
     a.use_gram_norms = gram_applies(p) ? 1 : 0;
     a.scaled = preclip_on(p) ? 1 : 0;
+    {
+        const int W = variant_tile_width(var);
+        a.epoch_mult = stage_epoch_multiplier((int64_t)B * p->parts * kWaves, 4.0 * (p->n + 1) * W,
+                                              kStageTiles * (256 / W));
+    }
     a.st = carve_problem(p);
     hipLaunchKernelGGL(fn, dim3(B, p->parts), dim3(kBlock), 0, s, a);
     *blocks = B;
@@ -765,6 +789,8 @@ int btard_coordinate_median(const float *g, int64_t ldg, int32_t n, int64_t d, f
     const int B = blocks_per_partition(resident, 1, whole, variant_tile_width(var));
     MedianArgs a;
     a.g = g; a.ld = ldg; a.n = n; a.d = d; a.v = v;
+    a.epoch_mult = stage_epoch_multiplier((int64_t)B * kWaves, 4.0 * (n + 1) * variant_tile_width(var),
+                                          kStageTiles);
     hipLaunchKernelGGL(fn, dim3(B), dim3(kBlock), 0, static_cast<hipStream_t>(stream), a);
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }

@@ -427,6 +427,7 @@ struct CcFinishArgs {
     int32_t prev_blocks;
     int32_t scaled;          // rows are taken times st.scale (pre-clipping)
     int32_t rule;            // as in CcArgs
+    uint32_t epoch_mult;     // write bursts of v: 2^32 / ticks per epoch (0: the default)
     CcState st;
 };
 
@@ -533,7 +534,7 @@ __global__ __launch_bounds__(kBlock, 3) void cc_finish_kernel(CcFinishArgs a)
     constexpr bool kStaged = LG <= 4;
     TileStage stage;
     TileStage *const staged = kStaged ? &stage : nullptr;
-    stage.begin(s_stage, wave, a.v, tr.xa, tr.stride);
+    stage.begin(s_stage, wave, a.v, tr.xa, tr.stride, a.epoch_mult);
     for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
         if constexpr (kStaged) stage.template flush_if_due<G::kLanes>(sub, 1, lg == 0);
         finish_tile<NP, LG, RAGGED, HAS_BASE, true>(a.g, a.ld, n, a.v0, a.v, lg, sub,

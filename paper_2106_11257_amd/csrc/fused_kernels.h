@@ -23,6 +23,7 @@ struct FusedArgs {
     int32_t S;               // 2n + 2: n norms^2, n <zhat, r_i>, |zhat|^2, |last update|^2
     int32_t use_gram_norms;  // partitions with gram_ok set take the light body (project_partition)
     int32_t scaled;          // rows are taken times st.scale (pre-clipping)
+    uint32_t epoch_mult;     // write bursts of v: 2^32 / ticks per epoch (0: the default)
     CcState st;
 };
 
@@ -202,7 +203,7 @@ __device__ __forceinline__ void project_partition(const FusedArgs &a, int j, dou
     const TileRange tr = tile_range<G::kW>(lo, hi);
     const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
     TileStage stage;
-    stage.begin(stage_area, wave, a.v, tr.xa, tr.stride);
+    stage.begin(stage_area, wave, a.v, tr.xa, tr.stride, a.epoch_mult);
     if constexpr (LG > 1) {
         for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
             stage.template flush_if_due<G::kLanes>(sub, 1, lg == 0);
@@ -349,7 +350,7 @@ __global__ __launch_bounds__(kBlock, 2) void cc_finish_verify_kernel(FusedArgs a
     constexpr bool kStaged = LG == 1 && NP <= 8;
     TileStage stage;
     TileStage *const staged = kStaged ? &stage : nullptr;
-    stage.begin(s_stage, wave, a.v, tr.xa, tr.stride);
+    stage.begin(s_stage, wave, a.v, tr.xa, tr.stride, a.epoch_mult);
     if constexpr (LG > 1 || SCALED) {
         for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
             if constexpr (kStaged) stage.template flush_if_due<64>(lane, 1);

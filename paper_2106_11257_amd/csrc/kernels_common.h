@@ -289,7 +289,14 @@ __device__ __forceinline__ void load_tile_interior(const float *__restrict__ g, 
 // pass runs, whenever the real-time counter that all of them read (s_memrealtime, 100 MHz)
 // enters a new epoch.  What is written and where does not depend on the clock, only when.
 constexpr int kStageTiles = 16;              // 16 KiB per wavefront, 64 KiB per workgroup
-constexpr uint32_t kEpochTicks = 6000;       // 60 us
+// The epoch length is the caller's (the host picks about three quarters of the time a
+// wavefront needs to fill its area, between 10 and 80 us); it arrives as the multiplier
+// 2^32 / ticks, so that the epoch number is one multiply-high of the counter's low word.
+constexpr uint32_t kEpochTicksDefault = 6000;                    // 60 us
+__host__ __device__ constexpr uint32_t epoch_multiplier(uint32_t ticks)
+{
+    return (uint32_t)(0x100000000ull / (ticks < 1 ? 1 : ticks));
+}
 constexpr int kStageSlots = kWaves * kStageTiles * 64;
 
 struct TileStage {
@@ -300,6 +307,12 @@ struct TileStage {
     int64_t stride;
     int count;
     uint32_t epoch;
+    uint32_t multiplier;  // 2^32 / ticks per epoch
+
+    __device__ __forceinline__ uint32_t epoch_now() const
+    {
+        return __umulhi((uint32_t)__builtin_amdgcn_s_memrealtime(), multiplier);
+    }
 
     // LANES: lanes that hold a tile of v (those of lane group 0), 4 coordinates each; the
     // area then takes 64 / LANES x kStageTiles tiles
@@ -307,14 +320,15 @@ struct TileStage {
     static constexpr int capacity() { return kStageTiles * (64 / LANES); }
 
     __device__ __forceinline__ void begin(f32x4_u *block_area, int wave, float *v, int64_t xa,
-                                          int64_t tile_stride)
+                                          int64_t tile_stride, uint32_t epoch_mult)
     {
         area = block_area + wave * (kStageTiles * 64);
         base = v + xa;
         first = 0;
         stride = tile_stride;
         count = 0;
-        epoch = (uint32_t)__builtin_amdgcn_s_memrealtime() / kEpochTicks;
+        multiplier = epoch_mult ? epoch_mult : epoch_multiplier(kEpochTicksDefault);
+        epoch = epoch_now();
     }
 
     // (sub: the lane's index in its lane group; holds: it belongs to lane group 0)
@@ -346,7 +360,7 @@ struct TileStage {
     template <int LANES>
     __device__ __forceinline__ void flush_if_due(int sub, int room, bool holds = true)
     {
-        const uint32_t now = (uint32_t)__builtin_amdgcn_s_memrealtime() / kEpochTicks;
+        const uint32_t now = epoch_now();
         if (count + room > capacity<LANES>() || now != epoch) flush<LANES>(sub, holds);
         epoch = now;
     }

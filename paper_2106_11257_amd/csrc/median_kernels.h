@@ -24,6 +24,7 @@ struct MedianArgs {
     int32_t n;
     int64_t d;
     float *v;
+    uint32_t epoch_mult;     // write bursts of v: 2^32 / ticks per epoch (0: the default)
 };
 
 // Batcher's odd-even merge sort of N = 2^m values (ascending), fully unrolled.
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(kBlock) void coordinate_median_kernel(MedianArgs a)
     // (with one lane group the interior tiles of v are parked in LDS and written in bursts)
     __shared__ f32x4_u s_stage[LG == 1 ? kStageSlots : 1];
     TileStage stage;
-    stage.begin(s_stage, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), a.v, tr.xa, tr.stride);
+    stage.begin(s_stage, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), a.v, tr.xa, tr.stride, a.epoch_mult);
     int64_t staged_next = -1;                           // the tile that would continue the staged run
     for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
         if constexpr (LG == 1) stage.template flush_if_due<64>(lane, 1);
