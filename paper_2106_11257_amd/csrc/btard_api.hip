@@ -214,13 +214,13 @@ int resident_blocks(const void *fn)
     return slot;
 }
 
-// Epoch of the write bursts of v (TileStage): about three quarters of the time in which a
-// wavefront fills its staging area, when `waves` wavefronts share ~6.5 TB/s and each tile
+// Epoch of the write bursts of v (TileStage): half the time in which a wavefront fills its
+// staging area (measured: 0.35 and 0.75 of it are both slower on the large slabs), when `waves` wavefronts share ~6.5 TB/s and each tile
 // costs tile_bytes of traffic; between 10 and 80 us.  Returned as 2^32 / ticks (100 MHz).
 uint32_t stage_epoch_multiplier(int64_t waves, double tile_bytes, int capacity_tiles)
 {
     const double tile_us = (double)waves * tile_bytes / 6.5e6;            // bytes / (6.5e12 B/s) in us
-    double us = 0.75 * (double)capacity_tiles * tile_us;
+    double us = 0.5 * (double)capacity_tiles * tile_us;
     if (us < 10.0) us = 10.0;
     if (us > 80.0) us = 80.0;
     return epoch_multiplier((uint32_t)(us * 100.0));

@@ -289,8 +289,8 @@ __device__ __forceinline__ void load_tile_interior(const float *__restrict__ g, 
 // pass runs, whenever the real-time counter that all of them read (s_memrealtime, 100 MHz)
 // enters a new epoch.  What is written and where does not depend on the clock, only when.
 constexpr int kStageTiles = 16;              // 16 KiB per wavefront, 64 KiB per workgroup
-// The epoch length is the caller's (the host picks about three quarters of the time a
-// wavefront needs to fill its area, between 10 and 80 us); it arrives as the multiplier
+// The epoch length is the caller's (the host picks half the time a wavefront needs to
+// fill its area, between 10 and 80 us); it arrives as the multiplier
 // 2^32 / ticks, so that the epoch number is one multiply-high of the counter's low word.
 constexpr uint32_t kEpochTicksDefault = 6000;                    // 60 us
 __host__ __device__ constexpr uint32_t epoch_multiplier(uint32_t ticks)
