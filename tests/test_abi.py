@@ -123,3 +123,19 @@ def test_argument_errors_are_caught_on_the_host_before_any_gpu_call():
     assert vp(tau=-1.0) == -1
     assert vp(delta=ctypes.c_void_p(0x2000000), ldd=4) == -1
     assert vp(wsb=8) == -2
+
+
+def test_binding_constants_match_the_header():
+    """The flag and limit values of the Python binding are those of include/btard.h."""
+    import re
+    from paper_2106_11257_amd import binding
+    header = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
+                               "include", "btard.h")).read()
+    defines = dict(re.findall(r"#define\s+(BTARD_[A-Z_]+)\s+(\d+)u?\b", header))
+    flags = [k for k in defines if k.startswith("BTARD_FLAG_")]
+    assert len(flags) >= 5
+    for name in flags:
+        assert getattr(binding, name) == int(defines[name]), name
+    # the flags are distinct bits
+    bits = [int(defines[k]) for k in flags if int(defines[k]) != 0]
+    assert len(set(bits)) == len(bits) and all(b & (b - 1) == 0 for b in bits)
