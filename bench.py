@@ -22,6 +22,17 @@ Two ways of running the same step are timed in one invocation:
 
 Both produce the same v, iteration counts and verification outputs (tests).
 
+With no --config the line describes the largest configuration (5: 16 peers, 1.3 G
+coordinates, an 84 GB slab) and carries a "per_config" object with the same figures, in
+short, for configurations 1-4 (measured with fewer steps).  --config k measures that
+configuration alone.
+
+`value` is an algorithmic-equivalent rate: bytes of peer gradients aggregated per
+CenteredClip iteration (4 n sum_j d_j iters_j) per second of the whole step.  On the
+headline path the iteration runs on the Gram matrix, so the slab itself is read only twice
+per step and `value` can exceed the HBM peak; "physical" gives the bytes a step really
+moves per second, and `roofline` the dominant kernel against the HBM (or matrix) peak.
+
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
                   [--mode both|headline|streaming]
 Prints one JSON line.
@@ -29,6 +40,7 @@ Prints one JSON line.
 from __future__ import annotations
 
 import argparse
+import gc
 import glob
 import json
 import os
@@ -63,6 +75,10 @@ def recorded_traffic(kernel: str, cfg: int):
     return None
 
 
+TRAFFIC_NOTE = ("traffic: HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
+                "this command, recorded in profiles/*.md (a bench run cannot read counters itself)")
+
+
 def mean(xs):
     return sum(xs) / len(xs) if xs else 0.0
 
@@ -72,7 +88,11 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="BASELINE configuration 1..5")
+    ap.add_argument("--config", type=int, default=0,
+                    help="BASELINE configuration 1..5 alone (default: 5 as the headline, and "
+                         "configurations 1-4 in short under per_config)")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="with no --config: leave out configurations 1-4")
     ap.add_argument("--mode", choices=("both", "headline", "streaming"), default="both")
     ap.add_argument("--host-sync", action="store_true",
                     help="headline path: look at what the Gram iteration left undone (one "
@@ -109,408 +129,484 @@ def main() -> int:
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    wl = workloads.make_workload(args.config, device=dev)
-    G, off = wl.G, wl.offsets
-    n, d, P, M = wl.n, wl.d, wl.parts, wl.max_iters
-    sizes = [off[j + 1] - off[j] for j in range(P)]
-    ws = btard.alloc_workspace(n, P, dev)
-    v = torch.empty(d, dtype=torch.float32, device=dev)
-    iters = torch.empty(P, dtype=torch.int32, device=dev)
-    step_norm = torch.empty(P, dtype=torch.float64, device=dev)
-    vout = {k: torch.empty((n, P), dtype=torch.float64, device=dev)
-            for k in ("norms", "weights", "proj")}
-    vout["colsum"] = torch.empty(P, dtype=torch.float64, device=dev)
-    if args.with_delta:
-        vout["delta"] = torch.empty((n, d), dtype=torch.float32, device=dev)
-    stream = torch.cuda.current_stream(dev)
-    slab_bytes = 4.0 * n * d
-    lam = 0.0
-    if args.preclip > 0.0:
-        row_norms = G[:, off[0]:off[1]].double().norm(dim=1)
-        lam = float(torch.tensor(args.preclip * float(row_norms.median()), dtype=torch.float32))
+    def measure(cfg, steps, warmup, brief, cpu_baseline):
+        """All figures of one configuration.  brief: the short form used for the per_config
+        entries (no comparison variants, no extras).  cpu_baseline: thread counts to time
+        the oracle with (0: all the host cores; empty: not at all)."""
+        wl = workloads.make_workload(cfg, device=dev)
+        G, off = wl.G, wl.offsets
+        n, d, P, M = wl.n, wl.d, wl.parts, wl.max_iters
+        sizes = [off[j + 1] - off[j] for j in range(P)]
+        ws = btard.alloc_workspace(n, P, dev)
+        v = torch.empty(d, dtype=torch.float32, device=dev)
+        iters = torch.empty(P, dtype=torch.int32, device=dev)
+        step_norm = torch.empty(P, dtype=torch.float64, device=dev)
+        vout = {k: torch.empty((n, P), dtype=torch.float64, device=dev)
+                for k in ("norms", "weights", "proj")}
+        vout["colsum"] = torch.empty(P, dtype=torch.float64, device=dev)
+        if args.with_delta:
+            vout["delta"] = torch.empty((n, d), dtype=torch.float32, device=dev)
+        factors = torch.empty((n, P), dtype=torch.float64, device=dev)
+        vout_preclipped = dict(vout, factors=torch.empty_like(factors))
+        stream = torch.cuda.current_stream(dev)
+        slab_bytes = 4.0 * n * d
+        lam = 0.0
+        if args.preclip > 0.0:
+            row_norms = G[:, off[0]:off[1]].double().norm(dim=1)
+            lam = float(torch.tensor(args.preclip * float(row_norms.median()), dtype=torch.float32))
 
-    if args.copy_calibration:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        if args.copy_calibration and not brief:
+            src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
 
-    def rec(events, i):
-        if events is not None:
-            events[i].record(stream)
+        def rec(events, i):
+            if events is not None:
+                events[i].record(stream)
 
-    # ---- the two ways of running a step; events (if given) mark the segment boundaries
-    prob_s = btard.make_problem(G, off, wl.tau, wl.eps, M, workspace=ws, preclip=lam)
-    seg_s = ("cc_begin", "cc_iterate", "cc_finish", "verify")
+        # ---- the two ways of running a step; events (if given) mark the segment boundaries
+        prob_s = btard.make_problem(G, off, wl.tau, wl.eps, M, workspace=ws, preclip=lam)
+        seg_s = ("cc_begin", "cc_iterate", "cc_finish", "verify")
 
-    def step_streaming(events=None):
-        rec(events, 0)
-        btard.cc_begin(prob_s)
-        rec(events, 1)
-        btard.cc_iterate(prob_s, 0, M)
-        rec(events, 2)
-        if lam > 0.0:
-            # (the stand-alone verification call knows nothing of pre-clipping: the fused
-            # last pass serves both segments here)
-            btard.cc_finish_verify(prob_s, M, wl.seed_z, v, iters, step_norm, out=vout)
-            rec(events, 3)
-        else:
+        def step_streaming(events=None):
+            rec(events, 0)
+            btard.cc_begin(prob_s)
+            rec(events, 1)
+            btard.cc_iterate(prob_s, 0, M)
+            rec(events, 2)
             btard.cc_finish(prob_s, M, v, iters, step_norm)
             rec(events, 3)
-            btard.verify_projections(G, off, v, wl.tau, wl.seed_z, want_delta=args.with_delta,
-                                     workspace=ws, out=vout)
-        rec(events, 4)
+            if lam > 0.0:
+                # (a verifying peer holds the factors of the rows it clipped: they are handed
+                # over, not measured again)
+                btard.cc_preclip_factors(prob_s, factors)
+                btard.verify_projections_preclipped(G, off, v, wl.tau, wl.seed_z, factors=factors,
+                                                    want_delta=args.with_delta, workspace=ws,
+                                                    out=vout_preclipped)
+            else:
+                btard.verify_projections(G, off, v, wl.tau, wl.seed_z, want_delta=args.with_delta,
+                                         workspace=ws, out=vout)
+            rec(events, 4)
 
-    # (the Gram kernels also do the work of btard_cc_begin where they can: P <= 255)
-    headline_flags = btard.BTARD_FLAG_GRAM | btard.BTARD_FLAG_GRAM_BEGINS
-    prob_h = btard.make_problem(G, off, wl.tau, wl.eps, M, workspace=ws,
-                                flags=headline_flags, preclip=lam)
-    seg_h = ("cc_begin", "gram_matrix", "gram_iterate", "fallback_passes", "finish_verify")
-    fallback_passes = []
+        # (the Gram kernels also do the work of btard_cc_begin where they can: P <= 255)
+        headline_flags = btard.BTARD_FLAG_GRAM | btard.BTARD_FLAG_GRAM_BEGINS
+        prob_h = btard.make_problem(G, off, wl.tau, wl.eps, M, workspace=ws,
+                                    flags=headline_flags, preclip=lam)
+        seg_h = ("cc_begin", "gram_matrix", "gram_iterate", "fallback_passes", "finish_verify")
+        fallback_passes = []
 
-    def step_headline(events=None, host_sync=False):
-        # Without host_sync nothing waits for the device: the last pass is enqueued right
-        # behind the Gram iteration, and whether that iteration finished every partition
-        # (it does on the benchmark configurations) is read back after the timed region,
-        # together with the results.  If it did not, the step is completed by
-        # complete_headline() and the synchronised variant is what gets reported.
-        rec(events, 0)
-        rec(events, 1)                                           # (no launch of its own any more)
-        btard.cc_gram_matrix(prob_h)
-        rec(events, 2)
-        btard.cc_gram_iterate(prob_h)
-        rec(events, 3)
-        passes = 0
-        if host_sync:
-            passes = btard.cc_remaining(prob_h)                  # one synchronisation
-            fallback_passes.append(passes)
-            btard.cc_iterate(prob_h, 0, passes)
-        rec(events, 4)
-        btard.cc_finish_verify(prob_h, passes, wl.seed_z, v, iters, step_norm, out=vout)
-        rec(events, 5)
-
-    def complete_headline():
-        """After an unsynchronised step: the passes the Gram iteration left, if any."""
-        passes = btard.cc_remaining(prob_h)
-        if passes > 0:
-            btard.cc_iterate(prob_h, 0, passes)
+        def step_headline(events=None, host_sync=False):
+            # Without host_sync nothing waits for the device: the last pass is enqueued right
+            # behind the Gram iteration, and whether that iteration finished every partition
+            # (it does on the benchmark configurations) is read back after the timed region,
+            # together with the results.  If it did not, the step is completed by
+            # complete_headline() and the synchronised variant is what gets reported.
+            rec(events, 0)
+            rec(events, 1)                                           # (no launch of its own any more)
+            btard.cc_gram_matrix(prob_h)
+            rec(events, 2)
+            btard.cc_gram_iterate(prob_h)
+            rec(events, 3)
+            passes = 0
+            if host_sync:
+                passes = btard.cc_remaining(prob_h)                  # one synchronisation
+                fallback_passes.append(passes)
+                btard.cc_iterate(prob_h, 0, passes)
+            rec(events, 4)
             btard.cc_finish_verify(prob_h, passes, wl.seed_z, v, iters, step_norm, out=vout)
+            rec(events, 5)
+
+        def complete_headline():
+            """After an unsynchronised step: the passes the Gram iteration left, if any."""
+            passes = btard.cc_remaining(prob_h)
+            if passes > 0:
+                btard.cc_iterate(prob_h, 0, passes)
+                btard.cc_finish_verify(prob_h, passes, wl.seed_z, v, iters, step_norm, out=vout)
+                torch.cuda.synchronize()
+            return passes
+
+        def run(step, nseg, steps):
+            for _ in range(warmup):
+                step()
             torch.cuda.synchronize()
-        return passes
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(nseg + 1)]
+                   for _ in range(steps)]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for k in range(steps):
+                step(evs[k])
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            seg_ms = [mean([evs[k][s].elapsed_time(evs[k][s + 1]) for k in range(steps)])
+                      for s in range(nseg)]
+            return (t1 - t0) * 1e3 / steps, seg_ms
 
-    def run(step, nseg, steps):
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(nseg + 1)]
-               for _ in range(steps)]
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(steps):
-            step(evs[k])
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        seg_ms = [mean([evs[k][s].elapsed_time(evs[k][s + 1]) for k in range(steps)])
-                  for s in range(nseg)]
-        return (t1 - t0) * 1e3 / steps, seg_ms
+        def work_done():
+            it = iters.cpu().tolist()
+            applied = sum(sizes[j] * max(it[j], 0) for j in range(P))
+            # passes a per-iteration path makes over partition j: one per update, plus the pass
+            # that finds an update below eps when the partition stops before the cap
+            passes = sum(sizes[j] * (max(it[j], 0) + (1 if 0 <= it[j] < M else 0)) for j in range(P))
+            return it, 4.0 * n * applied, 4.0 * n * passes
 
-    def work_done():
-        it = iters.cpu().tolist()
-        applied = sum(sizes[j] * max(it[j], 0) for j in range(P))
-        # passes a per-iteration path makes over partition j: one per update, plus the pass
-        # that finds an update below eps when the partition stops before the cap
-        passes = sum(sizes[j] * (max(it[j], 0) + (1 if 0 <= it[j] < M else 0)) for j in range(P))
-        return it, 4.0 * n * applied, 4.0 * n * passes
-
-    out = {
-        "metric": "aggregated peer-gradient GB/s per CenteredClip iteration + % of HBM roofline",
-        "value": None, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f64", "data": "synthetic",
-        "config": {"workload": wl.name, "n": n, "d": d, "parts": P, "tau": wl.tau, "eps": wl.eps,
-                   "max_iters": M, "seed_inputs": wl.seed_inputs, "seed_z": wl.seed_z},
-    }
-    if lam > 0.0:
-        out["config"]["preclip_lambda"] = lam
-
-    # ---- streaming path: the per-iteration kernel
-    if args.mode in ("both", "streaming"):
-        steps_s = args.steps if args.mode == "streaming" else max(3, args.steps // 4)
-        ms, seg = run(step_streaming, 4, steps_s)
-        it, agg_bytes, pass_bytes = work_done()
-        t_iter = seg[1] * 1e-3
-        achieved = pass_bytes / t_iter / 1e9
-        streaming = {
-            "value": round(agg_bytes / (ms * 1e-3) / 1e9, 1), "unit": "GB/s",
-            "ms_per_step": round(ms, 4), "steps": steps_s,
-            "segments_ms": {k: round(x, 4) for k, x in zip(seg_s, seg)},
-            "cc_only_GBps": round(agg_bytes / (sum(seg[0:3]) * 1e-3) / 1e9, 1),
-            "verify_GBps": round(4.0 * (n + 1) * d / (seg[3] * 1e-3) / 1e9, 1),
-            "roofline": {
-                "bound": "hbm", "kernel": "cc_pass_kernel", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": recorded_traffic("cc_pass_kernel", args.config),
-                "bytes_per_launch": pass_bytes / M, "launches_per_step": M,
-                "avg_launch_us": round(t_iter / M * 1e6, 2)},
+        out = {
+            "metric": "aggregated peer-gradient GB/s per CenteredClip iteration + % of HBM roofline",
+            "value": None, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f64", "data": "synthetic",
+            "config": {"workload": wl.name, "n": n, "d": d, "parts": P, "tau": wl.tau, "eps": wl.eps,
+                       "max_iters": M, "seed_inputs": wl.seed_inputs, "seed_z": wl.seed_z},
         }
-        out["streaming"] = streaming
-        out["config"].update({"iters_min": min(it), "iters_max": max(it)})
-        if args.mode == "streaming":
-            out["value"], out["ms_per_step"] = streaming["value"], streaming["ms_per_step"]
-            out["roofline"] = streaming["roofline"]
-            out["config"]["mode"] = "streaming: one pass over the data per iteration"
+        if lam > 0.0:
+            out["config"]["preclip_lambda"] = lam
 
-    # ---- headline path
-    if args.mode in ("both", "headline"):
-        def headline_numbers(host_sync, steps):
-            fallback_passes.clear()
-            ms, seg = run(lambda ev=None: step_headline(ev, host_sync), 5, steps)
-            left = 0 if host_sync else complete_headline()
-            return ms, seg, left
+        # ---- streaming path: the per-iteration kernel
+        if args.mode in ("both", "streaming"):
+            steps_s = steps if args.mode == "streaming" else max(3, steps // 4)
+            ms, seg = run(step_streaming, 4, steps_s)
+            it, agg_bytes, pass_bytes = work_done()
+            t_iter = seg[1] * 1e-3
+            achieved = pass_bytes / t_iter / 1e9
+            streaming = {
+                "value": round(agg_bytes / (ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                "ms_per_step": round(ms, 4), "steps": steps_s,
+                "segments_ms": {k: round(x, 4) for k, x in zip(seg_s, seg)},
+                "cc_only_GBps": round(agg_bytes / (sum(seg[0:3]) * 1e-3) / 1e9, 1),
+                "verify_GBps": round(4.0 * (n + 1) * d / (seg[3] * 1e-3) / 1e9, 1),
+                "roofline": {
+                    "bound": "hbm", "kernel": "cc_pass_kernel", "achieved": round(achieved, 1),
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                    "traffic": recorded_traffic("cc_pass_kernel", cfg),
+                    "bytes_per_launch": pass_bytes / M, "launches_per_step": M,
+                    "avg_launch_us": round(t_iter / M * 1e6, 2)},
+            }
+            out["streaming"] = streaming
+            out["config"].update({"iters_min": min(it), "iters_max": max(it)})
+            if args.mode == "streaming":
+                out["value"], out["ms_per_step"] = streaming["value"], streaming["ms_per_step"]
+                out["roofline"] = streaming["roofline"]
+                out["config"]["mode"] = "streaming: one pass over the data per iteration"
 
-        # (the Gram formulation serves n <= 64; beyond that every pass is a streaming pass
-        # and the step cannot skip the look at what is left)
-        synced = args.host_sync or n > 64
-        ms, seg, left = headline_numbers(synced, args.steps)
-        unsync_note = None
-        if left > 0:
-            # the Gram iteration handed partitions over: only the synchronised variant does
-            # the whole job inside the timed region
-            unsync_note = f"unsynchronised attempt left {left} passes to run; reporting the synchronised path"
-            ms, seg, _ = headline_numbers(True, args.steps)
-            synced = True
-        it, agg_bytes, pass_bytes = work_done()
-        fb = max(fallback_passes) if fallback_passes else 0
-        last = "cc_finish_verify_kernel"       # light body where the Gram iteration finished
-        kernels = {
-            # name: (ms between the HIP events around its launch(es), algorithmic bytes)
-            "gram_pass_kernel": (seg[1], slab_bytes),
-            last: (seg[4], slab_bytes + 4.0 * d),
-        }
-        if fb > 0:
-            # partitions the Gram iteration did not finish (or n > 16): per-iteration passes
-            kernels["cc_pass_kernel"] = (seg[3], pass_bytes)
-        # The kernels by themselves.  An event pair inside a step brackets a whole call (the
-        # last one also launches verify_finish_kernel) and adds a few microseconds of marker
-        # latency, so the two long kernels are also timed back to back on the finished state
-        # of the last step, K launches between two HIP events on the launch stream: the Gram
-        # pass alone, and the pair (Gram pass, fused last pass) as it runs in a step -- the
-        # last pass finds the end of the slab still in the memory-side cache -- from which
-        # the last pass is the difference.
-        def back_to_back(fn, reps=16):
-            fn()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for _ in range(reps):
+        # ---- headline path
+        if args.mode in ("both", "headline"):
+            def headline_numbers(host_sync, steps):
+                fallback_passes.clear()
+                ms, seg = run(lambda ev=None: step_headline(ev, host_sync), 5, steps)
+                left = 0 if host_sync else complete_headline()
+                return ms, seg, left
+
+            # (the Gram formulation serves n <= 64; beyond that every pass is a streaming pass
+            # and the step cannot skip the look at what is left)
+            synced = args.host_sync or n > 64
+            ms, seg, left = headline_numbers(synced, steps)
+            unsync_note = None
+            if left > 0:
+                # the Gram iteration handed partitions over: only the synchronised variant does
+                # the whole job inside the timed region
+                unsync_note = f"unsynchronised attempt left {left} passes to run; reporting the synchronised path"
+                ms, seg, _ = headline_numbers(True, steps)
+                synced = True
+            it, agg_bytes, pass_bytes = work_done()
+            fb = max(fallback_passes) if fallback_passes else 0
+            last = "cc_finish_verify_kernel"       # light body where the Gram iteration finished
+            kernels = {
+                # name: (ms between the HIP events around its launch(es), algorithmic bytes)
+                "gram_pass_kernel": (seg[1], slab_bytes),
+                last: (seg[4], slab_bytes + 4.0 * d),
+            }
+            if fb > 0:
+                # partitions the Gram iteration did not finish (or n > 16): per-iteration passes
+                kernels["cc_pass_kernel"] = (seg[3], pass_bytes)
+            # The kernels by themselves.  An event pair inside a step brackets a whole call (the
+            # last one also launches verify_finish_kernel) and adds a few microseconds of marker
+            # latency, so the two long kernels are also timed back to back on the finished state
+            # of the last step, K launches between two HIP events on the launch stream: the Gram
+            # pass alone, and the pair (Gram pass, fused last pass) as it runs in a step -- the
+            # last pass finds the end of the slab still in the memory-side cache -- from which
+            # the last pass is the difference.
+            def back_to_back(fn, reps=16):
                 fn()
-            e1.record(stream)
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / reps
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(reps):
+                    fn()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / reps
 
-        alone = {}
-        if fb == 0 and n <= 64:
-            reps = 16 if slab_bytes < 4e9 else 4
+            alone = {}
+            if fb == 0 and n <= 64:
+                reps = 16 if slab_bytes < 4e9 else 4
 
-            def pair():
-                btard.cc_gram_matrix(prob_h)
-                btard.debug_last_pass(prob_h, 0, wl.seed_z, v)
-            # (three rounds, the median of each: one round's difference is at the mercy of a
-            # single slow launch)
-            t_grams, t_lasts = [], []
-            for _ in range(3):
-                t_g = back_to_back(lambda: btard.cc_gram_matrix(prob_h), reps)
-                t_grams.append(t_g)
-                t_lasts.append(back_to_back(pair, reps) - t_g)
-            alone = {"gram_pass_kernel": sorted(t_grams)[1], last: sorted(t_lasts)[1]}
-            # (v and the outputs are as the last step left them: the same values again)
-        table = {}
-        for name, (t_ms, nbytes) in kernels.items():
-            ach = nbytes / (t_ms * 1e-3) / 1e9 if t_ms > 0 else 0.0
-            table[name] = {"us": round(t_ms * 1e3, 2), "algorithmic_bytes": nbytes,
-                           "achieved_GBps": round(ach, 1),
-                           "frac_of_hbm_peak": round(ach / HBM_PEAK_GBPS, 4)}
-            if name in alone:
-                # "us": between the events around the call in the timed steps;
-                # "kernel_us": the kernel alone, back to back -- what the roofline uses
-                k_ms = alone[name]
-                ach = nbytes / (k_ms * 1e-3) / 1e9
-                table[name].update({"kernel_us": round(k_ms * 1e3, 2),
-                                    "achieved_GBps": round(ach, 1),
-                                    "frac_of_hbm_peak": round(ach / HBM_PEAK_GBPS, 4)})
-                kernels[name] = (k_ms, nbytes)
-        dominant = max(kernels, key=lambda name: kernels[name][0])
-        out["value"] = round(agg_bytes / (ms * 1e-3) / 1e9, 1)
-        out["ms_per_step"] = round(ms, 4)
-        out["segments_ms"] = {k: round(x, 4) for k, x in zip(seg_h, seg)}
-        out["kernels"] = table
-        out["roofline"] = {
-            "bound": "hbm", "kernel": dominant, "achieved": table[dominant]["achieved_GBps"],
-            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": table[dominant]["frac_of_hbm_peak"],
-            "traffic": recorded_traffic(dominant, args.config),
-            "bytes_per_launch": table[dominant]["algorithmic_bytes"], "launches_per_step": 1,
-            "avg_launch_us": table[dominant].get("kernel_us", table[dominant]["us"])}
-        if dominant == "gram_pass_kernel" and 16 < n <= 64:
-            # 16 < n <= 64: the Gram pass is a dense fp64 contraction bound by the matrix unit:
-            # one 16 x 16 x 4 instruction (2048 flop) per pair of 16-peer groups and 4 coordinates
-            nb = (n + 15) // 16
-            flops = nb * (nb + 1) // 2 * 512.0 * d
-            t_s = kernels[dominant][0] * 1e-3
+                def pair():
+                    btard.cc_gram_matrix(prob_h)
+                    btard.debug_last_pass(prob_h, 0, wl.seed_z, v)
+                # (three rounds, the median of each: one round's difference is at the mercy of a
+                # single slow launch)
+                t_grams, t_lasts = [], []
+                for _ in range(3):
+                    t_g = back_to_back(lambda: btard.cc_gram_matrix(prob_h), reps)
+                    t_grams.append(t_g)
+                    t_lasts.append(back_to_back(pair, reps) - t_g)
+                alone = {"gram_pass_kernel": sorted(t_grams)[1], last: sorted(t_lasts)[1]}
+                # (v and the outputs are as the last step left them: the same values again)
+            table = {}
+            for name, (t_ms, nbytes) in kernels.items():
+                ach = nbytes / (t_ms * 1e-3) / 1e9 if t_ms > 0 else 0.0
+                table[name] = {"us": round(t_ms * 1e3, 2), "algorithmic_bytes": nbytes,
+                               "achieved_GBps": round(ach, 1),
+                               "frac_of_hbm_peak": round(ach / HBM_PEAK_GBPS, 4)}
+                if name in alone:
+                    # "us": between the events around the call in the timed steps;
+                    # "kernel_us": the kernel alone, back to back -- what the roofline uses
+                    k_ms = alone[name]
+                    ach = nbytes / (k_ms * 1e-3) / 1e9
+                    table[name].update({"kernel_us": round(k_ms * 1e3, 2),
+                                        "achieved_GBps": round(ach, 1),
+                                        "frac_of_hbm_peak": round(ach / HBM_PEAK_GBPS, 4)})
+                    kernels[name] = (k_ms, nbytes)
+            dominant = max(kernels, key=lambda name: kernels[name][0])
+            out["value"] = round(agg_bytes / (ms * 1e-3) / 1e9, 1)
+            out["ms_per_step"] = round(ms, 4)
+            out["segments_ms"] = {k: round(x, 4) for k, x in zip(seg_h, seg)}
+            out["kernels"] = table
             out["roofline"] = {
-                "bound": "mfma", "kernel": dominant, "achieved": round(flops / t_s / 1e12, 2),
-                "peak": 78.6, "unit": "TFLOP/s", "frac": round(flops / t_s / 1e12 / 78.6, 4),
-                "traffic": recorded_traffic(dominant, args.config),
-                "flops_per_launch": flops, "launches_per_step": 1,
-                "avg_launch_us": table[dominant].get("kernel_us", table[dominant]["us"]),
-                "hbm_frac": table[dominant]["frac_of_hbm_peak"]}
-        out["config"].update({
-            "iters_min": min(it), "iters_max": max(it),
-            "mode": "headline: Gram-matrix iteration (streaming fallback), "
-                    + ("one host sync before the last pass, " if synced else
-                       "no host sync inside the step (completeness read back afterwards), ")
-                    + "fused finish+verify",
-            "fallback_passes_per_step": fb})
-        if unsync_note:
-            out["config"]["note"] = unsync_note
-        if not synced and not args.no_graph:
-            # The same four launches captured once into a HIP graph and replayed: nothing in
-            # the unsynchronised step depends on the host, so a replay is the whole step.
-            # (The library clears its state with kernels, never with memset nodes.)
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                # a problem description that carries the capturing stream
-                prob_g = btard.make_problem(G, off, wl.tau, wl.eps, M, workspace=ws,
-                                            flags=headline_flags, preclip=lam)
-                btard.cc_gram_matrix(prob_g)
-                btard.cc_gram_iterate(prob_g)
-                btard.cc_finish_verify(prob_g, 0, wl.seed_z, v, iters, step_norm, out=vout)
-            for _ in range(args.warmup):
-                graph.replay()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(args.steps):
-                graph.replay()
-            torch.cuda.synchronize()
-            ms_g = (time.perf_counter() - t0) * 1e3 / args.steps
-            if btard.cc_remaining(prob_g) == 0 and iters.cpu().tolist() == it:
-                out["eager_launches"] = {"value": out["value"], "unit": "GB/s",
-                                         "ms_per_step": out["ms_per_step"]}
-                out["value"] = round(agg_bytes / (ms_g * 1e-3) / 1e9, 1)
-                out["ms_per_step"] = round(ms_g, 4)
-                out["config"]["mode"] += ", the step's 4 launches replayed as one HIP graph"
-                out["config"]["note_timing"] = ("value and ms_per_step: graph replays; segments_ms "
-                                                "and kernels[].us: HIP events around the calls of "
-                                                "the eager steps; kernels[].kernel_us and roofline: "
-                                                "the kernel alone, launched back to back")
-        if not synced and args.mode == "both":
-            # the same step with the synchronisation, for comparison
-            ms2, seg2, _ = headline_numbers(True, max(3, args.steps // 2))
-            out["with_host_sync"] = {
-                "value": round(agg_bytes / (ms2 * 1e-3) / 1e9, 1), "unit": "GB/s",
-                "ms_per_step": round(ms2, 4),
-                "segments_ms": {k: round(x, 4) for k, x in zip(seg_h, seg2)}}
+                "bound": "hbm", "kernel": dominant, "achieved": table[dominant]["achieved_GBps"],
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": table[dominant]["frac_of_hbm_peak"],
+                "traffic": recorded_traffic(dominant, cfg),
+                "bytes_per_launch": table[dominant]["algorithmic_bytes"], "launches_per_step": 1,
+                "avg_launch_us": table[dominant].get("kernel_us", table[dominant]["us"])}
+            if dominant == "gram_pass_kernel" and 16 < n <= 64:
+                # 16 < n <= 64: the Gram pass is a dense fp64 contraction bound by the matrix unit:
+                # one 16 x 16 x 4 instruction (2048 flop) per pair of 16-peer groups and 4 coordinates
+                nb = (n + 15) // 16
+                flops = nb * (nb + 1) // 2 * 512.0 * d
+                t_s = kernels[dominant][0] * 1e-3
+                out["roofline"] = {
+                    "bound": "mfma", "kernel": dominant, "achieved": round(flops / t_s / 1e12, 2),
+                    "peak": 78.6, "unit": "TFLOP/s", "frac": round(flops / t_s / 1e12 / 78.6, 4),
+                    "traffic": recorded_traffic(dominant, cfg),
+                    "flops_per_launch": flops, "launches_per_step": 1,
+                    "avg_launch_us": table[dominant].get("kernel_us", table[dominant]["us"]),
+                    "hbm_frac": table[dominant]["frac_of_hbm_peak"]}
+            # what a step really moves: the slab once for the Gram matrices, the slab and v once
+            # for the last pass, and whatever per-iteration passes the Gram iteration left
+            phys_bytes = sum(nbytes for (_t, nbytes) in kernels.values()) if n <= 64 else \
+                pass_bytes + slab_bytes + 4.0 * d
+            out["value_kind"] = ("algorithmic-equivalent: bytes of peer gradients aggregated per "
+                                 "CenteredClip iteration (4 n sum_j d_j iters_j) per second of the "
+                                 "whole step (CenteredClip to its stopping rule + verification); "
+                                 "not comparable with the HBM peak, see physical and roofline")
+            out["physical"] = {"bytes_per_step": phys_bytes, "unit": "GB/s"}
+            out["config"].update({
+                "iters_min": min(it), "iters_max": max(it),
+                "mode": "headline: Gram-matrix iteration (streaming fallback), "
+                        + ("one host sync before the last pass, " if synced else
+                           "no host sync inside the step (completeness read back afterwards), ")
+                        + "fused finish+verify",
+                "fallback_passes_per_step": fb})
+            if unsync_note:
+                out["config"]["note"] = unsync_note
+            if not synced and not args.no_graph:
+                # The same four launches captured once into a HIP graph and replayed: nothing in
+                # the unsynchronised step depends on the host, so a replay is the whole step.
+                # (The library clears its state with kernels, never with memset nodes.)
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    # a problem description that carries the capturing stream
+                    prob_g = btard.make_problem(G, off, wl.tau, wl.eps, M, workspace=ws,
+                                                flags=headline_flags, preclip=lam)
+                    btard.cc_gram_matrix(prob_g)
+                    btard.cc_gram_iterate(prob_g)
+                    btard.cc_finish_verify(prob_g, 0, wl.seed_z, v, iters, step_norm, out=vout)
+                for _ in range(warmup):
+                    graph.replay()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    graph.replay()
+                torch.cuda.synchronize()
+                ms_g = (time.perf_counter() - t0) * 1e3 / steps
+                if btard.cc_remaining(prob_g) == 0 and iters.cpu().tolist() == it:
+                    out["eager_launches"] = {"value": out["value"], "unit": "GB/s",
+                                             "ms_per_step": out["ms_per_step"]}
+                    out["value"] = round(agg_bytes / (ms_g * 1e-3) / 1e9, 1)
+                    out["ms_per_step"] = round(ms_g, 4)
+                    out["config"]["mode"] += ", the step's 4 launches replayed as one HIP graph"
+                    out["config"]["note_timing"] = ("value and ms_per_step: graph replays; segments_ms "
+                                                    "and kernels[].us: HIP events around the calls of "
+                                                    "the eager steps; kernels[].kernel_us and roofline: "
+                                                    "the kernel alone, launched back to back")
+            if not synced and args.mode == "both" and not brief:
+                # the same step with the synchronisation, for comparison
+                ms2, seg2, _ = headline_numbers(True, max(3, steps // 2))
+                out["with_host_sync"] = {
+                    "value": round(agg_bytes / (ms2 * 1e-3) / 1e9, 1), "unit": "GB/s",
+                    "ms_per_step": round(ms2, 4),
+                    "segments_ms": {k: round(x, 4) for k, x in zip(seg_h, seg2)}}
 
-    # ---- the baseline aggregators on the same slab (not part of the headline step)
-    if args.baselines:
-        def timed(fn, reps):
-            fn()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for _ in range(reps):
+            rate = out["physical"]["bytes_per_step"] / (out["ms_per_step"] * 1e-3) / 1e9
+            out["physical"].update({"GBps": round(rate, 1),
+                                    "frac_of_hbm_peak": round(rate / HBM_PEAK_GBPS, 4)})
+            out["roofline"]["traffic_note"] = TRAFFIC_NOTE
+
+        # ---- the baseline aggregators on the same slab (not part of the headline step)
+        if args.baselines and not brief:
+            def timed(fn, reps):
                 fn()
-            e1.record(stream)
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / reps
-        vm = torch.empty(d, dtype=torch.float32, device=dev)
-        t_med = timed(lambda: btard.coordinate_median(G, vm), 5)
-        gm_iters = 20
-        t_gm = timed(lambda: btard.geometric_median(G, off, 1e-6, 0.0, gm_iters, workspace=ws), 2)
-        med_bytes = slab_bytes + 4.0 * d
-        out["baselines"] = {
-            "coordinate_median": {
-                "us": round(t_med * 1e3, 2), "algorithmic_bytes": med_bytes,
-                "achieved_GBps": round(med_bytes / (t_med * 1e-3) / 1e9, 1),
-                "frac_of_hbm_peak": round(med_bytes / (t_med * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
-            "geometric_median": {
-                "iterations": gm_iters, "ms": round(t_gm, 4),
-                # gm_iters passes and the pass that writes v
-                "us_per_pass": round(t_gm * 1e3 / (gm_iters + 1), 2),
-                "achieved_GBps": round(slab_bytes * (gm_iters + 1) / (t_gm * 1e-3) / 1e9, 1)},
-        }
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(reps):
+                    fn()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / reps
+            vm = torch.empty(d, dtype=torch.float32, device=dev)
+            t_med = timed(lambda: btard.coordinate_median(G, vm), 5)
+            gm_iters = 20
+            t_gm = timed(lambda: btard.geometric_median(G, off, 1e-6, 0.0, gm_iters, workspace=ws), 2)
+            med_bytes = slab_bytes + 4.0 * d
+            out["baselines"] = {
+                "coordinate_median": {
+                    "us": round(t_med * 1e3, 2), "algorithmic_bytes": med_bytes,
+                    "achieved_GBps": round(med_bytes / (t_med * 1e-3) / 1e9, 1),
+                    "frac_of_hbm_peak": round(med_bytes / (t_med * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+                "geometric_median": {
+                    "iterations": gm_iters, "ms": round(t_gm, 4),
+                    # gm_iters passes and the pass that writes v
+                    "us_per_pass": round(t_gm * 1e3 / (gm_iters + 1), 2),
+                    "achieved_GBps": round(slab_bytes * (gm_iters + 1) / (t_gm * 1e-3) / 1e9, 1)},
+            }
 
-    # ---- the commitments hash(g_i[j]) and hash(v[j]) (not part of the headline step)
-    if args.hashes:
-        hws = torch.empty(max(btard.hash_workspace_bytes(n, off), 256), dtype=torch.uint8, device=dev)
-        dig = torch.empty((n, P, 32), dtype=torch.uint8, device=dev)
-        dig_v = torch.empty((1, P, 32), dtype=torch.uint8, device=dev)
+        # ---- the commitments hash(g_i[j]) and hash(v[j]) (not part of the headline step)
+        if args.hashes and not brief:
+            hws = torch.empty(max(btard.hash_workspace_bytes(n, off), 256), dtype=torch.uint8, device=dev)
+            dig = torch.empty((n, P, 32), dtype=torch.uint8, device=dev)
+            dig_v = torch.empty((1, P, 32), dtype=torch.uint8, device=dev)
 
-        def timed_ms(fn, reps):
-            fn()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for _ in range(reps):
+            def timed_ms(fn, reps):
                 fn()
-            e1.record(stream)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(reps):
+                    fn()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / reps
+            t_h = timed_ms(lambda: btard.partition_hashes(G, off, hws, dig), 3)
+            t_v = timed_ms(lambda: btard.partition_hashes(v, off, hws, dig_v), 3)
+            # 1402 vector instructions per 64-byte SHA-256 block (counted in the kernel's code);
+            # blocks by the tree's rule: chunks of 1024 bytes, then runs of 32 digests
+            def sha_blocks(nbytes):
+                return (nbytes + 8) // 64 + 1
+
+            def tree_blocks(words):
+                nbytes = 4 * words
+                cnt = max(1, -(-nbytes // 1024))
+                total = (cnt - 1) * sha_blocks(1024) + sha_blocks(nbytes - (cnt - 1) * 1024)
+                while cnt > 1:
+                    groups = -(-cnt // 32)
+                    total += (groups - 1) * sha_blocks(32 * 32) + sha_blocks((cnt - (groups - 1) * 32) * 32)
+                    cnt = groups
+                return total
+            blocks = n * sum(tree_blocks(w) for w in sizes)
+            lane_ops = blocks * 1402.0
+            alu_peak = 256 * 4 * 16 * 2.4e9          # lanes x clock: one 32-bit instruction per lane and cycle
+            out["hashes"] = {
+                "slab_ms": round(t_h, 4), "slab_GBps": round(slab_bytes / (t_h * 1e-3) / 1e9, 1),
+                "aggregate_ms": round(t_v, 4),
+                "roofline": {"bound": "alu", "achieved": round(lane_ops / (t_h * 1e-3) / 1e12, 2),
+                             "peak": round(alu_peak / 1e12, 2), "unit": "T lane-instructions/s",
+                             "frac": round(lane_ops / (t_h * 1e-3) / alu_peak, 4)},
+            }
+
+        # ---- the oracle on the host cores, as a baseline only
+        if cpu_baseline:
+            import oracle
+            k = int(max(1, min(P, 6.0e10 // max(2.0 * n * max(sizes) * M, 1))))
+            lo, hi = off[0], off[k]
+            sub = torch.empty((n, hi - lo), dtype=torch.float32, pin_memory=True)
+            for i in range(n):
+                sub[i].copy_(G[i, lo:hi], non_blocking=True)
             torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / reps
-        t_h = timed_ms(lambda: btard.partition_hashes(G, off, hws, dig), 3)
-        t_v = timed_ms(lambda: btard.partition_hashes(v, off, hws, dig_v), 3)
-        # 1402 vector instructions per 64-byte SHA-256 block (counted in the kernel's code);
-        # blocks by the tree's rule: chunks of 1024 bytes, then runs of 32 digests
-        def sha_blocks(nbytes):
-            return (nbytes + 8) // 64 + 1
+            sub = sub.numpy()
+            sub_off = [o - lo for o in off[: k + 1]]
+            all_threads = oracle.num_threads()
 
-        def tree_blocks(words):
-            nbytes = 4 * words
-            cnt = max(1, -(-nbytes // 1024))
-            total = (cnt - 1) * sha_blocks(1024) + sha_blocks(nbytes - (cnt - 1) * 1024)
-            while cnt > 1:
-                groups = -(-cnt // 32)
-                total += (groups - 1) * sha_blocks(32 * 32) + sha_blocks((cnt - (groups - 1) * 32) * 32)
-                cnt = groups
-            return total
-        blocks = n * sum(tree_blocks(w) for w in sizes)
-        lane_ops = blocks * 1402.0
-        alu_peak = 256 * 4 * 16 * 2.4e9          # lanes x clock: one 32-bit instruction per lane and cycle
-        out["hashes"] = {
-            "slab_ms": round(t_h, 4), "slab_GBps": round(slab_bytes / (t_h * 1e-3) / 1e9, 1),
-            "aggregate_ms": round(t_v, 4),
-            "roofline": {"bound": "alu", "achieved": round(lane_ops / (t_h * 1e-3) / 1e12, 2),
-                         "peak": round(alu_peak / 1e12, 2), "unit": "T lane-instructions/s",
-                         "frac": round(lane_ops / (t_h * 1e-3) / alu_peak, 4)},
-        }
+            def time_oracle(threads, budget_s):
+                oracle.set_num_threads(threads)
+                times = []
+                while True:                  # at least one run; repeat short ones (best of <= 15)
+                    t0 = time.perf_counter()
+                    scale = oracle.preclip_scales(sub, sub_off, lam)[0] if lam > 0.0 else None
+                    _, ito, _, _ = oracle.centered_clip(sub, sub_off, wl.tau, wl.eps, M, scale=scale)
+                    times.append(time.perf_counter() - t0)
+                    if sum(times) > budget_s or len(times) >= 15:
+                        break
+                oracle.set_num_threads(all_threads)
+                t_cpu = min(times)
+                cpu_bytes = 4.0 * n * sum((sub_off[j + 1] - sub_off[j]) * max(int(ito[j]), 0)
+                                          for j in range(k))
+                assert [int(x) for x in ito] == iters.cpu().tolist()[:k], \
+                    "oracle and GPU iteration counts differ"
+                return {
+                    "value": round(cpu_bytes / t_cpu / 1e9, 3), "unit": "GB/s",
+                    "cores": threads, "kind": "oracle",
+                    "sample": f"CenteredClip (no verification) on partitions 0..{k - 1} of {P} of "
+                              f"the same workload ({hi - lo} of {d} coordinates, all {n} peers, same "
+                              f"tau/eps/max_iters), best of {len(times)} runs: {t_cpu:.2f} s",
+                }
+            for threads in cpu_baseline:
+                key = "cpu_baseline" if threads in (0, all_threads) else f"cpu_baseline_{threads}_thread"
+                out[key] = time_oracle(threads if threads > 0 else all_threads,
+                                       10.0 if threads != 1 else 4.0)
+            del sub
+        return out
 
-    # ---- the oracle on the host cores, as a baseline only
-    if not args.no_cpu_baseline:
-        import oracle
-        k = int(max(1, min(P, 6.0e10 // max(2.0 * n * max(sizes) * M, 1))))
-        lo, hi = off[0], off[k]
-        sub = G[:, lo:hi].contiguous().cpu().numpy()
-        sub_off = [o - lo for o in off[: k + 1]]
-        times = []
-        while True:                      # at least one run; repeat short ones (best of <= 15)
-            t0 = time.perf_counter()
-            scale = oracle.preclip_scales(sub, sub_off, lam)[0] if lam > 0.0 else None
-            _, ito, _, _ = oracle.centered_clip(sub, sub_off, wl.tau, wl.eps, M, scale=scale)
-            times.append(time.perf_counter() - t0)
-            if sum(times) > 10.0 or len(times) >= 15:
-                break
-        t_cpu = min(times)
-        cpu_bytes = 4.0 * n * sum((sub_off[j + 1] - sub_off[j]) * max(int(ito[j]), 0)
-                                  for j in range(k))
-        out["cpu_baseline"] = {
-            "value": round(cpu_bytes / t_cpu / 1e9, 3), "unit": "GB/s",
-            "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"CenteredClip (no verification) on partitions 0..{k - 1} of {P} of the same "
-                      f"workload ({hi - lo} of {d} coordinates, all {n} peers, same tau/eps/"
-                      f"max_iters), best of {len(times)} runs: {t_cpu:.2f} s",
-        }
-        assert [int(x) for x in ito] == iters.cpu().tolist()[:k], \
-            "oracle and GPU iteration counts differ"
+    def fits(cfg):
+        name, n_c, d_c, _tau, _m = workloads._SHAPES[cfg]
+        free, _total = torch.cuda.mem_get_info()
+        return free >= 4.0 * n_c * d_c * 1.08 + (2 << 30)
 
+    def measured(*a):
+        r = measure(*a)
+        gc.collect()                      # (the slab and the outputs of this configuration)
+        torch.cuda.empty_cache()
+        return r
+
+    cpu = [] if args.no_cpu_baseline else [0]
+    if args.config:
+        out = measured(args.config, args.steps, args.warmup, False,
+                       cpu + ([1] if cpu and args.config == 1 else []))
+    else:
+        # the largest configuration that fits this GPU is the headline ...
+        head = next((c for c in (5, 4, 3, 2, 1) if fits(c)), 1)
+        out = measured(head, args.steps, args.warmup, False, cpu)
+        # ... and the others follow in short (same recipe, fewer steps)
+        if not args.no_per_config:
+            keys = ("value", "ms_per_step", "physical", "roofline", "kernels", "segments_ms")
+            per = {}
+            for c in (1, 2, 3, 4, 5):
+                if c == head or not fits(c):
+                    continue
+                r = measured(c, max(4, args.steps // 2), max(2, args.warmup), True,
+                             [1] if (c == 1 and cpu) else [])
+                e = {"workload": r["config"]["workload"],
+                     "iters_min": r["config"].get("iters_min"), "iters_max": r["config"].get("iters_max"),
+                     "mode": r["config"].get("mode")}
+                e.update({k: r[k] for k in keys if k in r})
+                if "streaming" in r:
+                    e["streaming"] = {k: r["streaming"][k] for k in ("ms_per_step", "roofline")}
+                for k in r:
+                    if k.startswith("cpu_baseline"):
+                        e[k] = r[k]
+                per[f"cfg{c}"] = e
+            out["per_config"] = per
     print(json.dumps(out), flush=True)
     return 0
 

@@ -189,9 +189,10 @@ typedef struct btard_cc_problem {
  * colsum) is that of the clipped rows.  g itself is not modified: the factors are applied
  * as the data is read.  They come from the diagonal of the Gram matrix with
  * BTARD_FLAG_GRAM (no extra pass), else from one extra pass over g in btard_cc_begin.
- * Where a kernel forms g~ explicitly it does so as a peer holding fp32 tensors would:
- * factor rounded to fp32, one fp32 multiplication per element.  v0 must be NULL (the
- * iteration starts at the mean of the clipped rows).
+ * The factors are fp64 and g~ is the exact product alpha * g (fp32 value widened to fp64,
+ * one fused multiply-add per residual): nothing is rounded to fp32 on the way.  With
+ * v0 == NULL the iteration starts at the mean of the clipped rows; a start vector is taken
+ * as given (it is not clipped).
  */
 /*
  * Clipping radii per iteration: eq. (CenteredClip) is written with tau_l, which App. D.2,
@@ -247,6 +248,26 @@ int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
                              double *colsum, float *delta, int64_t ldd,
                              void *workspace, size_t workspace_bytes,
                              void *stream, uint32_t flags);
+
+/*
+ * The same quantities for PRE-CLIPPED rows (BTARD-Clipped-SGD, App. E.3, Alg. 9 line 3 with
+ * Alg. 6 lines 6-12): a peer that receives an aggregate v of clipped gradients and verifies
+ * it without having run CenteredClip itself.  Everything is that of the rows
+ * g~_i[j] = alpha_ij g_i[j]; g is not modified.  The factors are either the caller's
+ * (factors_in: DEVICE, n * parts doubles, entry (i, j) at i * parts + j; lambda is then
+ * ignored) or, with factors_in == NULL, alpha_ij = min{1, lambda / ||g_i[j]||_2} from the
+ * radius 0 < lambda < +INF, which costs one more pass over g for the norms.  factors_out
+ * (DEVICE, n * parts doubles, or NULL) receives the factors that were used.  Other
+ * arguments, outputs, workspace and errors as btard_verify_projections.
+ */
+int btard_verify_projections_preclipped(const float *g, int64_t ldg, int32_t n, int64_t d,
+                                        const int64_t *offsets_host, int32_t parts,
+                                        const float *v, float lambda, const double *factors_in,
+                                        float tau, uint64_t seed, double *norms,
+                                        double *weights, double *proj, double *colsum,
+                                        float *delta, int64_t ldd, double *factors_out,
+                                        void *workspace, size_t workspace_bytes, void *stream,
+                                        uint32_t flags);
 
 /*
  * CenteredClip and the verification quantities of its own result in one call:

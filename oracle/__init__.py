@@ -9,6 +9,7 @@ from .oracle import (  # noqa: F401
     coordinate_median,
     geometric_median,
     num_threads,
+    set_num_threads,
     philox4x32_10,
     preclip_scales,
     split,

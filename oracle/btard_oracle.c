@@ -62,6 +62,17 @@ int oracle_num_threads(void)
 #endif
 }
 
+/* Threads the coordinate loops use from now on (k >= 1); the arithmetic is    */
+/* untouched, only the order of the fp64 additions in the reductions changes. */
+void oracle_set_num_threads(int k)
+{
+#ifdef _OPENMP
+    if (k >= 1) omp_set_num_threads(k);
+#else
+    (void)k;
+#endif
+}
+
 /* ------------------------------------------------------------------------ */
 /* Split(v, n): App. D.1.  The first (d mod parts) parts have ceil(d/parts)   */
 /* entries, the others floor(d/parts).  off has parts+1 entries.             */

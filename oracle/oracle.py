@@ -37,6 +37,8 @@ def _load():
     c = ctypes
     P = c.POINTER
     lib.oracle_num_threads.restype = c.c_int
+    lib.oracle_set_num_threads.argtypes = [c.c_int]
+    lib.oracle_set_num_threads.restype = None
     lib.oracle_split.argtypes = [c.c_int64, c.c_int32, P(c.c_int64)]
     lib.oracle_split.restype = c.c_int
     lib.oracle_centered_clip.argtypes = [
@@ -99,6 +101,11 @@ def _load():
 
 def num_threads() -> int:
     return int(_load().oracle_num_threads())
+
+
+def set_num_threads(k: int) -> None:
+    """Threads the oracle's coordinate loops use from now on (for timing it on one core)."""
+    _load().oracle_set_num_threads(int(k))
 
 
 def _offsets(off: Sequence[int]):

@@ -138,6 +138,12 @@ def load_library():
         c.c_void_p, c.c_float, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_void_p, c.c_int64, c.c_void_p, c.c_size_t, c.c_void_p, c.c_uint32]
     lib.btard_verify_projections.restype = c.c_int
+    lib.btard_verify_projections_preclipped.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.POINTER(c.c_int64), c.c_int32,
+        c.c_void_p, c.c_float, c.c_void_p, c.c_float, c.c_uint64, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_size_t,
+        c.c_void_p, c.c_uint32]
+    lib.btard_verify_projections_preclipped.restype = c.c_int
     lib.btard_debug_zhat.argtypes = [c.c_uint64, c.c_int64, c.c_int64, c.c_void_p, c.c_void_p]
     lib.btard_debug_zhat.restype = c.c_int
     _lib = lib
@@ -522,6 +528,43 @@ def verify_projections(g: torch.Tensor, offsets: Sequence[int], v: torch.Tensor,
     return out
 
 
+def verify_projections_preclipped(g: torch.Tensor, offsets: Sequence[int], v: torch.Tensor,
+                                  tau: float, seed: int, lam: float = 0.0,
+                                  factors: Optional[torch.Tensor] = None,
+                                  want_delta: bool = False,
+                                  workspace: Optional[torch.Tensor] = None,
+                                  out: Optional[dict] = None) -> dict:
+    """btard_verify_projections_preclipped: the factors are `factors` ([n, P] fp64) if given,
+    else those of the radius `lam`.  Returns dict(norms, weights, proj, colsum, delta,
+    factors = the factors used)."""
+    n, d = int(g.shape[0]), int(g.shape[1])
+    P = len(offsets) - 1
+    dev = g.device
+    if out is None:
+        out = {}
+    for key in ("norms", "weights", "proj", "factors"):
+        if key not in out:
+            out[key] = torch.empty((n, P), dtype=torch.float64, device=dev)
+    if "colsum" not in out:
+        out["colsum"] = torch.empty(P, dtype=torch.float64, device=dev)
+    if want_delta and out.get("delta") is None:
+        out["delta"] = torch.empty((n, d), dtype=torch.float32, device=dev)
+    delta = out.get("delta") if want_delta else None
+    if workspace is None:
+        workspace = alloc_workspace(n, P, dev)
+    if factors is not None:
+        assert factors.dtype == torch.float64 and factors.is_contiguous()
+        assert tuple(factors.shape) == (n, P)
+    rc = load_library().btard_verify_projections_preclipped(
+        _ptr(g), _row_stride(g), n, d, _off_array(offsets), P, _ptr(v), float(lam),
+        _ptr(factors), float(tau), int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(out["norms"]),
+        _ptr(out["weights"]), _ptr(out["proj"]), _ptr(out["colsum"]), _ptr(delta),
+        _row_stride(delta) if delta is not None else 0, _ptr(out["factors"]), _ptr(workspace),
+        workspace.numel(), _stream_ptr(dev), BTARD_FLAG_NONE)
+    _check(rc, "btard_verify_projections_preclipped")
+    return out
+
+
 def debug_zhat(seed: int, x_begin: int, count: int, device) -> torch.Tensor:
     out = torch.empty(count, dtype=torch.float32, device=device)
     rc = load_library().btard_debug_zhat(int(seed) & 0xFFFFFFFFFFFFFFFF, int(x_begin),
@@ -545,6 +588,7 @@ btard_debug_last_pass = debug_last_pass
 btard_cc_iterate = cc_iterate
 btard_cc_finish = cc_finish
 btard_verify_projections = verify_projections
+btard_verify_projections_preclipped = verify_projections_preclipped
 btard_cc_finish_verify = cc_finish_verify
 btard_centered_clip_verify = centered_clip_verify
 btard_cc_preclip_factors = cc_preclip_factors

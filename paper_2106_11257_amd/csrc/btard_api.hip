@@ -12,12 +12,9 @@
 #include <utility>
 #include <vector>
 
-#include "cc_kernels.h"
-#include "fused_kernels.h"
+#include "dispatch.h"
 #include "gram_kernels.h"
 #include "hash_kernels.h"
-#include "median_kernels.h"
-#include "verify_kernels.h"
 
 namespace btard {
 namespace {
@@ -104,8 +101,6 @@ CcState carve_cc(void *ws, int32_t n, int32_t P)
 }
 
 // ---- kernel variants: peers per lane group (NP) x lane groups per wavefront (LG)
-enum Variant { V4x1, V8x1, V16x1, V16x2, V16x4, V16x8, V16x16, kVariants };
-
 Variant pick_variant(int32_t n)
 {
     if (n <= 4) return V4x1;
@@ -127,60 +122,6 @@ int variant_tile_width(Variant v)
         default: return Geo<16, 1>::kW;
     }
 }
-
-typedef void (*CcPassFn)(CcArgs);
-typedef void (*CcFinishFn)(CcFinishArgs);
-typedef void (*VerifyFn)(VerifyArgs);
-typedef void (*FusedFn)(FusedArgs);
-
-// [variant][ragged: n < NP*LG][has v0]
-#define BTARD_PASS_ROW(NP, LG)                                                                  \
-    {{cc_pass_kernel<NP, LG, false, false, false>, cc_pass_kernel<NP, LG, false, true, false>},  \
-     {cc_pass_kernel<NP, LG, true, false, false>, cc_pass_kernel<NP, LG, true, true, false>}}
-const CcPassFn kCcPass[kVariants][2][2] = {
-    BTARD_PASS_ROW(4, 1),  BTARD_PASS_ROW(8, 1),  BTARD_PASS_ROW(16, 1), BTARD_PASS_ROW(16, 2),
-    BTARD_PASS_ROW(16, 4), BTARD_PASS_ROW(16, 8), BTARD_PASS_ROW(16, 16)};
-#undef BTARD_PASS_ROW
-// with pre-clipping factors (never with a start vector)  [variant][ragged]
-#define BTARD_PASS_S(NP, LG) \
-    {cc_pass_kernel<NP, LG, false, false, true>, cc_pass_kernel<NP, LG, true, false, true>}
-const CcPassFn kCcPassScaled[kVariants][2] = {
-    BTARD_PASS_S(4, 1),  BTARD_PASS_S(8, 1),  BTARD_PASS_S(16, 1), BTARD_PASS_S(16, 2),
-    BTARD_PASS_S(16, 4), BTARD_PASS_S(16, 8), BTARD_PASS_S(16, 16)};
-#undef BTARD_PASS_S
-#define BTARD_CC_ROW(K, NP, LG)                                                   \
-    {{K<NP, LG, false, false>, K<NP, LG, false, true>},                           \
-     {K<NP, LG, true, false>, K<NP, LG, true, true>}}
-const CcFinishFn kCcFinish[kVariants][2][2] = {
-    BTARD_CC_ROW(cc_finish_kernel, 4, 1),  BTARD_CC_ROW(cc_finish_kernel, 8, 1),
-    BTARD_CC_ROW(cc_finish_kernel, 16, 1), BTARD_CC_ROW(cc_finish_kernel, 16, 2),
-    BTARD_CC_ROW(cc_finish_kernel, 16, 4), BTARD_CC_ROW(cc_finish_kernel, 16, 8),
-    BTARD_CC_ROW(cc_finish_kernel, 16, 16)};
-#undef BTARD_CC_ROW
-#define BTARD_V_ROW(NP, LG) {verify_pass_kernel<NP, LG, false>, verify_pass_kernel<NP, LG, true>}
-const VerifyFn kVerify[kVariants][2] = {BTARD_V_ROW(4, 1),  BTARD_V_ROW(8, 1),  BTARD_V_ROW(16, 1),
-                                        BTARD_V_ROW(16, 2), BTARD_V_ROW(16, 4), BTARD_V_ROW(16, 8),
-                                        BTARD_V_ROW(16, 16)};
-#undef BTARD_V_ROW
-// [scaled: with pre-clipping factors][variant][ragged]
-#define BTARD_F_ROW(NP, LG, S) \
-    {cc_finish_verify_kernel<NP, LG, false, S>, cc_finish_verify_kernel<NP, LG, true, S>}
-const FusedFn kFused[2][kVariants][2] = {
-    {BTARD_F_ROW(4, 1, false), BTARD_F_ROW(8, 1, false), BTARD_F_ROW(16, 1, false),
-     BTARD_F_ROW(16, 2, false), BTARD_F_ROW(16, 4, false), BTARD_F_ROW(16, 8, false),
-     BTARD_F_ROW(16, 16, false)},
-    {BTARD_F_ROW(4, 1, true), BTARD_F_ROW(8, 1, true), BTARD_F_ROW(16, 1, true),
-     BTARD_F_ROW(16, 2, true), BTARD_F_ROW(16, 4, true), BTARD_F_ROW(16, 8, true),
-     BTARD_F_ROW(16, 16, true)}};
-#undef BTARD_F_ROW
-
-typedef void (*MedianFn)(MedianArgs);
-#define BTARD_M_ROW(NP, LG) \
-    {coordinate_median_kernel<NP, LG, false>, coordinate_median_kernel<NP, LG, true>}
-const MedianFn kMedian[kVariants][2] = {BTARD_M_ROW(4, 1),  BTARD_M_ROW(8, 1),  BTARD_M_ROW(16, 1),
-                                        BTARD_M_ROW(16, 2), BTARD_M_ROW(16, 4), BTARD_M_ROW(16, 8),
-                                        BTARD_M_ROW(16, 16)};
-#undef BTARD_M_ROW
 
 int variant_peers(Variant v)
 {
@@ -299,7 +240,6 @@ int check_problem(const btard_cc_problem *p)
             if (!(p->tau_schedule[l] > 0.0f)) return BTARD_ERR_INVALID_ARG;
     }
     if (!(p->preclip >= 0.0f)) return BTARD_ERR_INVALID_ARG;             // NaN or negative
-    if (preclip_on(p) && p->v0) return BTARD_ERR_INVALID_ARG;            // clipped rows start at their mean
     return check_workspace(p->workspace, p->workspace_bytes, p->n, p->parts);
 }
 
@@ -342,6 +282,11 @@ size_t btard_workspace_bytes(int32_t n, int32_t parts)
 
 static bool gram_applies(const btard_cc_problem *p);
 static int pass_blocks(const btard_cc_problem *p, Variant var, int ragged, int based);
+static int launch_verification(const float *g, int64_t ldg, int32_t n, const int64_t *offsets_host,
+                               int32_t parts, const float *v, float tau, uint64_t seed,
+                               double *norms, double *weights, double *proj, double *colsum,
+                               float *delta, int64_t ldd, const CcState &st, bool scaled,
+                               hipStream_t s);
 
 int btard_cc_begin(const btard_cc_problem *p)
 {
@@ -383,9 +328,9 @@ int btard_cc_begin(const btard_cc_problem *p)
         a.g = p->g; a.ld = p->ldg; a.n = p->n; a.v0 = nullptr;
         a.tau = (double)p->tau; a.eps = (double)p->eps; a.max_iters = p->max_iters;
         a.prev_blocks = B; a.pass = 0; a.scaled = 0; a.rule = kRuleCenteredClip; a.st = st;
-        hipLaunchKernelGGL(kCcPass[var][ragged][0], dim3(B, P), dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL(cc_pass_fn(var, ragged, false, false), dim3(B, P), dim3(kBlock), 0, s, a);
         hipLaunchKernelGGL(preclip_scales_kernel, dim3(P), dim3(kBlock), 0, s, st, p->n, B,
-                           (double)p->preclip, p->max_iters);
+                           (double)p->preclip, p->max_iters, p->v0 ? 1 : 0);
     }
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
@@ -552,7 +497,7 @@ int btard_debug_gram(const btard_cc_problem *p, double *gram_out)
 // Workgroups per partition of the pass kernel for this problem (the same in every pass).
 static int pass_blocks(const btard_cc_problem *p, Variant var, int ragged, int based)
 {
-    const CcPassFn fn = preclip_on(p) ? kCcPassScaled[var][ragged] : kCcPass[var][ragged][based];
+    const CcPassFn fn = cc_pass_fn(var, ragged, based, preclip_on(p));
     const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
     if (resident <= 0) return 0;
     return blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
@@ -567,7 +512,7 @@ int btard_cc_iterate(const btard_cc_problem *p, int32_t first_iteration, int32_t
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     const Variant var = pick_variant(p->n);
     const int ragged = p->n < variant_peers(var) ? 1 : 0, based = p->v0 ? 1 : 0;
-    const CcPassFn fn = preclip_on(p) ? kCcPassScaled[var][ragged] : kCcPass[var][ragged][based];
+    const CcPassFn fn = cc_pass_fn(var, ragged, based, preclip_on(p));
     const int B = pass_blocks(p, var, ragged, based);
     if (B <= 0) return BTARD_ERR_DEVICE;
     CcArgs a;
@@ -592,7 +537,7 @@ int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     const Variant var = pick_variant(p->n);
     const int ragged = p->n < variant_peers(var) ? 1 : 0, based = p->v0 ? 1 : 0;
-    const CcFinishFn fn = kCcFinish[var][ragged][based];
+    const CcFinishFn fn = cc_finish_fn(var, ragged, based);
     const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
     if (resident <= 0) return BTARD_ERR_DEVICE;
     const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
@@ -656,7 +601,7 @@ static int launch_fused_pass(const btard_cc_problem *p, int32_t iterations, floa
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     const Variant var = pick_variant(p->n);
     const int ragged = p->n < variant_peers(var) ? 1 : 0;
-    const FusedFn fn = kFused[preclip_on(p) ? 1 : 0][var][ragged];
+    const FusedFn fn = fused_pass_fn(var, ragged, preclip_on(p));
     const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
     if (resident <= 0) return BTARD_ERR_DEVICE;
     const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
@@ -689,13 +634,13 @@ int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float 
     if (!v || !iters || iterations < 0 || !norms || !weights || !proj) return BTARD_ERR_INVALID_ARG;
     if ((p->flags & BTARD_FLAG_GEOMETRIC_MEDIAN) != 0) return BTARD_ERR_INVALID_ARG;
     if (p->v0) {
-        // with a caller-supplied start vector: the two separate passes
+        // with a caller-supplied start vector: the two separate passes (the offsets and, with
+        // pre-clipping, the factors are in the workspace already)
         const int r1 = btard_cc_finish(p, iterations, v, iters, last_step_norm);
         if (r1 != BTARD_OK) return r1;
-        return btard_verify_projections(p->g, p->ldg, p->n, p->d, p->offsets_host, p->parts, v,
-                                        p->tau, seed, norms, weights, proj, colsum, nullptr, 0,
-                                        p->workspace, p->workspace_bytes, p->stream,
-                                        BTARD_FLAG_NONE);
+        return launch_verification(p->g, p->ldg, p->n, p->offsets_host, p->parts, v, p->tau, seed,
+                                   norms, weights, proj, colsum, nullptr, 0, carve_problem(p),
+                                   preclip_on(p), static_cast<hipStream_t>(p->stream));
     }
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     int B = 0;
@@ -782,7 +727,7 @@ int btard_coordinate_median(const float *g, int64_t ldg, int32_t n, int64_t d, f
     if (!g || !v) return BTARD_ERR_INVALID_ARG;
     const Variant var = pick_variant(n);
     const int ragged = n < variant_peers(var) ? 1 : 0;
-    const MedianFn fn = kMedian[var][ragged];
+    const MedianFn fn = median_fn(var, ragged);
     const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
     if (resident <= 0) return BTARD_ERR_DEVICE;
     const int64_t whole[2] = {0, d};
@@ -995,6 +940,52 @@ int btard_centered_clip_verify_preclipped(const float *g, int64_t ldg, int32_t n
     return factors ? btard_cc_preclip_factors(&p, factors) : BTARD_OK;
 }
 
+// The verification pass, its finish and (optionally) the Delta pass on an aggregate v.
+// scaled: the rows are taken times the factors in the workspace (st.scale), which the caller
+// of this function has put there on the same stream.
+static int launch_verification(const float *g, int64_t ldg, int32_t n, const int64_t *offsets_host,
+                               int32_t parts, const float *v, float tau, uint64_t seed,
+                               double *norms, double *weights, double *proj, double *colsum,
+                               float *delta, int64_t ldd, const CcState &st, bool scaled,
+                               hipStream_t s)
+{
+    const Variant var = pick_variant(n);
+    const int ragged = n < variant_peers(var) ? 1 : 0;
+    const VerifyFn vfn = verify_pass_fn(var, ragged, scaled);
+    const int resident = resident_blocks(reinterpret_cast<const void *>(vfn));
+    if (resident <= 0) return BTARD_ERR_DEVICE;
+    const int B = blocks_per_partition(resident, parts, offsets_host, variant_tile_width(var));
+
+    VerifyArgs a;
+    a.g = g; a.ld = ldg; a.n = n; a.v = v; a.seed = seed; a.off = st.off;
+    a.partial = st.partial; a.S = 2 * n + 1;
+    a.scale = scaled ? st.scale : nullptr; a.R = st.R;
+    hipLaunchKernelGGL(vfn, dim3(B, parts), dim3(kBlock), 0, s, a);
+
+    VerifyFinishArgs f;
+    f.partial = st.partial; f.n = n; f.P = parts; f.B = B; f.S = a.S; f.tau = (double)tau;
+    f.norms = norms; f.weights = weights; f.proj = proj; f.colsum = colsum;
+    f.report = 0; f.state_iters = nullptr; f.report_buf = nullptr;
+    f.iters_out = nullptr; f.step_norm_out = nullptr;
+    hipLaunchKernelGGL(verify_finish_kernel, dim3(parts), dim3(kFinishThreads), 0, s, f);
+
+    if (delta) {
+        DeltaArgs da;
+        da.g = g; da.ld = ldg; da.n = n; da.P = parts; da.v = v; da.off = st.off;
+        da.weights = weights; da.delta = delta; da.ldd = ldd;
+        da.scale = scaled ? st.scale : nullptr; da.R = st.R;
+        int64_t max_len = 1;
+        for (int32_t j = 0; j < parts; ++j)
+            if (offsets_host[j + 1] - offsets_host[j] > max_len)
+                max_len = offsets_host[j + 1] - offsets_host[j];
+        int64_t bx = (max_len / kVec + 2 + kBlock - 1) / kBlock;
+        const int64_t cap = (kMaxBlocks * 4) / parts > 0 ? (kMaxBlocks * 4) / parts : 1;
+        if (bx > cap) bx = cap;
+        hipLaunchKernelGGL(delta_kernel, dim3((unsigned)bx, parts), dim3(kBlock), 0, s, da);
+    }
+    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+}
+
 int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
                              const int64_t *offsets_host, int32_t parts, const float *v,
                              float tau, uint64_t seed, double *norms, double *weights,
@@ -1013,40 +1004,44 @@ int btard_verify_projections(const float *g, int64_t ldg, int32_t n, int64_t d,
     CcState st = carve_cc(workspace, n, parts);
     const int up = upload_offsets(offsets_host, parts, st.off, s);
     if (up != BTARD_OK) return up;
+    return launch_verification(g, ldg, n, offsets_host, parts, v, tau, seed, norms, weights, proj,
+                               colsum, delta, ldd, st, false, s);
+}
 
-    const Variant var = pick_variant(n);
-    const int ragged = n < variant_peers(var) ? 1 : 0;
-    const VerifyFn vfn = kVerify[var][ragged];
-    const int resident = resident_blocks(reinterpret_cast<const void *>(vfn));
-    if (resident <= 0) return BTARD_ERR_DEVICE;
-    const int B = blocks_per_partition(resident, parts, offsets_host, variant_tile_width(var));
+int btard_verify_projections_preclipped(const float *g, int64_t ldg, int32_t n, int64_t d,
+                                        const int64_t *offsets_host, int32_t parts,
+                                        const float *v, float lambda, const double *factors_in,
+                                        float tau, uint64_t seed, double *norms, double *weights,
+                                        double *proj, double *colsum, float *delta, int64_t ldd,
+                                        double *factors_out, void *workspace,
+                                        size_t workspace_bytes, void *stream, uint32_t flags)
+{
+    if (!basic_args_ok(g, ldg, n, d, offsets_host, parts)) return BTARD_ERR_INVALID_ARG;
+    if (!v || !norms || !weights || !proj || !(tau > 0.0f) || flags != BTARD_FLAG_NONE)
+        return BTARD_ERR_INVALID_ARG;
+    if (delta && (ldd < d || overlaps(delta, v, d))) return BTARD_ERR_INVALID_ARG;
+    // the factors: the caller's, or from the radius (one pass over g for the rows' norms)
+    if (!factors_in && !(lambda > 0.0f && std::isfinite(lambda))) return BTARD_ERR_INVALID_ARG;
+    const int wrc = check_workspace(workspace, workspace_bytes, n, parts);
+    if (wrc != BTARD_OK) return wrc;
 
-    VerifyArgs a;
-    a.g = g; a.ld = ldg; a.n = n; a.v = v; a.seed = seed; a.off = st.off;
-    a.partial = st.partial; a.S = 2 * n + 1;
-    hipLaunchKernelGGL(vfn, dim3(B, parts), dim3(kBlock), 0, s, a);
-
-    VerifyFinishArgs f;
-    f.partial = st.partial; f.n = n; f.P = parts; f.B = B; f.S = a.S; f.tau = (double)tau;
-    f.norms = norms; f.weights = weights; f.proj = proj; f.colsum = colsum;
-    f.report = 0; f.state_iters = nullptr; f.report_buf = nullptr;
-    f.iters_out = nullptr; f.step_norm_out = nullptr;
-    hipLaunchKernelGGL(verify_finish_kernel, dim3(parts), dim3(kFinishThreads), 0, s, f);
-
-    if (delta) {
-        DeltaArgs da;
-        da.g = g; da.ld = ldg; da.n = n; da.P = parts; da.v = v; da.off = st.off;
-        da.weights = weights; da.delta = delta; da.ldd = ldd;
-        int64_t max_len = 1;
-        for (int32_t j = 0; j < parts; ++j)
-            if (offsets_host[j + 1] - offsets_host[j] > max_len)
-                max_len = offsets_host[j + 1] - offsets_host[j];
-        int64_t bx = (max_len / kVec + 2 + kBlock - 1) / kBlock;
-        const int64_t cap = (kMaxBlocks * 4) / parts > 0 ? (kMaxBlocks * 4) / parts : 1;
-        if (bx > cap) bx = cap;
-        hipLaunchKernelGGL(delta_kernel, dim3((unsigned)bx, parts), dim3(kBlock), 0, s, da);
-    }
-    return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    btard_cc_problem p;
+    p.g = g; p.ldg = ldg; p.n = n; p.d = d; p.offsets_host = offsets_host; p.parts = parts;
+    p.tau = tau; p.eps = 0.0f; p.max_iters = 0; p.v0 = nullptr;
+    p.workspace = workspace; p.workspace_bytes = workspace_bytes; p.stream = stream;
+    p.flags = BTARD_FLAG_NONE; p.preclip = factors_in ? 0.0f : lambda; p.tau_schedule = nullptr;
+    // (uploads the offsets; with a radius also measures the norms and leaves the factors in
+    // the workspace)
+    const int rb = btard_cc_begin(&p);
+    if (rb != BTARD_OK) return rb;
+    const CcState st = carve_problem(&p);
+    if (factors_in)
+        hipLaunchKernelGGL(preclip_import_kernel, dim3(parts), dim3(64), 0, s, st, n, factors_in);
+    if (factors_out)
+        hipLaunchKernelGGL(preclip_export_kernel, dim3(parts), dim3(64), 0, s, st, n, factors_out);
+    return launch_verification(g, ldg, n, offsets_host, parts, v, tau, seed, norms, weights, proj,
+                               colsum, delta, ldd, st, true, s);
 }
 
 int btard_debug_zhat(uint64_t seed, int64_t x_begin, int64_t count, float *out, void *stream)

@@ -86,13 +86,13 @@ struct DblChunk {
     double v[kOffChunk];
 };
 
-__global__ void upload_doubles_kernel(double *dst, int32_t first, int32_t count, DblChunk chunk)
+static __global__ void upload_doubles_kernel(double *dst, int32_t first, int32_t count, DblChunk chunk)
 {
     const int t = threadIdx.x;
     if (t < count) dst[first + t] = chunk.v[t];
 }
 
-__global__ void upload_offsets_kernel(int64_t *off, int32_t first, int32_t count, OffChunk chunk)
+static __global__ void upload_offsets_kernel(int64_t *off, int32_t first, int32_t count, OffChunk chunk)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < count) off[first + t] = chunk.v[t];
@@ -101,7 +101,7 @@ __global__ void upload_offsets_kernel(int64_t *off, int32_t first, int32_t count
 // One launch per chunk of offsets: workgroup b sets up partition first + b (if there is
 // one: the last chunk entry may be the end offset only), workgroup 0 also stores the chunk.
 // zero_start: all coefficients 0 (v^0 = 0), for the pass that measures the rows' own norms.
-__global__ __launch_bounds__(kOffChunk) void cc_begin_kernel(CcState st, int32_t n, int32_t has_v0,
+static __global__ __launch_bounds__(kOffChunk) void cc_begin_kernel(CcState st, int32_t n, int32_t has_v0,
                                                              int32_t max_iters, int32_t first,
                                                              int32_t count, int32_t zero_start,
                                                              OffChunk chunk)
@@ -217,15 +217,6 @@ __device__ __forceinline__ bool control_step(const CcState &st, int j, int n, do
     __syncthreads();
     *iters_out = it;
     return dn != 0;
-}
-
-// A workgroup-uniform double held in LDS -> scalar registers.
-__device__ __forceinline__ double uniform_double(double x)
-{
-    const uint64_t b = (uint64_t)__double_as_longlong(x);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
 }
 
 // This lane group's coefficients out of LDS.
@@ -573,7 +564,7 @@ struct CcReportArgs {
     double *step_norm_out;   // may be null
 };
 
-__global__ __launch_bounds__(kBlock) void cc_report_kernel(CcReportArgs a)
+static __global__ __launch_bounds__(kBlock) void cc_report_kernel(CcReportArgs a)
 {
     __shared__ double s_red[kBlock];
     const int j = blockIdx.x;
@@ -590,12 +581,14 @@ __global__ __launch_bounds__(kBlock) void cc_report_kernel(CcReportArgs a)
 // pre-clipping factors (BTARD-Clipped-SGD, App. E.3, Alg. 9 line 3 and the text after the
 // algorithm): alpha_ij = min{1, lambda / ||g_i[j]||}.  The norms come from one ordinary pass
 // started at v^0 = 0 (cc_begin_kernel with zero_start), whose partial sums this kernel
-// reduces; it then sets the coefficients to the real start (the mean of the clipped rows).
+// reduces; it then sets the coefficients to the real start (the caller's vector, else the
+// mean of the clipped rows).
 // One workgroup per partition.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void preclip_scales_kernel(CcState st, int32_t n,
-                                                                int32_t blocks, double lambda,
-                                                                int32_t max_iters)
+static __global__ __launch_bounds__(kBlock) void preclip_scales_kernel(CcState st, int32_t n,
+                                                                       int32_t blocks, double lambda,
+                                                                       int32_t max_iters,
+                                                                       int32_t has_v0)
 {
     __shared__ double s_red[kBlock];
     const int j = blockIdx.x, R = st.R, t = threadIdx.x;
@@ -608,7 +601,8 @@ __global__ __launch_bounds__(kBlock) void preclip_scales_kernel(CcState st, int3
             al = (N <= lambda) ? 1.0 : lambda / N;      // (a non-finite norm gives a NaN factor,
         }                                               //  which the first real pass reports)
         st.scale[(int64_t)j * R + t] = al;
-        st.coef[(int64_t)j * R + t] = (t < n) ? 1.0 / (double)n : 0.0;
+        // the real start: the caller's vector, else the mean of the clipped rows
+        st.coef[(int64_t)j * R + t] = has_v0 ? ((t == n) ? 1.0 : 0.0) : ((t < n) ? 1.0 / (double)n : 0.0);
     }
     if (t == 0) {                                   // (the norm pass ran with a cap of >= 1)
         st.done[j] = (max_iters <= 0) ? 1 : 0;
@@ -617,15 +611,22 @@ __global__ __launch_bounds__(kBlock) void preclip_scales_kernel(CcState st, int3
 }
 
 // the factors for the caller: out[i * P + j] = alpha_ij
-__global__ void preclip_export_kernel(CcState st, int32_t n, double *out)
+static __global__ void preclip_export_kernel(CcState st, int32_t n, double *out)
 {
     const int j = blockIdx.x;
     for (int i = threadIdx.x; i < n; i += blockDim.x) out[(int64_t)i * st.P + j] = st.scale[(int64_t)j * st.R + i];
 }
 
+// the caller's factors into the workspace: scale[j * R + i] = in[i * P + j]
+static __global__ void preclip_import_kernel(CcState st, int32_t n, const double *in)
+{
+    const int j = blockIdx.x;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) st.scale[(int64_t)j * st.R + i] = in[(int64_t)i * st.P + j];
+}
+
 // Verification 3 of Alg. 6: check_ij = [norm_ij > Delta_max], votes per partition and the
 // strict-majority trigger of CheckAveraging.  One thread per partition.
-__global__ void verification3_kernel(const double *norms, int32_t n, int32_t P, double delta_max,
+static __global__ void verification3_kernel(const double *norms, int32_t n, int32_t P, double delta_max,
                                      uint8_t *check, int32_t *votes, uint8_t *trigger)
 {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -645,7 +646,7 @@ __global__ void verification3_kernel(const double *norms, int32_t n, int32_t P, 
 // (or is NaN); the broadcast projections of a partition "do not sum to zero" when
 // |sum_i s_ij| > atol + rtol sum_i |s_ij| (summed over i = 0 .. n-1 in order).  One thread per
 // partition.
-__global__ void verification12_kernel(const double *claimed_norms, const double *claimed_proj,
+static __global__ void verification12_kernel(const double *claimed_norms, const double *claimed_proj,
                                       const double *norms, const double *proj, int32_t n,
                                       int32_t P, double rtol, double atol, uint8_t *bad_norm,
                                       uint8_t *bad_proj, uint8_t *bad_sum)

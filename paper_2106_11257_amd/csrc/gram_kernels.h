@@ -852,6 +852,12 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
     double al = 0.0;
     int it = a.fresh ? 0 : a.st.iters[j];
     int dn = a.fresh ? 0 : a.st.done[j];
+    // A row with an Inf or a NaN in it has a non-finite squared norm Gamma_ii (and only such
+    // a row has: squares of fp32 values cannot overflow fp64), and then its residual norm
+    // is not finite at any v: the partition is reported with iters = -1, as the
+    // per-iteration passes do.  (The clamps at zero below would otherwise swallow a NaN:
+    // fmax returns its other operand.)
+    if (!dn && __any(peer && !isfinite(diag))) { it = -1; dn = 1; }
     double ev = 0.0;                          // bound on the error put into v so far
 
     // y = Gamma c, qv = c^T Gamma c and Sc = sum_i |c_i| ||g_i|| travel with c: after an
@@ -865,12 +871,14 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         // (tau_l of eq. (5) if the caller gave a schedule)
         const double tau = (a.st.has_sched && it < kMaxSchedule) ? s_tau[it] : a.tau;
         // norms, weights and how wrong the weights may be
-        const double N2 = fmax(diag - 2.0 * y + qv, 0.0);
+        const double N2raw = diag - 2.0 * y + qv;
+        // (tested before the clamp: fmax(NaN, 0) is 0)
+        if (__any(peer && !isfinite(N2raw))) { it = -1; dn = 1; break; }
+        const double N2 = fmax(N2raw, 0.0);
         const double eN2 = kGramUnit * (rt + Sc) * (rt + Sc);
         // ||g_i - v|| = N2 / sqrt(N2) and tau / ||g_i - v|| from one reciprocal square root
         const double rs = rsqrt_newton(N2);
-        const double Nn = (N2 > 0.0) ? N2 * rs : N2;              // (0, or NaN as it comes)
-        if (__any(peer && !isfinite(Nn))) { it = -1; dn = 1; break; }
+        const double Nn = (N2 > 0.0) ? N2 * rs : 0.0;
         double w = 0.0, err_w = 0.0;
         if (peer) {
             w = (Nn <= tau) ? 1.0 : tau * rs;

@@ -1,5 +1,8 @@
 // Device-side building blocks shared by the gfx950 kernels: tile geometry,
 // row loads that tolerate 4-byte alignment, wavefront (64-lane) reductions.
+// The kernel headers are included by several translation units (one per family of
+// instantiations); kernels that are not templates are therefore declared static, and only
+// the unit that launches one keeps its code.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -370,6 +373,31 @@ struct TileStage {
 // emitted).  Used between the two sweeps over a tile so that the fp32 values are
 // converted to fp64 again in the second sweep instead of keeping 2x the registers live.
 __device__ __forceinline__ void forget(float &x) { asm volatile("" : "+v"(x)); }
+
+// A workgroup-uniform double (the same in every lane) -> scalar registers.
+__device__ __forceinline__ double uniform_double(double x)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+// Pre-clipping factors alpha_ij of this lane group's peers for one partition (scale_j: the
+// partition's n factors; a null pointer or an absent peer gives 1).  With one lane group the
+// factors are wavefront-uniform and live in scalar registers.
+template <int NP, int LG, bool RAGGED>
+__device__ __forceinline__ void fetch_scale_factors(const double *__restrict__ scale_j, int n, int lg,
+                                                    double (&al)[NP])
+{
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const int i = lg * NP + k;
+        const bool have = scale_j != nullptr && (!RAGGED || i < n);
+        const double f = have ? scale_j[have ? i : 0] : 1.0;
+        al[k] = (LG == 1) ? uniform_double(f) : f;
+    }
+}
 
 // Sum over the lanes of one lane group (xor masks below LANES) ...
 template <int LANES>

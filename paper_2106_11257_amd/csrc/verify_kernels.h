@@ -48,7 +48,7 @@ __device__ __forceinline__ void zhat_block(uint64_t seed, int64_t q, float (&z)[
     }
 }
 
-__global__ void zhat_debug_kernel(uint64_t seed, int64_t x_begin, int64_t count, float *out)
+static __global__ void zhat_debug_kernel(uint64_t seed, int64_t x_begin, int64_t count, float *out)
 {
     const int64_t q0 = x_begin / 4;
     const int64_t nq = (x_begin + count + 3) / 4 - q0;
@@ -73,14 +73,19 @@ struct VerifyArgs {
     const int64_t *off;      // [P+1] device copy
     double *partial;         // [P][B][S], S = 2n + 1: n norms^2, n <zhat, r_i>, |zhat|^2
     int32_t S;
+    // SCALED kernels only: pre-clipping factors alpha_ij at scale[j * R + i] (BTARD-Clipped-SGD,
+    // App. E.3): the residuals are those of the rows alpha_ij g_i[j]
+    const double *scale;
+    int32_t R;
 };
 
 // One tile of the verification pass; INTERIOR as in fused_tile: a straight-line body for
 // tiles wholly inside the partition, a guarded one for its first and last tile.
-template <int NP, int LG, bool RAGGED, bool INTERIOR>
+template <int NP, int LG, bool RAGGED, bool INTERIOR, bool SCALED>
 __device__ __forceinline__ void verify_tile(const float *__restrict__ g, int64_t ld, int n,
                                             const float *__restrict__ v, uint64_t seed, int lg,
                                             int sub, int64_t xu, int64_t lo, int64_t hi,
+                                            const double (&al)[NP],
                                             double (&accN)[NP], double (&accR)[NP], double &z2)
 {
     const int64_t x0 = xu + (int64_t)sub * kVec;               // a multiple of 4
@@ -103,7 +108,9 @@ __device__ __forceinline__ void verify_tile(const float *__restrict__ g, int64_t
     for (int k = 0; k < NP; ++k) {
 #pragma unroll
         for (int e = 0; e < kVec; ++e) {
-            const double r = (double)val[k][e] - vv[e];
+            double r;
+            if constexpr (SCALED) r = fma(al[k], (double)val[k][e], -vv[e]);
+            else r = (double)val[k][e] - vv[e];
             accN[k] = fma(r, r, accN[k]);
             accR[k] = fma(z[e], r, accR[k]);
         }
@@ -116,9 +123,10 @@ __device__ __forceinline__ void verify_tile(const float *__restrict__ g, int64_t
 
 // The arithmetic of an interior tile whose rows (val) and slice of v (vf) are already in
 // registers.
-template <int NP, int LG>
+template <int NP, int LG, bool SCALED>
 __device__ __forceinline__ void verify_rows(uint64_t seed, int lg, int sub, int64_t xu,
                                             float (&val)[NP][4], float (&vf)[4],
+                                            const double (&al)[NP],
                                             double (&accN)[NP], double (&accR)[NP], double &z2)
 {
     const int64_t x0 = xu + (int64_t)sub * kVec;               // a multiple of 4
@@ -136,7 +144,9 @@ __device__ __forceinline__ void verify_rows(uint64_t seed, int lg, int sub, int6
 #pragma unroll
         for (int e = 0; e < kVec; ++e) {
             forget(val[k][e]);   // converted here, row by row; also keeps this after the loads
-            const double r = (double)val[k][e] - vv[e];
+            double r;
+            if constexpr (SCALED) r = fma(al[k], (double)val[k][e], -vv[e]);
+            else r = (double)val[k][e] - vv[e];
             accN[k] = fma(r, r, accN[k]);
             accR[k] = fma(z[e], r, accR[k]);
         }
@@ -147,7 +157,8 @@ __device__ __forceinline__ void verify_rows(uint64_t seed, int lg, int sub, int6
     }
 }
 
-template <int NP, int LG, bool RAGGED>
+// SCALED: on pre-clipped rows (the factors cost registers the plain variant does not pay for).
+template <int NP, int LG, bool RAGGED, bool SCALED>
 __global__ __launch_bounds__(kBlock, 2) void verify_pass_kernel(VerifyArgs a)
 {
     using G = Geo<NP, LG>;
@@ -163,6 +174,8 @@ __global__ __launch_bounds__(kBlock, 2) void verify_pass_kernel(VerifyArgs a)
 #pragma unroll
     for (int k = 0; k < NP; ++k) { accN[k] = 0.0; accR[k] = 0.0; }
     double z2 = 0.0;
+    double al[NP];
+    if constexpr (SCALED) fetch_scale_factors<NP, LG, RAGGED>(a.scale + (int64_t)j * a.R, n, lg, al);
 
     // interior tiles first ...
     const TileRange tr = tile_range<G::kW>(lo, hi);
@@ -170,7 +183,12 @@ __global__ __launch_bounds__(kBlock, 2) void verify_pass_kernel(VerifyArgs a)
     // before the arithmetic of the current one, so that memory requests are in flight all
     // the time and not only while the wavefront waits.
     const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
-    if (iw.begin < iw.end) {
+    if constexpr (SCALED && LG > 1) {
+        // (the factors live in vector registers here and a second register set does not fit)
+        for (int64_t u = iw.begin; u < iw.end; u += tr.stride)
+            verify_tile<NP, LG, RAGGED, true, SCALED>(a.g, a.ld, n, a.v, a.seed, lg, sub,
+                                                      tr.xa + u * G::kW, lo, hi, al, accN, accR, z2);
+    } else if (iw.begin < iw.end) {
         float va[NP][4], vb[NP][4], fa[4], fb[4];
         int64_t u = iw.begin;
         load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u * G::kW, lo, hi, true, va);
@@ -182,7 +200,7 @@ __global__ __launch_bounds__(kBlock, 2) void verify_pass_kernel(VerifyArgs a)
             if (u1 >= iw.end) break;                 // the last tile is in (va, fa)
             load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u1 * G::kW, lo, hi, true, vb);
             load_row4_vec(a.v + tr.xa + u1 * G::kW + sub * kVec, fb);
-            verify_rows<NP, LG>(a.seed, lg, sub, tr.xa + u * G::kW, va, fa, accN, accR, z2);
+            verify_rows<NP, LG, SCALED>(a.seed, lg, sub, tr.xa + u * G::kW, va, fa, al, accN, accR, z2);
             const int64_t u2 = u1 + tr.stride;
             if (u2 >= iw.end) {                      // the last tile is in (vb, fb): move it
 #pragma unroll
@@ -197,10 +215,10 @@ __global__ __launch_bounds__(kBlock, 2) void verify_pass_kernel(VerifyArgs a)
             }
             load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, tr.xa + u2 * G::kW, lo, hi, true, va);
             load_row4_vec(a.v + tr.xa + u2 * G::kW + sub * kVec, fa);
-            verify_rows<NP, LG>(a.seed, lg, sub, tr.xa + u1 * G::kW, vb, fb, accN, accR, z2);
+            verify_rows<NP, LG, SCALED>(a.seed, lg, sub, tr.xa + u1 * G::kW, vb, fb, al, accN, accR, z2);
             u = u2;
         }
-        verify_rows<NP, LG>(a.seed, lg, sub, tr.xa + u * G::kW, va, fa, accN, accR, z2);
+        verify_rows<NP, LG, SCALED>(a.seed, lg, sub, tr.xa + u * G::kW, va, fa, al, accN, accR, z2);
     }
     sum_within_group_all<G::kLanes, NP>(accN);
     sum_within_group_all<G::kLanes, NP>(accR);
@@ -226,8 +244,8 @@ __global__ __launch_bounds__(kBlock, 2) void verify_pass_kernel(VerifyArgs a)
             if ((t == 1 && tr.units < 2) || !owns_tile(tr, u)) continue;
             const int64_t xu = tr.xa + u * G::kW;
             if (tile_is_interior<G::kW>(xu, lo, hi)) continue;
-            verify_tile<NP, LG, RAGGED, false>(a.g, a.ld, n, a.v, a.seed, lg, sub, xu, lo, hi, eN,
-                                               eR, ez2);
+            verify_tile<NP, LG, RAGGED, false, SCALED>(a.g, a.ld, n, a.v, a.seed, lg, sub, xu, lo,
+                                                       hi, al, eN, eR, ez2);
             any = true;
         }
         if (any) {
@@ -276,7 +294,7 @@ struct VerifyFinishArgs {
 // partial sums in a fixed order (each workgroup repeats that small sum).
 constexpr int kFinishThreads = 1024;
 
-__global__ __launch_bounds__(kFinishThreads) void verify_finish_kernel(VerifyFinishArgs a)
+static __global__ __launch_bounds__(kFinishThreads) void verify_finish_kernel(VerifyFinishArgs a)
 {
     const int j = blockIdx.x;
     const int n = a.n, P = a.P, B = a.B, S = a.S;
@@ -333,10 +351,13 @@ struct DeltaArgs {
     const double *weights;   // [n][P]
     float *delta;
     int64_t ldd;
+    const double *scale;     // pre-clipping factors at scale[j * R + i], or null: the rows as given
+    int32_t R;
 };
 
-// Delta_i^j = w_ij (g_i[j] - v[j]), one pass: read n + 1 rows, write n rows.
-__global__ __launch_bounds__(kBlock) void delta_kernel(DeltaArgs a)
+// Delta_i^j = w_ij (g_i[j] - v[j]) (of the rows alpha_ij g_i[j] if factors are given), one
+// pass: read n + 1 rows, write n rows.
+static __global__ __launch_bounds__(kBlock) void delta_kernel(DeltaArgs a)
 {
     const int j = blockIdx.y;
     const int64_t lo = a.off[j], hi = a.off[j + 1];
@@ -351,12 +372,13 @@ __global__ __launch_bounds__(kBlock) void delta_kernel(DeltaArgs a)
         else load_row4_guarded(a.v, x0, lo, hi, vf);
         for (int i = 0; i < a.n; ++i) {
             const double w = a.weights[(int64_t)i * a.P + j];
+            const double al = a.scale ? a.scale[(int64_t)j * a.R + i] : 1.0;
             float gv[4];
             if (full) load_row4_vec(a.g + (int64_t)i * a.ld + x0, gv);
             else load_row4_guarded(a.g + (int64_t)i * a.ld, x0, lo, hi, gv);
             float o[4];
 #pragma unroll
-            for (int e = 0; e < kVec; ++e) o[e] = (float)(w * ((double)gv[e] - (double)vf[e]));
+            for (int e = 0; e < kVec; ++e) o[e] = (float)(w * fma(al, (double)gv[e], -(double)vf[e]));
             float *dst = a.delta + (int64_t)i * a.ldd;
             if (full) {
                 f32x4_u t;

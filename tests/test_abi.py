@@ -124,6 +124,16 @@ def test_argument_errors_are_caught_on_the_host_before_any_gpu_call():
     assert vp(delta=ctypes.c_void_p(0x2000000), ldd=4) == -1
     assert vp(wsb=8) == -2
 
+    def vpp(g=fake, v=fake, lam=1.0, fac=None, tau=1.0, wsb=big):
+        return lib.btard_verify_projections_preclipped(g, 8, 2, 8, off, 2, v, lam, fac, tau, 1, fake,
+                                                       fake, fake, None, None, 0, None, ws, wsb,
+                                                       None, 0)
+
+    assert vpp(g=None) == -1 and vpp(v=None) == -1 and vpp(tau=0.0) == -1
+    # neither factors nor a usable radius
+    assert vpp(lam=0.0) == -1 and vpp(lam=float("inf")) == -1 and vpp(lam=float("nan")) == -1
+    assert vpp(wsb=8) == -2 and vpp(lam=0.0, fac=fake, wsb=8) == -2
+
 
 def test_binding_constants_match_the_header():
     """The flag and limit values of the Python binding are those of include/btard.h."""

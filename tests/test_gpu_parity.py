@@ -242,14 +242,38 @@ def test_converging_partitions_stop_at_the_oracles_iteration(dev):
         assert np.abs(cs).max() < 1e-4 * np.abs(out["proj"].cpu().numpy()).max()
 
 
-def test_nonfinite_input_is_flagged_per_partition(dev):
-    G, off = workloads.generic_case(6, 2000, 4, seed=9, device=dev)
+@pytest.mark.parametrize("n", [6, 16, 40])
+@pytest.mark.parametrize("flags", [0, 1, 3])          # none, GRAM, GRAM | HOST_SYNC
+@pytest.mark.parametrize("eps", [1e-6, 0.0])
+@pytest.mark.parametrize("poison", ["inf", "-inf", "nan"])
+def test_nonfinite_input_is_flagged_per_partition(dev, n, flags, eps, poison):
+    """Reading R10: a partition whose residual norms are not finite reports iters = -1, on
+    every path (per-iteration passes, Gram iteration, fused last pass); the other
+    partitions are independent problems and must come out exactly as without the poison."""
+    G, off = workloads.generic_case(n, 2000, 4, seed=9, device=dev)
+    M, tau, seed = 10, 1.0, 77
+    clean = btard.centered_clip_verify(G, off, tau, eps, M, seed, flags=flags)
     G = G.clone()
-    G[2, off[1] + 5] = float("inf")
-    v, iters, sn = btard.centered_clip(G, off, 1.0, 1e-6, 10)
+    G[2, off[1] + 5] = float(poison)
+    say(f"[nonfinite] n={n} flags={flags} eps={eps} poison={poison}")
+    v, iters, sn = btard.centered_clip(G, off, tau, eps, M, flags=flags)
+    v2, iters2, sn2, out2 = btard.centered_clip_verify(G, off, tau, eps, M, seed, flags=flags)
     torch.cuda.synchronize()
-    it = iters.cpu().numpy()
-    assert it[1] == -1 and (it[[0, 2, 3]] > 0).all()
+    others = [0, 2, 3]
+    for it in (iters.cpu().numpy(), iters2.cpu().numpy()):
+        assert it[1] == -1, it
+        assert (it[others] == clean[1].cpu().numpy()[others]).all() and (it[others] > 0).all()
+    for j in others:
+        lo, hi = off[j], off[j + 1]
+        assert torch.equal(v[lo:hi], clean[0][lo:hi]) and torch.equal(v2[lo:hi], clean[0][lo:hi])
+        assert torch.equal(sn2[j], clean[2][j])
+        for k in ("norms", "weights"):
+            assert torch.equal(out2[k][:, j], clean[3][k][:, j]), k
+    # (the projections of the other partitions share |zhat| with every partition; it does not
+    # depend on the data, only -- in its last bits -- on which body of the last pass summed
+    # the poisoned partition's share of it)
+    np.testing.assert_allclose(out2["proj"][:, others].cpu().numpy(),
+                               clean[3]["proj"][:, others].cpu().numpy(), rtol=1e-12, atol=0.0)
 
 
 def test_results_are_bit_reproducible(dev):
@@ -393,7 +417,7 @@ def test_gram_last_pass_without_waiting_for_the_iteration(dev):
                                    (5, 1_600_016)])
 def test_gram_path_configs_reduced_length(dev, cfg, d):
     wl = workloads.make_workload(cfg, device=dev, d=d)
-    check_cc(wl.G, wl.offsets, wl.tau, wl.eps, wl.max_iters, label=wl.name,
+    check_cc(wl.G, config_offsets(wl), wl.tau, wl.eps, wl.max_iters, label=wl.name,
              flags=btard.BTARD_FLAG_GRAM)
 
 
@@ -508,9 +532,90 @@ def test_preclipped_gram_hand_over_and_phased_calls(dev):
     vo, ito, _, _ = oracle.centered_clip(G.cpu().numpy(), off, 1e-3, 1e-6, 40, scale=alpha)
     np.testing.assert_array_equal(iters.cpu().numpy(), ito)
     assert rel_l2(v.cpu().numpy(), vo) <= V_TOL
-    with pytest.raises(btard.BtardError):        # a start vector and pre-clipping do not go together
-        btard.cc_begin(btard.make_problem(G, off, 1.0, 1e-6, 5, v0=torch.zeros(20000, device=dev),
-                                          preclip=lam))
+
+
+@pytest.mark.parametrize("n,d,P,pad", [(3, 1031, 2, 0), (9, 5000, 4, 2), (16, 70001, 16, 0),
+                                       (16, 262147, 3, 5), (33, 2000, 3, 1), (64, 20000, 64, 0),
+                                       (130, 700, 2, 0)])
+def test_verify_projections_of_preclipped_rows(dev, n, d, P, pad):
+    """App. E.3 with Alg. 6 lines 6-12: a peer that receives an aggregate of pre-clipped rows
+    verifies it without running CenteredClip: the stand-alone call with the radius (norm pass
+    inside) and with the caller's factors, incl. Delta, against the oracle on scaled rows."""
+    G, off = workloads.generic_case(n, d, P, seed=7 * n + d, device=dev, ld=d + pad, spread=0.05,
+                                    outliers=max(1, n // 4), outlier_scale=30.0)
+    Gh = G.cpu().numpy()
+    norms = np.linalg.norm(Gh.astype(np.float64)[:, off[0]:off[1]], axis=1)
+    lam = float(np.float32(np.sqrt(norms.min() * norms.max())))
+    tau, seed = 0.7, 0xE3
+    alpha, _ = oracle.preclip_scales(Gh, off, lam)
+    assert (alpha < 1.0).any() and (alpha == 1.0).any()
+    # some aggregate (here: what CenteredClip on the clipped rows returns after 3 updates)
+    vo, _, _, _ = oracle.centered_clip(Gh, off, tau, 0.0, 3, scale=alpha)
+    v = torch.tensor(vo, dtype=torch.float32, device=dev)
+    vh = v.cpu().numpy().astype(np.float64)
+    ref = oracle.verify(Gh, off, vh, tau, seed, scale=alpha, want_delta=True)
+    say(f"[verify preclipped] n={n} d={d} P={P} lambda={lam}")
+    by_radius = btard.verify_projections_preclipped(G, off, v, tau, seed, lam=lam, want_delta=True)
+    by_factors = btard.verify_projections_preclipped(
+        G, off, v, tau, seed, factors=torch.tensor(alpha, dtype=torch.float64, device=dev),
+        want_delta=True)
+    torch.cuda.synchronize()
+    for got in (by_radius, by_factors):
+        np.testing.assert_allclose(got["factors"].cpu().numpy(), alpha, rtol=1e-12)
+        np.testing.assert_allclose(got["norms"].cpu().numpy(), ref["norms"], rtol=SCALAR_TOL, atol=1e-30)
+        np.testing.assert_allclose(got["weights"].cpu().numpy(), ref["weights"], rtol=SCALAR_TOL)
+        assert rel_l2(got["proj"].cpu().numpy(), ref["proj"]) <= PROJ_TOL
+        cs = got["colsum"].cpu().numpy()
+        assert np.abs(cs - ref["colsum"]).max() <= PROJ_TOL * np.abs(ref["proj"]).sum(axis=0).max()
+        dl = got["delta"].cpu().numpy()
+        for j in range(P):
+            lo, hi = off[j], off[j + 1]
+            for i in range(n):
+                assert rel_l2(dl[i, lo:hi], ref["delta"][i, lo:hi]) <= 1e-6, f"delta row {i} part {j}"
+    # a radius above every norm: the plain call's results, bit for bit
+    plain = btard.verify_projections(G, off, v, tau, seed)
+    none = btard.verify_projections_preclipped(G, off, v, tau, seed, lam=1e30)
+    torch.cuda.synchronize()
+    assert (none["factors"] == 1.0).all()
+    for k in ("norms", "weights", "proj", "colsum"):
+        assert torch.equal(none[k], plain[k]), k
+    with pytest.raises(btard.BtardError):          # neither a radius nor factors
+        btard.verify_projections_preclipped(G, off, v, tau, seed)
+
+
+@pytest.mark.parametrize("n,d,P,pad", [(5, 1000, 7, 13), (16, 70001, 16, 0), (40, 9000, 4, 3)])
+def test_preclipped_rows_with_a_start_vector(dev, n, d, P, pad):
+    """Pre-clipping and a caller's start vector together (phased calls; the vector is taken
+    as given), CenteredClip and the verification quantities against the oracle."""
+    G, off = workloads.generic_case(n, d, P, seed=900 + n, device=dev, ld=d + pad, spread=0.05,
+                                    outliers=max(1, n // 4), outlier_scale=30.0)
+    Gh = G.cpu().numpy()
+    norms = np.linalg.norm(Gh.astype(np.float64)[:, off[0]:off[1]], axis=1)
+    lam = float(np.float32(np.sqrt(norms.min() * norms.max())))
+    tau, eps, M, seed = 0.5, 1e-6, 25, 31
+    gen = torch.Generator(device=dev); gen.manual_seed(n)
+    v0 = (G[0] + 0.01 * torch.randn(d, generator=gen, device=dev)).contiguous()
+    alpha, _ = oracle.preclip_scales(Gh, off, lam)
+    vo, ito, sno, _ = oracle.centered_clip(Gh, off, tau, eps, M, scale=alpha,
+                                           v0=v0.cpu().numpy().astype(np.float64))
+    for flags in (0, btard.BTARD_FLAG_GRAM):       # (with a start vector the Gram flag is ignored)
+        p = btard.make_problem(G, off, tau, eps, M, v0=v0, preclip=lam, flags=flags)
+        btard.cc_begin(p); btard.cc_gram(p)
+        btard.cc_iterate(p, 0, M)
+        v, iters, sn, out = btard.cc_finish_verify(p, M, seed)
+        fac = btard.cc_preclip_factors(p)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(fac.cpu().numpy(), alpha, rtol=1e-12)
+        np.testing.assert_array_equal(iters.cpu().numpy(), ito)
+        vh = v.cpu().numpy()
+        for j in range(P):
+            lo, hi = off[j], off[j + 1]
+            assert rel_l2(vh[lo:hi], vo[lo:hi]) <= V_TOL, f"partition {j}"
+        np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=SCALAR_TOL, atol=1e-11)
+        ref = oracle.verify(Gh, off, vh.astype(np.float64), tau, seed, scale=alpha)
+        np.testing.assert_allclose(out["norms"].cpu().numpy(), ref["norms"], rtol=SCALAR_TOL, atol=1e-30)
+        np.testing.assert_allclose(out["weights"].cpu().numpy(), ref["weights"], rtol=SCALAR_TOL)
+        assert rel_l2(out["proj"].cpu().numpy(), ref["proj"]) <= PROJ_TOL
 
 
 @pytest.mark.parametrize("cfg,d", [(2, 400_003), (4, 1 << 20), (3, 300_000)])
@@ -723,8 +828,9 @@ def test_verifications_1_and_2_flags(dev):
                                    (5, 1_600_016)])
 def test_configs_reduced_length(dev, cfg, d):
     wl = workloads.make_workload(cfg, device=dev, d=d)
-    v, iters, sn = check_cc(wl.G, wl.offsets, wl.tau, wl.eps, wl.max_iters, label=wl.name)
-    check_verify(wl.G, wl.offsets, v, wl.tau, wl.seed_z, want_delta=(cfg in (1, 2)), label=wl.name)
+    off = config_offsets(wl)
+    v, iters, sn = check_cc(wl.G, off, wl.tau, wl.eps, wl.max_iters, label=wl.name)
+    check_verify(wl.G, off, v, wl.tau, wl.seed_z, want_delta=(cfg in (1, 2)), label=wl.name)
 
 
 @pytest.mark.parametrize("cfg,d", [(2, 400_003), (3, 300_001)])
@@ -732,48 +838,110 @@ def test_configs_with_dense_rows(dev, cfg, d):
     """The same recipe with row stride = d (rows on 4-byte boundaries only), both paths."""
     wl = workloads.make_workload(cfg, device=dev, d=d, row_align=1)
     assert wl.G.stride(0) == d
-    v, iters, sn = check_cc(wl.G, wl.offsets, wl.tau, wl.eps, wl.max_iters, label=wl.name)
-    check_verify(wl.G, wl.offsets, v, wl.tau, wl.seed_z, label=wl.name)
-    check_cc(wl.G, wl.offsets, wl.tau, wl.eps, wl.max_iters, label=wl.name, flags=btard.BTARD_FLAG_GRAM)
+    off = config_offsets(wl)
+    v, iters, sn = check_cc(wl.G, off, wl.tau, wl.eps, wl.max_iters, label=wl.name)
+    check_verify(wl.G, off, v, wl.tau, wl.seed_z, label=wl.name)
+    check_cc(wl.G, off, wl.tau, wl.eps, wl.max_iters, label=wl.name, flags=btard.BTARD_FLAG_GRAM)
 
 
-FULL = [
-    # cfg, partitions the oracle recomputes (None = all)
-    (1, None),
-    (2, None),
-    (3, [0, 17, 63]),
-    (4, [0, 7]),
-    (5, [11]),
-]
+# Full size: every partition of every configuration against the oracle, on both paths.  A
+# configuration's slab is generated once and both GPU paths are run on it (first test of the
+# group); every partition then is a test of its own, so that a run shows its progress and no
+# single test is long: the partition's columns are copied to the host, the oracle computes
+# CenteredClip and the verification quantities on them, and the per-iteration path AND the
+# path the benchmark's headline times (Gram iteration where it applies, last pass fused with
+# the verification pass) are each compared with the ORACLE.
+_FULL = {}
 
 
-@pytest.mark.parametrize("cfg,sample", FULL)
-def test_configs_full_size(dev, cfg, sample):
+def _drop_full_run():
+    _FULL.clear()
+    torch.cuda.empty_cache()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _release_full_run():
+    yield
+    _drop_full_run()
+
+
+def config_offsets(wl):
+    """The partition offsets through the library's own Split (C ABI), checked against the
+    oracle's and the generator's."""
+    off = btard.split_offsets(wl.d, wl.parts)
+    assert off == [int(x) for x in oracle.split(wl.d, wl.parts)] == list(wl.offsets)
+    return off
+
+
+def full_run(dev, cfg):
+    run = _FULL.get("run")
+    if run is not None and run["cfg"] == cfg:
+        return run
+    _drop_full_run()
     free, total = torch.cuda.mem_get_info()
-    need = 4 * workloads._SHAPES[cfg][1] * workloads._SHAPES[cfg][2] * 1.25 + (2 << 30)
+    need = 4 * workloads._SHAPES[cfg][1] * workloads._SHAPES[cfg][2] * 1.1 + (2 << 30)
     if free < need:
         pytest.skip(f"needs {need / 2**30:.0f} GiB of device memory")
     wl = workloads.make_workload(cfg, device=dev)
+    off = config_offsets(wl)
     say(f"[full] {wl.name}: slab {wl.slab_bytes / 2**30:.2f} GiB generated")
-    # the per-iteration path and the two separate calls ...
-    v, iters, sn = check_cc(wl.G, wl.offsets, wl.tau, wl.eps, wl.max_iters, parts_to_check=sample,
-                            label=wl.name)
-    say(f"    iters = {iters.cpu().numpy().tolist()}")
-    out = check_verify(wl.G, wl.offsets, v, wl.tau, wl.seed_z, parts_to_check=sample, label=wl.name)
-    # ... and the path the benchmark's headline times (Gram iteration where it applies, one
-    # host synchronisation, last pass fused with the verification pass) must agree with them
-    F = btard.BTARD_FLAG_GRAM | btard.BTARD_FLAG_HOST_SYNC
-    v2, iters2, sn2, out2 = btard.centered_clip_verify(wl.G, wl.offsets, wl.tau, wl.eps,
-                                                       wl.max_iters, wl.seed_z, flags=F)
+    # the per-iteration path and the two separate calls
+    v, iters, sn = btard.centered_clip(wl.G, off, wl.tau, wl.eps, wl.max_iters)
+    out = btard.verify_projections(wl.G, off, v, wl.tau, wl.seed_z)
+    # the headline path, as bench.py runs it: nothing waits for the device; completeness is
+    # read back afterwards (and completed by passes if the Gram iteration handed over)
+    prob = btard.make_problem(wl.G, off, wl.tau, wl.eps, wl.max_iters,
+                              flags=btard.BTARD_FLAG_GRAM | btard.BTARD_FLAG_GRAM_BEGINS)
+    btard.cc_gram_matrix(prob)
+    btard.cc_gram_iterate(prob)
+    v2, iters2, sn2, out2 = btard.cc_finish_verify(prob, 0, wl.seed_z)
+    left = btard.cc_remaining(prob)
+    if left > 0:
+        btard.cc_iterate(prob, 0, left)
+        v2, iters2, sn2, out2 = btard.cc_finish_verify(prob, left, wl.seed_z)
     torch.cuda.synchronize()
-    assert torch.equal(iters, iters2)
-    vh, v2h = v.cpu().numpy(), v2.cpu().numpy()
-    for j in range(wl.parts):
-        lo, hi = wl.offsets[j], wl.offsets[j + 1]
-        assert rel_l2(v2h[lo:hi], vh[lo:hi]) <= 1e-6, f"partition {j}"
-    np.testing.assert_allclose(sn2.cpu().numpy(), sn.cpu().numpy(), rtol=1e-4, atol=1e-11)
-    a, b = out2["proj"].cpu().numpy(), out["proj"].cpu().numpy()
-    assert rel_l2(a, b) <= 1e-5
-    np.testing.assert_allclose(out2["norms"].cpu().numpy(), out["norms"].cpu().numpy(), rtol=1e-6)
-    del wl, v, v2
-    torch.cuda.empty_cache()
+    say(f"    iters = {iters.cpu().numpy().tolist()}; Gram iteration left {left} passes")
+    host = lambda t: t.cpu().numpy()
+    run = dict(cfg=cfg, wl=wl, off=off, left=left,
+               paths={"passes": dict(v=host(v), iters=host(iters), sn=host(sn),
+                                     out={k: host(t) for k, t in out.items() if t is not None}),
+                      "headline": dict(v=host(v2), iters=host(iters2), sn=host(sn2),
+                                       out={k: host(t) for k, t in out2.items() if t is not None})},
+               znorm=oracle.z_norm(wl.seed_z, wl.d),
+               stage=torch.empty((wl.n, max(off[j + 1] - off[j] for j in range(wl.parts))),
+                                 dtype=torch.float32, pin_memory=True))
+    del v, v2, out, out2
+    _FULL["run"] = run
+    return run
+
+
+FULL_CASES = [(cfg, j) for cfg in (1, 2, 3, 4, 5) for j in range(workloads._SHAPES[cfg][1])]
+
+
+@pytest.mark.parametrize("cfg,j", FULL_CASES)
+def test_configs_full_size_partition_against_the_oracle(dev, cfg, j):
+    run = full_run(dev, cfg)
+    wl, off = run["wl"], run["off"]
+    lo, hi = off[j], off[j + 1]
+    stage = run["stage"]
+    for i in range(wl.n):
+        stage[i, :hi - lo].copy_(wl.G[i, lo:hi], non_blocking=True)
+    torch.cuda.synchronize()
+    sub = stage.numpy()[:, :hi - lo]
+    vo, ito, sno, _ = oracle.centered_clip(sub, [0, hi - lo], wl.tau, wl.eps, wl.max_iters)
+    for name, got in run["paths"].items():
+        where = f"cfg {cfg} partition {j} ({name})"
+        assert got["iters"][j] == ito[0], where
+        assert rel_l2(got["v"][lo:hi], vo) <= V_TOL, where
+        assert got["sn"][j] == pytest.approx(sno[0], rel=SCALAR_TOL, abs=1e-11), where
+        # the verification quantities of the v that this path returned
+        ref = oracle.verify(sub, [0, hi - lo], got["v"][lo:hi].astype(np.float64), wl.tau,
+                            wl.seed_z, x_base=lo, znorm=run["znorm"])
+        o = got["out"]
+        assert rel_l2(o["proj"][:, j], ref["proj"][:, 0]) <= PROJ_TOL, where
+        np.testing.assert_allclose(o["norms"][:, j], ref["norms"][:, 0], rtol=SCALAR_TOL,
+                                   atol=1e-30, err_msg=where)
+        np.testing.assert_allclose(o["weights"][:, j], ref["weights"][:, 0], rtol=SCALAR_TOL,
+                                   err_msg=where)
+        scale = np.abs(ref["proj"][:, 0]).sum()
+        assert abs(o["colsum"][j] - ref["colsum"][0]) <= PROJ_TOL * scale + 1e-300, where
