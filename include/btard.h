@@ -289,6 +289,31 @@ int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d
                                double *colsum, void *workspace,
                                size_t workspace_bytes, void *stream, uint32_t flags);
 
+/*
+ * btard_centered_clip_verify for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The workspace is an array of BTARD_NOALLOC_SCRATCH_BYTES inside the library
+ * (one copy per device, held until the process ends); inputs and outputs are still the
+ * caller's.  The call allocates nothing and does not synchronise.
+ *   - Limit: btard_workspace_bytes(n, parts) <= BTARD_NOALLOC_SCRATCH_BYTES (n <= 16 peers and
+ *     up to about 2000 partitions; any d); beyond it the call returns BTARD_ERR_WORKSPACE
+ *     before anything is enqueued.
+ *   - flags: BTARD_FLAG_NONE or BTARD_FLAG_GRAM (BTARD_FLAG_HOST_SYNC is refused: nothing in
+ *     here waits for the device).
+ *   - All calls on one device share that device's array, whatever their stream: calls that
+ *     overlap in time on one device race.  Order them on one stream (or by events).  The
+ *     array keeps the previous call's contents; every call sets up the state it reads.
+ * Results are those of btard_centered_clip_verify with a workspace of the caller's, bit for
+ * bit.
+ */
+#define BTARD_NOALLOC_SCRATCH_BYTES (12u << 20)
+int btard_centered_clip_verify_noalloc(const float *g, int64_t ldg, int32_t n, int64_t d,
+                                       const int64_t *offsets_host, int32_t parts, float tau,
+                                       float eps, int32_t max_iters, const float *v0, float *v,
+                                       int32_t *iters, double *last_step_norm, uint64_t seed,
+                                       double *norms, double *weights, double *proj,
+                                       double *colsum, void *stream, uint32_t flags);
+
 /* The same for the phased interface: btard_cc_finish + btard_verify_projections. */
 int btard_cc_finish_verify(const btard_cc_problem *p, int32_t iterations, float *v,
                            int32_t *iters, double *last_step_norm, uint64_t seed,

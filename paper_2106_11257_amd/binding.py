@@ -101,6 +101,11 @@ def load_library():
         c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t,
         c.c_void_p, c.c_uint32]
     lib.btard_centered_clip_verify.restype = c.c_int
+    lib.btard_centered_clip_verify_noalloc.argtypes = [
+        c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.POINTER(c.c_int64), c.c_int32,
+        c.c_float, c.c_float, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_uint32]
+    lib.btard_centered_clip_verify_noalloc.restype = c.c_int
     lib.btard_geometric_median.argtypes = [
         c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.POINTER(c.c_int64), c.c_int32,
         c.c_float, c.c_float, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
@@ -363,6 +368,24 @@ def centered_clip_verify(g: torch.Tensor, offsets: Sequence[int], tau: float, ep
     return v, iters, last_step_norm, out
 
 
+def centered_clip_verify_noalloc(g: torch.Tensor, offsets: Sequence[int], tau: float, eps: float,
+                                 max_iters: int, seed: int, v: torch.Tensor, iters: torch.Tensor,
+                                 last_step_norm: torch.Tensor, out: dict,
+                                 v0: Optional[torch.Tensor] = None,
+                                 flags: int = BTARD_FLAG_NONE) -> None:
+    """btard_centered_clip_verify_noalloc: every buffer is the caller's (v [d] fp32, iters [P]
+    int32, last_step_norm [P] fp64, out = dict(norms, weights, proj [n, P], colsum [P]) fp64);
+    nothing is allocated here either."""
+    n, d = int(g.shape[0]), int(g.shape[1])
+    P = len(offsets) - 1
+    rc = load_library().btard_centered_clip_verify_noalloc(
+        _ptr(g), _row_stride(g), n, d, _off_array(offsets), P, float(tau), float(eps),
+        int(max_iters), _ptr(v0), _ptr(v), _ptr(iters), _ptr(last_step_norm),
+        int(seed) & 0xFFFFFFFFFFFFFFFF, _ptr(out["norms"]), _ptr(out["weights"]),
+        _ptr(out["proj"]), _ptr(out["colsum"]), _stream_ptr(g.device), int(flags))
+    _check(rc, "btard_centered_clip_verify_noalloc")
+
+
 def geometric_median(g: torch.Tensor, offsets: Sequence[int], nu: float, eps: float,
                      max_iters: int, v0: Optional[torch.Tensor] = None,
                      workspace: Optional[torch.Tensor] = None):
@@ -591,6 +614,7 @@ btard_verify_projections = verify_projections
 btard_verify_projections_preclipped = verify_projections_preclipped
 btard_cc_finish_verify = cc_finish_verify
 btard_centered_clip_verify = centered_clip_verify
+btard_centered_clip_verify_noalloc = centered_clip_verify_noalloc
 btard_cc_preclip_factors = cc_preclip_factors
 btard_tau_schedule = tau_schedule
 btard_hash_workspace_bytes = hash_workspace_bytes

@@ -698,6 +698,50 @@ int btard_centered_clip_verify(const float *g, int64_t ldg, int32_t n, int64_t d
                                   colsum);
 }
 
+// ---- the entry point that allocates nothing: its workspace is this array.  Every device the
+// library runs on holds its own copy at its own address; host code uses the address that
+// hipGetSymbolAddress returns for the current device, never the array's name.
+static __device__ __align__(256) unsigned char scratch[BTARD_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices];        // per device, set on the first call there
+
+// Address of `scratch` on the current device (nullptr on failure).
+void *scratch_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int btard_centered_clip_verify_noalloc(const float *g, int64_t ldg, int32_t n, int64_t d,
+                                       const int64_t *offsets_host, int32_t parts, float tau,
+                                       float eps, int32_t max_iters, const float *v0, float *v,
+                                       int32_t *iters, double *last_step_norm, uint64_t seed,
+                                       double *norms, double *weights, double *proj,
+                                       double *colsum, void *stream, uint32_t flags)
+{
+    // (no synchronisation and no read-back in here: the look BTARD_FLAG_HOST_SYNC permits
+    // is not available)
+    if ((flags & ~(uint32_t)BTARD_FLAG_GRAM) != 0) return BTARD_ERR_INVALID_ARG;
+    if (n < 1 || n > kMaxPeers || parts < 1 || parts > kMaxParts) return BTARD_ERR_INVALID_ARG;
+    if (ws_layout(n, parts).total > (size_t)BTARD_NOALLOC_SCRATCH_BYTES) return BTARD_ERR_WORKSPACE;
+    void *ws = scratch_on_current_device();
+    if (!ws) return BTARD_ERR_DEVICE;
+    return btard_centered_clip_verify(g, ldg, n, d, offsets_host, parts, tau, eps, max_iters, v0, v,
+                                      iters, last_step_norm, seed, norms, weights, proj, colsum, ws,
+                                      (size_t)BTARD_NOALLOC_SCRATCH_BYTES, stream, flags);
+}
+
 int btard_geometric_median(const float *g, int64_t ldg, int32_t n, int64_t d,
                            const int64_t *offsets_host, int32_t parts, float nu, float eps,
                            int32_t max_iters, const float *v0, float *v, int32_t *iters,
