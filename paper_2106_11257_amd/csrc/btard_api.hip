@@ -23,6 +23,7 @@ constexpr int kMaxPeers = 255;
 constexpr int kMaxParts = 65535;
 constexpr int kMaxBlocks = 4096;      // workgroups per launch the partial-sum area is sized for
 constexpr size_t kAlign = 256;
+constexpr int kMinTilesPerWave = 4;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -181,7 +182,11 @@ int blocks_per_partition(int resident, int32_t P, const int64_t *off, int tile_w
     int64_t B = resident / P;
     const int64_t cap_ws = kMaxBlocks / P;
     if (B > cap_ws) B = cap_ws;
-    const int64_t cap_work = (max_units + kWaves - 1) / kWaves;
+    // (at least kMinTilesPerWave tiles per wavefront: on small slabs fewer, longer-lived
+    // workgroups cost less than the start-up of many -- dispatch, the control step's sums over
+    // all workgroups' partial results, the first loads' latency.  Measured on a 64 MiB slab
+    // with 16 partitions: 25.0 us per pass with 1 tile, 17.8 with 2, 17.4 with 4, 18.6 with 6.)
+    const int64_t cap_work = (max_units + kWaves * kMinTilesPerWave - 1) / (kWaves * kMinTilesPerWave);
     if (B > cap_work) B = cap_work;
     if (B < 1) B = 1;
     return (int)B;
@@ -360,6 +365,10 @@ static GramFn gram_kernel(const btard_cc_problem *p)
 {
     if (p->n < 8) return gram_pass_band_kernel<8, true>;
     if (p->n == 8) return gram_pass_band_kernel<8, false>;
+#ifdef BTARD_GRAM16_BAND
+    if (p->n < kGramPeers) return gram_pass_band_kernel<16, true>;
+    if (p->n == kGramPeers) return gram_pass_band_kernel<16, false>;
+#endif
     if (p->n < kGramPeers) return gram_pass_kernel<true>;
     if (p->n == kGramPeers) return gram_pass_kernel<false>;
     switch (gram_peer_blocks(p)) {
@@ -385,7 +394,11 @@ static int gram_blocks(const btard_cc_problem *p)
     const int resident = resident_blocks(reinterpret_cast<const void *>(gram_kernel(p)));
     if (resident <= 0) return 0;
     // n <= 8: a workgroup's wavefronts share its 256-coordinate tiles, i.e. 64 per wavefront
+#ifdef BTARD_GRAM16_BAND
+    const int tile = 64;
+#else
     const int tile = p->n <= 8 ? 64 : (p->n <= kGramPeers ? 256 : 64);
+#endif
     return blocks_per_partition(resident, p->parts, p->offsets_host, tile);
 }
 

@@ -62,42 +62,41 @@ __device__ __forceinline__ void gram_partition_range(const GramArgs &a, int j, i
 // matrix is symmetric, so which of the two is "row" is immaterial).
 __device__ __forceinline__ int gram_entry(int lane, int r) { return ((lane >> 4) + 4 * r) * kGramPeers + (lane & 15); }
 
-// x of the lane 4 s positions to the left in the same row of 16 lanes, cyclically
-// (DPP row_ror: lane t receives from lane (t - 4 s) mod 16).
-template <int S>
-__device__ __forceinline__ double row_rotate4(double x)
-{
-    const uint64_t b = (uint64_t)__double_as_longlong(x);
-    // (every lane receives a value, so there is no "old" register to preserve)
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)b, 0x120 + 4 * S, 0xf, 0xf, false);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(b >> 32), 0x120 + 4 * S, 0xf, 0xf, false);
-    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
-}
-
 // 8 < n <= 16.  In the matrix instructions' operands lane (p = lane % 16, q = lane / 16)
 // holds peer p's value of one coordinate: in the 16 coordinates 16 s .. 16 s + 15 of a tile
 // the lane owns 4 q .. 4 q + 3 and feeds them, one at a time, to v_mfma_f64_4x4x4_4b_f64.
 // That instruction multiplies four independent 4 x 4 blocks: block b's first operand is
 // held by lanes 16 k + 4 b + i (row i, k-slot k), its second by lanes 16 k + 4 b + j, and its
 // result D[b][i][j] by lane 16 i + 4 b + j (checked on the device; the tests compare the
-// matrix with a plain product).  With the lane's value as BOTH operands, block b is the
-// 4 x 4 diagonal block of Gamma for peers 4 b .. 4 b + 3; with the second operand rotated by
-// 4 or 8 lanes within the 16, block b pairs peers 4 b .. with peers 4 (b - 1) .. or
-// 4 (b - 2) ..: three instructions per 4 coordinates form the 10 distinct 4 x 4 blocks of the
-// symmetric matrix (and 2 of them twice), 768 multiply-adds where one 16 x 16 x 4
-// instruction spends 1024 -- and the small instruction issues every 17 cycles (75 TFLOP/s
-// over the chip) against 105 for the large one (48 TFLOP/s), so the pass is no longer bound
-// by the matrix unit (measured with the 16 x 16 x 4 form: 143-148 us on the 0.7 GB slab).
-// Vector and fp64 matrix instructions of a SIMD do not overlap on this chip (a tile's
-// arithmetic takes the sum of the two: 5500 cycles, 3500 of them matrix instructions), and
-// the instruction's operand-broadcast controls are not honoured for fp64; reading the
-// rotated operands from LDS instead of moving them between lanes changed nothing.
+// matrix with a plain product).  The symmetric 16 x 16 matrix has 10 distinct 4 x 4 blocks:
+//   - the lane's value as BOTH operands: block b = the diagonal block of peers 4 b ..;
+//   - second operand = the value of peer p - 4 (mod 16): block b pairs peers 4 b .. with
+//     peers 4 (b - 1) ..: the four blocks next to the diagonal (cyclically: (0, 3) included);
+//   - the two remaining blocks, (0, 2) and (1, 3), would fill only half an instruction, so
+//     one instruction takes them for TWO coordinates x and y of the lane at once: in its
+//     first operand lanes p < 8 hold their own value at x and lanes p >= 8 the value of
+//     peer p - 8 at y, in its second lanes p < 8 hold peer p + 8 at x and lanes p >= 8
+//     their own value at y; blocks 0, 1 are then (0, 2), (1, 3) summed over x, blocks 2, 3
+//     the same two summed over y (added at the end).
+// That is 5 instructions per 8 coordinates, every block slot a distinct needed block: 640
+// multiply-adds per 4 coordinates where one 16 x 16 x 4 instruction spends 1024 -- and the
+// fp64 matrix rate is the same for both shapes (the small instruction issues every 16-17
+// cycles).  The operands of other peers come straight out of the wavefront's LDS copy of
+// the tile (three 128-bit reads per 4 coordinates: rows p, p - 4, p - 8), each converted
+// to fp64 where it is used: no moves between lanes.  Vector and fp64 matrix instructions of
+// a SIMD do not overlap on this chip (a tile's arithmetic takes the sum of the two), and
+// the pass is bound by their issue, not by memory: with 6 instructions per 8 coordinates
+// and lane rotations (DPP, 16 moves per 4 coordinates) it took 13.2 ms on the 84 GB slab,
+// with the rotated operands read from LDS 13.15 ms.
 // The slab is read row by row (a wavefront's load instruction covers 1 KiB of one peer's
 // row, the pattern that reaches the highest bandwidth) and turned into the operand layout
 // (16 peers across the lanes) through the wavefront's own LDS area: written row-wise,
 // read back as 16 coordinates x 16 peers.  No barrier is involved.  Rows of the LDS copy
 // are 16 bytes longer than 1 KiB so that the 16 peers' reads fall into different banks.
-constexpr int kGramLdsRow = 256 + 4;                 // floats per LDS row
+#ifndef BTARD_GRAM_LDS_PAD
+#define BTARD_GRAM_LDS_PAD 4
+#endif
+constexpr int kGramLdsRow = 256 + BTARD_GRAM_LDS_PAD;  // floats per LDS row
 
 // `stream` (wavefront-uniform): non-temporal loads, for the part of the slab that will not
 // survive in the memory-side cache until the last pass reads it again anyway.
@@ -144,28 +143,64 @@ __device__ __forceinline__ void gram_stage(float (&tile)[16][kGramLdsRow], int l
 }
 
 // ... and read back peer-wise into the matrix instructions.
+// acc[0]: diagonal blocks, acc[1]: blocks (b, b - 1), acc[2]: blocks (0, 2), (1, 3) twice;
+// two accumulators each, used in turn, so that consecutive instructions do not wait for
+// each other.
 template <bool RAGGED>
-__device__ __forceinline__ void gram_multiply(const float (&tile)[16][kGramLdsRow], int p, int q, bool have,
+__device__ __forceinline__ void gram_multiply(const float (&tile)[16][kGramLdsRow], int p, int q, int n,
                                               double (&acc)[3][2])
 {
+    const int p1 = (p + 12) & 15, p2 = (p + 8) & 15;           // peers p - 4 and p - 8 (mod 16)
+    const bool low = p < 8;
+    const bool have = p < n, have1 = p1 < n, have2 = p2 < n;
+    // third block set: lanes p < 8 take coordinates 0, 1 of the lane's four (own value first,
+    // peer p + 8 second), lanes p >= 8 coordinates 2, 3 (peer p - 8 first, own value second):
+    // the LDS addresses do the selection
+    const int pa = low ? p : p2, pb = low ? p2 : p, xo = low ? 0 : 2;
+    const bool have_a = low ? have : have2, have_b = low ? have2 : have;
+    typedef float f32x2_a __attribute__((ext_vector_type(2), aligned(8)));
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
         const f32x4_u t = *reinterpret_cast<const f32x4_u *>(&tile[p][16 * s + 4 * q]);
-        const float val[4] = {t.x, t.y, t.z, t.w};
-        // the operands of the group's 12 instructions first, each in registers of its own
-        double d[4], d1[4], d2[4];
+        const f32x4_u t1 = *reinterpret_cast<const f32x4_u *>(&tile[p1][16 * s + 4 * q]);
+        const f32x2_a ta = *reinterpret_cast<const f32x2_a *>(&tile[pa][16 * s + 4 * q + xo]);
+        const f32x2_a tb = *reinterpret_cast<const f32x2_a *>(&tile[pb][16 * s + 4 * q + xo]);
+        float val[4] = {t.x, t.y, t.z, t.w};
+        float val1[4] = {t1.x, t1.y, t1.z, t1.w};
+        float va[2] = {ta.x, ta.y}, vb[2] = {tb.x, tb.y};
+        if (RAGGED) {
+            // (rows of absent peers hold a copy of the last row: replaced by zero)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                val[e] = have ? val[e] : 0.0f;
+                val1[e] = have1 ? val1[e] : 0.0f;
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                va[h] = have_a ? va[h] : 0.0f;
+                vb[h] = have_b ? vb[h] : 0.0f;
+            }
+        }
+        // the operands of the group's 10 instructions first, each in registers of its own
+        double d[4], d1[4], da[2], db[2];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            d[e] = (double)(RAGGED && !have ? 0.0f : val[e]);
-            d1[e] = row_rotate4<1>(d[e]);
-            d2[e] = row_rotate4<2>(d[e]);
+            d[e] = (double)val[e];
+            d1[e] = (double)val1[e];
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            da[h] = (double)va[h];
+            db[h] = (double)vb[h];
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             acc[0][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(d[e], d[e], acc[0][e & 1], 0, 0, 0);
             acc[1][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(d[e], d1[e], acc[1][e & 1], 0, 0, 0);
-            acc[2][e & 1] = __builtin_amdgcn_mfma_f64_4x4x4f64(d[e], d2[e], acc[2][e & 1], 0, 0, 0);
         }
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            acc[2][h] = __builtin_amdgcn_mfma_f64_4x4x4f64(da[h], db[h], acc[2][h], 0, 0, 0);
     }
 }
 
@@ -182,9 +217,8 @@ __global__ __launch_bounds__(kBlock, 2) void gram_pass_kernel(GramArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int p = lane & 15, q = lane >> 4;
-    const bool have = p < n;
 
-    // [rotation 0, 1, 2][two independent sets: consecutive MFMAs do not wait for each other]
+    // [block set][two independent accumulators: consecutive MFMAs do not wait for each other]
     double acc[3][2];
 #pragma unroll
     for (int s = 0; s < 3; ++s) { acc[s][0] = 0.0; acc[s][1] = 0.0; }
@@ -193,8 +227,9 @@ __global__ __launch_bounds__(kBlock, 2) void gram_pass_kernel(GramArgs a)
     const int64_t stream_units = tr.units * a.stream_permille / 1000;
 
     // One register set: while a tile is multiplied out of LDS, the next one's loads travel.
-    // (Two sets, loaded two tiles ahead, were slower: the pass is not short of requests in
-    // flight.)
+    // (Two sets, loaded two tiles ahead, gain nothing on the 84 GB slab -- 12.85 against
+    // 12.89 ms -- and lose on the 0.7 GB one, 126 against 116 us: the pass is not short of
+    // requests in flight.)
     f32x4_u rows[16];
     if (tr.first < tr.units) {
         const int64_t xu = tr.xa + tr.first * kW;
@@ -209,21 +244,33 @@ __global__ __launch_bounds__(kBlock, 2) void gram_pass_kernel(GramArgs a)
             gram_fetch_rows<RAGGED>(a.g, a.ld, n, lane, xn, lo, hi, tile_is_interior<kW>(xn, lo, hi),
                                     un < stream_units, rows);
         }
-        gram_multiply<RAGGED>(tile[wave], p, q, have, acc);
+#ifdef BTARD_PROBE_NO_MULTIPLY
+        if (a.n > 100) gram_multiply<RAGGED>(tile[wave], p, q, n, acc);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#else
+        gram_multiply<RAGGED>(tile[wave], p, q, n, acc);
+#endif
     }
 
     // Workgroup partial: the 4 wavefronts' matrices added in order.  Lane 16 i + 4 b + jj holds
-    // entry (4 b + i, 4 ((b - s) mod 4) + jj) of rotation s; rotation 1 forms the blocks
-    // (b, b - 1) only, whose transposes are written as well.
+    // entry (4 b + i, 4 b + jj) of the diagonal blocks and entry (4 b + i, 4 ((b - 1) mod 4) + jj)
+    // of the blocks next to them; of the third set, blocks b = 0, 1 hold entry
+    // (4 b + i, 8 + 4 b + jj) summed over one half of the coordinates and blocks b + 2 (8 lanes
+    // further on) the same entry summed over the other half.  Transposes are written as well.
     {
         const int i = lane >> 4, b = (lane >> 2) & 3, jj = lane & 3;
         const int r = 4 * b + i;
-#pragma unroll
-        for (int s = 0; s < 3; ++s) {
-            const int c = 4 * ((b - s + 4) & 3) + jj;
-            const double x = acc[s][0] + acc[s][1];
-            sh[wave][r * kGramPeers + c] = x;
-            if (s == 1) sh[wave][c * kGramPeers + r] = x;
+        sh[wave][r * kGramPeers + 4 * b + jj] = acc[0][0] + acc[0][1];
+        const int c1 = 4 * ((b + 3) & 3) + jj;
+        const double x1 = acc[1][0] + acc[1][1];
+        sh[wave][r * kGramPeers + c1] = x1;
+        sh[wave][c1 * kGramPeers + r] = x1;
+        double x2 = acc[2][0] + acc[2][1];
+        x2 += __shfl_xor(x2, 8, 64);                 // (the same sum in both lanes: a + b = b + a)
+        if (b < 2) {
+            const int c2 = 8 + 4 * b + jj;
+            sh[wave][r * kGramPeers + c2] = x2;
+            sh[wave][c2 * kGramPeers + r] = x2;
         }
     }
     __syncthreads();
