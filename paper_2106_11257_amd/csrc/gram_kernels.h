@@ -696,33 +696,41 @@ __device__ __forceinline__ double lane_value_at(double x, int k)
     return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
 }
 
-// Value of lane K of the same row of 16 lanes, for every lane (DPP row_newbcast: no scalar
-// register in between, so no wait states before the value is used).
-template <int K>
-__device__ __forceinline__ double row_value(double x)
+// sum_k row[k] * (x of lane k of the same row of 16 lanes): sixteen fused multiply-adds whose
+// first factor is the broadcast itself (v_fmac_f64 with the DPP control row_newbcast:k, the
+// one control the fp64 unit accepts), in two chains that are added at the end -- a third of
+// the instructions of a broadcast by moves (two 32-bit moves per value) followed by a
+// multiply-add.  The s_nop covers the wait states a DPP access needs after a vector
+// instruction that wrote x (2) or the execution mask (5): the compiler cannot see into the
+// block.  To be used where all 64 lanes are active.
+__device__ __forceinline__ double row_dot16(const double (&row)[16], double x)
 {
-    const uint64_t b = (uint64_t)__double_as_longlong(x);
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)b, 0x150 + K, 0xf, 0xf, false);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(b >> 32), 0x150 + K, 0xf, 0xf, false);
-    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+    double y0 = 0.0, y1 = 0.0;
+#define BTARD_BC(k) " row_newbcast:" #k " row_mask:0xf bank_mask:0xf\n"
+    asm("s_nop 4\n"
+        "v_fmac_f64_dpp %0, %2, %3" BTARD_BC(0)
+        "v_fmac_f64_dpp %1, %2, %4" BTARD_BC(1)
+        "v_fmac_f64_dpp %0, %2, %5" BTARD_BC(2)
+        "v_fmac_f64_dpp %1, %2, %6" BTARD_BC(3)
+        "v_fmac_f64_dpp %0, %2, %7" BTARD_BC(4)
+        "v_fmac_f64_dpp %1, %2, %8" BTARD_BC(5)
+        "v_fmac_f64_dpp %0, %2, %9" BTARD_BC(6)
+        "v_fmac_f64_dpp %1, %2, %10" BTARD_BC(7)
+        "v_fmac_f64_dpp %0, %2, %11" BTARD_BC(8)
+        "v_fmac_f64_dpp %1, %2, %12" BTARD_BC(9)
+        "v_fmac_f64_dpp %0, %2, %13" BTARD_BC(10)
+        "v_fmac_f64_dpp %1, %2, %14" BTARD_BC(11)
+        "v_fmac_f64_dpp %0, %2, %15" BTARD_BC(12)
+        "v_fmac_f64_dpp %1, %2, %16" BTARD_BC(13)
+        "v_fmac_f64_dpp %0, %2, %17" BTARD_BC(14)
+        "v_fmac_f64_dpp %1, %2, %18" BTARD_BC(15)
+        : "+v"(y0), "+v"(y1)
+        : "v"(x), "v"(row[0]), "v"(row[1]), "v"(row[2]), "v"(row[3]), "v"(row[4]), "v"(row[5]),
+          "v"(row[6]), "v"(row[7]), "v"(row[8]), "v"(row[9]), "v"(row[10]), "v"(row[11]),
+          "v"(row[12]), "v"(row[13]), "v"(row[14]), "v"(row[15]));
+#undef BTARD_BC
+    return y0 + y1;
 }
-
-template <int K, int N>
-struct RowDot {
-    // (two chains of fused multiply-adds: half the dependent latency)
-    static __device__ __forceinline__ double run(const double (&row)[N], double x, double y0, double y1)
-    {
-        return RowDot<K + 2, N>::run(row, x, fma(row[K], row_value<K>(x), y0),
-                                     fma(row[K + 1], row_value<K + 1>(x), y1));
-    }
-};
-template <int N>
-struct RowDot<16, N> {
-    static __device__ __forceinline__ double run(const double (&)[N], double, double y0, double y1)
-    {
-        return y0 + y1;
-    }
-};
 
 // 1 / sqrt(x) for finite x > 0 to within a few units in the last place: the hardware
 // estimate and two Newton steps (a dozen dependent instructions where a square root
@@ -745,7 +753,7 @@ __device__ __forceinline__ double row_dot(const double (&row)[N], double x)
 {
     if constexpr (N == 16) {
         // (the peers are replicated in the four rows of 16 lanes)
-        return RowDot<0, N>::run(row, x, 0.0, 0.0);
+        return row_dot16(row, x);
     } else {
         double y = 0.0;
 #pragma unroll
@@ -914,14 +922,14 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
     double qv, Sc;
     peers_sum2<N>(q, c * y, fabs(c) * rt, qv, Sc);
 
+    // sqrt(kGramUnit), rounded up: error bar of a norm whose square is within its own error
+    constexpr double kGramUnitRoot = 1.1920929e-7;
     while (!dn) {                             // wavefront-uniform
         // (tau_l of eq. (5) if the caller gave a schedule)
         const double tau = (a.st.has_sched && it < kMaxSchedule) ? s_tau[it] : a.tau;
-        // norms, weights and how wrong the weights may be
-        const double N2raw = diag - 2.0 * y + qv;
-        // (tested before the clamp: fmax(NaN, 0) is 0)
-        if (__any(peer && !isfinite(N2raw))) { it = -1; dn = 1; break; }
-        const double N2 = fmax(N2raw, 0.0);
+        // norms, weights and how wrong the weights may be.  (Everything stays finite from
+        // here on: Gamma is finite, the coefficients stay within the unit simplex's hull.)
+        const double N2 = fmax(diag - 2.0 * y + qv, 0.0);
         const double eN2 = kGramUnit * (rt + Sc) * (rt + Sc);
         // ||g_i - v|| = N2 / sqrt(N2) and tau / ||g_i - v|| from one reciprocal square root
         const double rs = rsqrt_newton(N2);
@@ -932,28 +940,26 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
             // a weight that is (or may be) tau/N inherits half the relative error of N^2;
             // its contribution to v is w * N <= tau
             if (N2 + eN2 > tau * tau) {
-                // (error bars are bounds: hardware reciprocal / square-root estimates,
-                // rounded up by 1 %, instead of full divisions)
-                const double rel = (N2 > eN2) ? 0.505 * eN2 * __builtin_amdgcn_rcp(N2) : 1.0;
+                // (error bars are bounds, rounded up by 1 %; 1 / N2 = rs^2)
+                const double rel = (N2 > eN2) ? 0.505 * eN2 * (rs * rs) : 1.0;
                 err_w = rel * fmin(Nn, tau) * inv_n;
             }
         }
         double W, E;
         peers_sum2<N>(q, w, err_w, W, E);
         const double ev_new = ev + E;
-        // the update this would apply, and its norm sqrt(a^T Gamma a)
+        // the update this would apply, and its squared norm a^T Gamma a
         const double an = peer ? (w - W * c) * inv_n : 0.0;
         const double u = row_dot<N>(row, an);
         const double cn = c + an;
         double yn = y + u;
         double Tn2, Sa, Scn, qvn;
         peers_sum4<N>(q, an * u, fabs(an) * rt, fabs(cn) * rt, cn * yn, Tn2, Sa, Scn, qvn);
-        const double T = (Tn2 > 0.0) ? Tn2 * rsqrt_newton(Tn2) : 0.0;
+        Tn2 = fmax(Tn2, 0.0);
         // error budget: the (generously bounded, never discounted) error put into v must
-        // stay a small fraction of ||v|| and of the step itself (whose norm is compared
-        // with eps below)
-        const double budget = fmin(0.99e-8 * __builtin_amdgcn_sqrt(fmax(qv, 0.0)), 1e-3 * T);
-        if (ev_new > budget) break;                               // hand over before this update
+        // stay below 0.99e-8 ||v|| and below 1e-3 of the step itself (whose norm is compared
+        // with eps below); compared in squares, which needs no square root
+        if (ev_new * ev_new > fmin(0.98e-16 * fmax(qv, 0.0), 1e-6 * Tn2)) break;   // hand over before this update
         ev = ev_new;
         al = an;
         c = cn;
@@ -968,15 +974,19 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         qv = qvn;
         Sc = Scn;
         if (it >= a.max_iters) dn = 1;
-        // stopping rule on the update just applied, with its error bar
+        // stopping rule on the update just applied, T = sqrt(Tn2) against eps, with its error
+        // bar: eT bounds the error of T (from that of Tn2, eT2: eT2 / T where that is smaller
+        // than sqrt(eT2); 1 / T from the hardware's estimate, rounded up by 1 %), and the plain
+        // iteration's step may differ from this one by the error in v as well.  The comparisons
+        // themselves are made in squares, on the exact Tn2.
         if (a.eps > 0.0) {
             const double eT2 = kGramUnit * Sa * Sa;
-            const double eT = (T * T > eT2) ? 1.01 * eT2 * __builtin_amdgcn_rcp(T)
-                                            : 1.01 * __builtin_amdgcn_sqrt(eT2);
-            // the plain iteration's step may differ from this one by the error in v as well
+            const double eT = (Tn2 > eT2) ? 1.011 * eT2 * __builtin_amdgcn_rsq(Tn2)
+                                          : 1.01 * kGramUnitRoot * Sa;
             const double band = eT + 2.0 * ev;
-            if (T + band < a.eps) dn = 1;                         // certainly converged
-            else if (!(T - band >= a.eps)) break;                 // cannot tell: hand over
+            const double below = a.eps - band, above = a.eps + band;
+            if (below > 0.0 && Tn2 < below * below) dn = 1;          // certainly converged
+            else if (!(Tn2 >= above * above)) break;                  // cannot tell: hand over
         }
     }
     // A partition that finished here: the norms at the final v and the norm of the last
