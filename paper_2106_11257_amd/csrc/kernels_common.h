@@ -301,6 +301,8 @@ __host__ __device__ constexpr uint32_t epoch_multiplier(uint32_t ticks)
     return (uint32_t)(0x100000000ull / (ticks < 1 ? 1 : ticks));
 }
 constexpr int kStageSlots = kWaves * kStageTiles * 64;
+constexpr uint32_t kSpinFraction = 3951369912u;                 // 0.92 x 2^32
+constexpr int kSpinLooks = 2048;
 
 struct TileStage {
     // wavefront-uniform state (scalar registers); the lane's addresses are formed when used
@@ -363,7 +365,21 @@ struct TileStage {
     template <int LANES>
     __device__ __forceinline__ void flush_if_due(int sub, int room, bool holds = true)
     {
-        const uint32_t now = epoch_now();
+        // A wavefront that gets here in the last 8 % of an epoch (and holds tiles) waits for
+        // the epoch's end instead of going on for another tile: the bursts of all wavefronts
+        // then begin within a narrower window (measured on the 84 GB slab: last pass 14.18
+        // against 14.63 ms; windows of 4 %, 6 %, 10 % and 15 %: 14.47, 14.33, 14.35 and
+        // 15.1 ms).  The wait is bounded: the clock always advances, and the loop gives up
+        // after kSpinLooks looks at it.  The low word of ticks x multiplier is the elapsed
+        // fraction of the epoch in units of 2^-32.
+        uint32_t ticks = (uint32_t)__builtin_amdgcn_s_memrealtime();
+        uint32_t now = __umulhi(ticks, multiplier);
+        if (now == epoch && count > 0 && ticks * multiplier > kSpinFraction) {
+            for (int look = 0; look < kSpinLooks && now == epoch; ++look) {
+                __builtin_amdgcn_s_sleep(1);
+                now = epoch_now();
+            }
+        }
         if (count + room > capacity<LANES>() || now != epoch) flush<LANES>(sub, holds);
         epoch = now;
     }

@@ -21,6 +21,7 @@ pytestmark = pytest.mark.gpu
 V_TOL = 1e-5
 PROJ_TOL = 1e-4
 SCALAR_TOL = 1e-6
+GRAM_STEP_TOL = 1e-6
 
 
 @pytest.fixture(scope="module")
@@ -60,9 +61,9 @@ def check_cc(G, off, tau, eps, M, v0=None, parts_to_check=None, label="", flags=
             lo, hi = off[j], off[j + 1]
             assert rel_l2(v_h[lo:hi], vo[lo:hi]) <= V_TOL, f"partition {j}"
         assert rel_l2(v_h, vo) <= V_TOL
-        # Gram mode bounds the error it puts into v by 1e-3 of the step (a bound ~100x above
-        # what is observed); the plain passes differ by summation order only
-        np.testing.assert_allclose(sn_h, sno, rtol=(1e-4 if flags else SCALAR_TOL), atol=1e-11)
+        # (Gram mode bounds the error it puts into v by 1e-3 of the step, ~100x above what is
+        # observed: its step norms are held to the same 1e-6 as the plain passes')
+        np.testing.assert_allclose(sn_h, sno, rtol=(GRAM_STEP_TOL if flags else SCALAR_TOL), atol=1e-11)
     else:
         for j in todo:
             lo, hi = off[j], off[j + 1]
@@ -406,7 +407,7 @@ def test_gram_last_pass_without_waiting_for_the_iteration(dev):
         for j in range(len(off) - 1):
             lo, hi = off[j], off[j + 1]
             assert rel_l2(v.cpu().numpy()[lo:hi], v_ref[lo:hi]) <= 1e-5
-        np.testing.assert_allclose(sn.cpu().numpy(), sn_ref, rtol=1e-4, atol=1e-11)
+        np.testing.assert_allclose(sn.cpu().numpy(), sn_ref, rtol=GRAM_STEP_TOL, atol=1e-11)
         ref = oracle.verify(Gh, off, v.cpu().numpy(), tau, seed)
         np.testing.assert_allclose(out["norms"].cpu().numpy(), ref["norms"], rtol=1e-6, atol=1e-12)
         pr = out["proj"].cpu().numpy()
@@ -468,7 +469,7 @@ def check_preclipped(G, off, lam, tau, eps, M, seed, flags, label):
     for j in range(len(off) - 1):
         lo, hi = off[j], off[j + 1]
         assert rel_l2(v_h[lo:hi], vo[lo:hi]) <= V_TOL, f"partition {j}"
-    np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=1e-4, atol=1e-11)
+    np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=GRAM_STEP_TOL, atol=1e-11)
     ref = oracle.verify(Gh, off, v_h.astype(np.float64), tau, seed, scale=alpha)
     np.testing.assert_allclose(out["norms"].cpu().numpy(), ref["norms"], rtol=1e-6, atol=1e-9)
     np.testing.assert_allclose(out["weights"].cpu().numpy(), ref["weights"], rtol=1e-6)
@@ -663,7 +664,7 @@ def test_scheduled_radii_match_the_oracle(dev, n, d, P, flags):
         vo, ito, sno, _ = oracle.centered_clip(Gh, off, 1.0, eps, M, tau_l=sched)
         np.testing.assert_array_equal(iters.cpu().numpy(), ito)
         assert rel_l2(v.cpu().numpy(), vo) <= V_TOL
-        np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=1e-4, atol=1e-11)
+        np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=GRAM_STEP_TOL, atol=1e-11)
         # the verification weights use the constant tau of the problem (Alg. 6 has one tau)
         ref = oracle.verify(Gh, off, v.cpu().numpy().astype(np.float64), 1.0, 0xBEE)
         np.testing.assert_allclose(out["norms"].cpu().numpy(), ref["norms"], rtol=1e-6, atol=1e-9)
