@@ -321,7 +321,11 @@ def test_zhat_matches_the_z_spec(dev):
 @pytest.mark.parametrize("n,d,P,pad", [(3, 1031, 2, 0), (9, 5000, 4, 2), (16, 70001, 16, 0),
                                        (16, 262147, 3, 5), (1, 300, 2, 1), (12, 7, 3, 0), (8, 5003, 3, 1),
                                        (5, 40001, 2, 3), (17, 3000, 2, 1), (33, 2000, 3, 1),
-                                       (40, 70003, 4, 0), (64, 20000, 64, 0), (64, 333, 1, 2)])
+                                       (40, 70003, 4, 0), (64, 20000, 64, 0), (64, 333, 1, 2),
+                                       # every peer count of the 16-peer matrix kernel: absent
+                                       # peers in each of its three operand sets
+                                       (10, 3001, 2, 1), (11, 2999, 3, 0), (12, 3000, 3, 1),
+                                       (13, 5000, 2, 2), (14, 4097, 2, 3), (15, 4097, 2, 3)])
 def test_gram_matrix_matches_matmul(dev, n, d, P, pad):
     G, off = workloads.generic_case(n, d, P, seed=31 * n + d, device=dev, ld=d + pad, spread=0.5,
                                     outliers=n // 3)
