@@ -131,29 +131,35 @@ int variant_peers(Variant v)
 }
 
 // Workgroups that are resident at once for a kernel on the current device
-// (compute units x occupancy), cached per (device, kernel).
+// (compute units x occupancy), cached per (device, kernel); .second = the compute units.
 struct ResidentCache {
     std::mutex mu;
-    std::map<std::pair<int, const void *>, int> value;
+    std::map<std::pair<int, const void *>, std::pair<int, int>> value;
 };
 ResidentCache g_resident;
 
-int resident_blocks(const void *fn)
+struct Resident {
+    int blocks;   // 0: the query failed
+    int cus;
+};
+
+Resident resident_blocks(const void *fn)
 {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipGetDevice(&dev) != hipSuccess) return Resident{0, 0};
     std::lock_guard<std::mutex> lock(g_resident.mu);
-    int &slot = g_resident.value[std::make_pair(dev, fn)];
-    if (slot == 0) {
+    std::pair<int, int> &slot = g_resident.value[std::make_pair(dev, fn)];
+    if (slot.first == 0) {
         int cus = 0, occ = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-            return 0;
+            return Resident{0, 0};
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, fn, kBlock, 0) != hipSuccess)
-            return 0;
+            return Resident{0, 0};
         if (occ < 1) occ = 1;
-        slot = cus * occ;
+        if (cus < 1) cus = 1;
+        slot = std::make_pair(cus * occ, cus);
     }
-    return slot;
+    return Resident{slot.first, slot.second};
 }
 
 // Epoch of the write bursts of v (TileStage): half the time in which a wavefront fills its
@@ -168,10 +174,25 @@ uint32_t stage_epoch_multiplier(int64_t waves, double tile_bytes, int capacity_t
     return epoch_multiplier((uint32_t)(us * 100.0));
 }
 
-// Workgroups per partition: fill the device once (all partitions run side by side; the
-// pass gains bandwidth up to full occupancy), but never more than the partial-sum area
-// holds or the work needs.
-int blocks_per_partition(int resident, int32_t P, const int64_t *off, int tile_w)
+// Workgroups per partition.  The device is filled once (no tail wave); what is chosen is how
+// many partitions stream side by side.
+//   - By default all of them: B = resident / P.
+//   - On slabs far beyond the caches that is many concurrent row streams (P x n rows, each
+//     read through a narrow window), which costs bandwidth: measured on an 84 GB slab with
+//     n = P = 16, B = 256 workgroups per partition (2 or 4 partitions at a time instead of
+//     16) takes 12.27 against 12.79 ms for the Gram pass, 13.72 against 14.21 ms for the last
+//     pass and 12.08 against 12.19 ms for an iteration's pass, while one partition at a time
+//     is slower again (12.8, 14.6, 12.85 ms); with n = 8 rows per partition on an 8.6 GB slab
+//     the best figures are those of 64 (passes) to 16-32 (last pass) concurrent rows as well.
+//     So where every wavefront still gets kStreamTiles tiles, as many partitions run at a
+//     time as make 16 rows per resident workgroup of a compute unit: B = 16 n.
+//   - Never more than the partial-sum area holds, nor so many that a wavefront gets fewer
+//     than kMinTilesPerWave tiles: on small slabs fewer, longer-lived workgroups cost less
+//     than the start-up of many (dispatch, the control step's sums over all workgroups'
+//     partial results, the first loads' latency; 64 MiB slab with 16 partitions: 25.0 us per
+//     pass with 1 tile per wavefront, 17.8 with 2, 17.4 with 4, 18.6 with 6).
+constexpr int kStreamTiles = 32;
+int blocks_per_partition(Resident r, int32_t n, int32_t P, const int64_t *off, int tile_w)
 {
     int64_t max_units = 1;
     for (int32_t j = 0; j < P; ++j) {
@@ -179,13 +200,17 @@ int blocks_per_partition(int resident, int32_t P, const int64_t *off, int tile_w
         const int64_t units = hi > lo ? (hi - tile_origin_for(lo, tile_w) + tile_w - 1) / tile_w : 0;
         if (units > max_units) max_units = units;
     }
-    int64_t B = resident / P;
+    int64_t B = r.blocks / P;
+    {
+        const int64_t occ = r.blocks / r.cus > 0 ? r.blocks / r.cus : 1;
+        int64_t at_once = 16 * occ / n;
+        if (at_once < 1) at_once = 1;
+        if (at_once > P) at_once = P;
+        const int64_t Bs = r.blocks / at_once;
+        if (Bs > B && max_units / (kWaves * Bs) >= kStreamTiles) B = Bs;
+    }
     const int64_t cap_ws = kMaxBlocks / P;
     if (B > cap_ws) B = cap_ws;
-    // (at least kMinTilesPerWave tiles per wavefront: on small slabs fewer, longer-lived
-    // workgroups cost less than the start-up of many -- dispatch, the control step's sums over
-    // all workgroups' partial results, the first loads' latency.  Measured on a 64 MiB slab
-    // with 16 partitions: 25.0 us per pass with 1 tile, 17.8 with 2, 17.4 with 4, 18.6 with 6.)
     const int64_t cap_work = (max_units + kWaves * kMinTilesPerWave - 1) / (kWaves * kMinTilesPerWave);
     if (B > cap_work) B = cap_work;
     if (B < 1) B = 1;
@@ -391,15 +416,15 @@ static int gram_stream_permille(const btard_cc_problem *p)
 
 static int gram_blocks(const btard_cc_problem *p)
 {
-    const int resident = resident_blocks(reinterpret_cast<const void *>(gram_kernel(p)));
-    if (resident <= 0) return 0;
+    const Resident resident = resident_blocks(reinterpret_cast<const void *>(gram_kernel(p)));
+    if (resident.blocks <= 0) return 0;
     // n <= 8: a workgroup's wavefronts share its 256-coordinate tiles, i.e. 64 per wavefront
 #ifdef BTARD_GRAM16_BAND
     const int tile = 64;
 #else
     const int tile = p->n <= 8 ? 64 : (p->n <= kGramPeers ? 256 : 64);
 #endif
-    return blocks_per_partition(resident, p->parts, p->offsets_host, tile);
+    return blocks_per_partition(resident, p->n, p->parts, p->offsets_host, tile);
 }
 
 int btard_cc_gram_matrix(const btard_cc_problem *p)
@@ -511,9 +536,9 @@ int btard_debug_gram(const btard_cc_problem *p, double *gram_out)
 static int pass_blocks(const btard_cc_problem *p, Variant var, int ragged, int based)
 {
     const CcPassFn fn = cc_pass_fn(var, ragged, based, preclip_on(p));
-    const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
-    if (resident <= 0) return 0;
-    return blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
+    const Resident resident = resident_blocks(reinterpret_cast<const void *>(fn));
+    if (resident.blocks <= 0) return 0;
+    return blocks_per_partition(resident, p->n, p->parts, p->offsets_host, variant_tile_width(var));
 }
 
 int btard_cc_iterate(const btard_cc_problem *p, int32_t first_iteration, int32_t count)
@@ -551,9 +576,9 @@ int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int
     const Variant var = pick_variant(p->n);
     const int ragged = p->n < variant_peers(var) ? 1 : 0, based = p->v0 ? 1 : 0;
     const CcFinishFn fn = cc_finish_fn(var, ragged, based);
-    const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
-    if (resident <= 0) return BTARD_ERR_DEVICE;
-    const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
+    const Resident resident = resident_blocks(reinterpret_cast<const void *>(fn));
+    if (resident.blocks <= 0) return BTARD_ERR_DEVICE;
+    const int B = blocks_per_partition(resident, p->n, p->parts, p->offsets_host, variant_tile_width(var));
     const int Bpass = pass_blocks(p, var, ragged, based);
     if (Bpass <= 0) return BTARD_ERR_DEVICE;
     CcFinishArgs a;
@@ -564,7 +589,9 @@ int btard_cc_finish(const btard_cc_problem *p, int32_t iterations, float *v, int
     {
         // (a tile: the n rows' and v's 4 bytes per coordinate; tiles staged: see TileStage)
         const int W = variant_tile_width(var);
-        a.epoch_mult = stage_epoch_multiplier((int64_t)B * p->parts * kWaves,
+        // (the wavefronts that share the memory at any time: those resident at once)
+        const int64_t running = (int64_t)B * p->parts < resident.blocks ? (int64_t)B * p->parts : resident.blocks;
+        a.epoch_mult = stage_epoch_multiplier(running * kWaves,
                                               4.0 * (p->n + 1 + (p->v0 ? 1 : 0)) * W,
                                               kStageTiles * (256 / W));
     }
@@ -615,9 +642,9 @@ static int launch_fused_pass(const btard_cc_problem *p, int32_t iterations, floa
     const Variant var = pick_variant(p->n);
     const int ragged = p->n < variant_peers(var) ? 1 : 0;
     const FusedFn fn = fused_pass_fn(var, ragged, preclip_on(p));
-    const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
-    if (resident <= 0) return BTARD_ERR_DEVICE;
-    const int B = blocks_per_partition(resident, p->parts, p->offsets_host, variant_tile_width(var));
+    const Resident resident = resident_blocks(reinterpret_cast<const void *>(fn));
+    if (resident.blocks <= 0) return BTARD_ERR_DEVICE;
+    const int B = blocks_per_partition(resident, p->n, p->parts, p->offsets_host, variant_tile_width(var));
     const int Bpass = pass_blocks(p, var, ragged, 0);
     if (Bpass <= 0) return BTARD_ERR_DEVICE;
     FusedArgs a;
@@ -629,7 +656,8 @@ static int launch_fused_pass(const btard_cc_problem *p, int32_t iterations, floa
     a.scaled = preclip_on(p) ? 1 : 0;
     {
         const int W = variant_tile_width(var);
-        a.epoch_mult = stage_epoch_multiplier((int64_t)B * p->parts * kWaves, 4.0 * (p->n + 1) * W,
+        const int64_t running = (int64_t)B * p->parts < resident.blocks ? (int64_t)B * p->parts : resident.blocks;
+        a.epoch_mult = stage_epoch_multiplier(running * kWaves, 4.0 * (p->n + 1) * W,
                                               kStageTiles * (256 / W));
     }
     a.st = carve_problem(p);
@@ -785,10 +813,10 @@ int btard_coordinate_median(const float *g, int64_t ldg, int32_t n, int64_t d, f
     const Variant var = pick_variant(n);
     const int ragged = n < variant_peers(var) ? 1 : 0;
     const MedianFn fn = median_fn(var, ragged);
-    const int resident = resident_blocks(reinterpret_cast<const void *>(fn));
-    if (resident <= 0) return BTARD_ERR_DEVICE;
+    const Resident resident = resident_blocks(reinterpret_cast<const void *>(fn));
+    if (resident.blocks <= 0) return BTARD_ERR_DEVICE;
     const int64_t whole[2] = {0, d};
-    const int B = blocks_per_partition(resident, 1, whole, variant_tile_width(var));
+    const int B = blocks_per_partition(resident, n, 1, whole, variant_tile_width(var));
     MedianArgs a;
     a.g = g; a.ld = ldg; a.n = n; a.d = d; a.v = v;
     a.epoch_mult = stage_epoch_multiplier((int64_t)B * kWaves, 4.0 * (n + 1) * variant_tile_width(var),
@@ -1009,9 +1037,9 @@ static int launch_verification(const float *g, int64_t ldg, int32_t n, const int
     const Variant var = pick_variant(n);
     const int ragged = n < variant_peers(var) ? 1 : 0;
     const VerifyFn vfn = verify_pass_fn(var, ragged, scaled);
-    const int resident = resident_blocks(reinterpret_cast<const void *>(vfn));
-    if (resident <= 0) return BTARD_ERR_DEVICE;
-    const int B = blocks_per_partition(resident, parts, offsets_host, variant_tile_width(var));
+    const Resident resident = resident_blocks(reinterpret_cast<const void *>(vfn));
+    if (resident.blocks <= 0) return BTARD_ERR_DEVICE;
+    const int B = blocks_per_partition(resident, n, parts, offsets_host, variant_tile_width(var));
 
     VerifyArgs a;
     a.g = g; a.ld = ldg; a.n = n; a.v = v; a.seed = seed; a.off = st.off;
