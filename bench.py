@@ -453,6 +453,40 @@ def main() -> int:
                                     "frac_of_hbm_peak": round(rate / HBM_PEAK_GBPS, 4)})
             out["roofline"]["traffic_note"] = TRAFFIC_NOTE
 
+        # ---- a plain grid-stride kernel on the same slab: what a straightforward kernel reaches
+        # with the traffic of a pass (rows read) and of the last pass (rows read, one row written)
+        if not brief and d % 4 == 0 and G.stride(0) % 4 == 0:
+            def timed_us(fn, reps):
+                fn()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(reps):
+                    fn()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / reps * 1e3
+            vp = torch.empty(d, dtype=torch.float32, device=dev)
+            reps = 3 if slab_bytes > 4e9 else 20
+            best_r, best_w = None, None
+            for blocks in (2048, 4096, 16384):
+                t_r = timed_us(lambda: btard.debug_plain_stream(G, None, blocks), reps)
+                t_w = timed_us(lambda: btard.debug_plain_stream(G, vp, blocks), reps)
+                if best_r is None or t_r < best_r[0]:
+                    best_r = (t_r, blocks)
+                if best_w is None or t_w < best_w[0]:
+                    best_w = (t_w, blocks)
+            del vp
+            out["plain_kernel"] = {
+                "what": "btard_debug_plain_stream: a grid-stride kernel, one 16-byte load per row and "
+                        "thread, fp32 sums, non-temporal loads and stores; best of 2048, 4096 and "
+                        "16384 workgroups",
+                "rows_read": {"us": round(best_r[0], 2), "workgroups": best_r[1],
+                              "GBps": round(slab_bytes / (best_r[0] * 1e-6) / 1e9, 1)},
+                "rows_read_one_written": {"us": round(best_w[0], 2), "workgroups": best_w[1],
+                                          "GBps": round((slab_bytes + 4.0 * d) / (best_w[0] * 1e-6) / 1e9, 1)},
+            }
+
         # ---- the baseline aggregators on the same slab (not part of the headline step)
         if args.baselines and not brief:
             def timed(fn, reps):

@@ -86,6 +86,9 @@ def load_library():
     lib.btard_debug_gram.restype = c.c_int
     lib.btard_debug_last_pass.argtypes = [c.POINTER(_Problem), c.c_int32, c.c_void_p, c.c_uint64]
     lib.btard_debug_last_pass.restype = c.c_int
+    lib.btard_debug_plain_stream.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int64, c.c_void_p,
+                                             c.c_int32, c.c_void_p]
+    lib.btard_debug_plain_stream.restype = c.c_int
     lib.btard_cc_iterate.argtypes = [c.POINTER(_Problem), c.c_int32, c.c_int32]
     lib.btard_cc_iterate.restype = c.c_int
     lib.btard_cc_finish.argtypes = [c.POINTER(_Problem), c.c_int32, c.c_void_p, c.c_void_p,
@@ -323,6 +326,18 @@ def debug_last_pass(p: Problem, iterations: int, seed: int, v: torch.Tensor) -> 
     _check(load_library().btard_debug_last_pass(ctypes.byref(p.c), int(iterations), _ptr(v),
                                                 int(seed) & 0xFFFFFFFFFFFFFFFF),
            "btard_debug_last_pass")
+
+
+def debug_plain_stream(g: torch.Tensor, v: Optional[torch.Tensor], blocks: int) -> None:
+    """btard_debug_plain_stream: a plain grid-stride kernel that reads the rows of g and, if v
+    is given, writes their fp32 sum to it (a yardstick for the measured kernels)."""
+    n, d = g.shape
+    if v is not None and (v.dtype != torch.float32 or v.numel() != d or not v.is_contiguous()):
+        raise ValueError("v must be a contiguous float32 vector of length d")
+    _check(load_library().btard_debug_plain_stream(_ptr(g), _row_stride(g), n, d,
+                                                   _ptr(v) if v is not None else None, int(blocks),
+                                                   _stream_ptr(g.device)),
+           "btard_debug_plain_stream")
 
 
 def cc_finish_verify(p: Problem, iterations: int, seed: int, v: Optional[torch.Tensor] = None,
@@ -608,6 +623,7 @@ btard_cc_gram_iterate = cc_gram_iterate
 btard_cc_remaining = cc_remaining
 btard_debug_gram = debug_gram
 btard_debug_last_pass = debug_last_pass
+btard_debug_plain_stream = debug_plain_stream
 btard_cc_iterate = cc_iterate
 btard_cc_finish = cc_finish
 btard_verify_projections = verify_projections

@@ -161,3 +161,30 @@ def test_geometric_median_resnet18_partitions(dev):
         assert rel_l2(vh[lo:hi], vo) <= V_TOL
         assert sh[j] == pytest.approx(sno[0], rel=SCALAR_TOL, abs=1e-11)
         say(f"    partition {j}: iters={ito[0]} ok")
+
+
+# ---------------------------------------------------------------------------
+# The measurement yardstick (a plain streaming kernel; no part of the method): it has to
+# touch exactly what it says -- every row once, and v only when asked to.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n,d,ld,blocks", [(1, 4, 4, 1), (3, 1000, 1004, 2), (16, 70000, 70000, 7),
+                                           (64, 4096, 4100, 300), (255, 516, 516, 3)])
+def test_plain_stream_sums_the_rows(dev, n, d, ld, blocks):
+    say(f"[plain stream] n={n} d={d} ld={ld} blocks={blocks}")
+    gen = torch.Generator(device="cpu").manual_seed(9000 + n)
+    host = torch.randn((n, ld), generator=gen, dtype=torch.float32)
+    buf = host.to(dev)
+    G = buf[:, :d]
+    v = torch.full((d + 8,), -7.0, dtype=torch.float32, device=dev)
+    btard.debug_plain_stream(G, None, blocks)             # reads only
+    torch.cuda.synchronize()
+    assert (v == -7.0).all()
+    btard.debug_plain_stream(G, v[:d], blocks)
+    torch.cuda.synchronize()
+    # fp32 sums in the order of the peers, as the kernel adds them
+    want = torch.zeros(d, dtype=torch.float32)
+    for i in range(n):
+        want += host[i, :d]
+    assert torch.equal(v[:d].cpu(), want)
+    assert (v[d:] == -7.0).all()                          # nothing beyond d
+    assert torch.equal(buf.cpu(), host)                   # g untouched
