@@ -292,15 +292,70 @@ __device__ __forceinline__ void fold_scales(const CcState &st, int j, int n, int
     }
 }
 
+// The tile at xu (interior or not) of this lane group's rows, and of the start vector.
+template <int NP, int LG, bool RAGGED, bool HAS_BASE>
+__device__ __forceinline__ void pass_load_any(const CcArgs &a, int n, int lg, int sub, int64_t xu,
+                                              int64_t lo, int64_t hi, float (&val)[NP][4],
+                                              float (&base)[4])
+{
+    constexpr int kW = Geo<NP, LG>::kW;
+    const bool interior = (xu >= lo) && (xu + kW <= hi);   // wavefront-uniform
+    load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
+    if (HAS_BASE) {
+        const int64_t x0 = xu + (int64_t)sub * kVec;
+        if (interior) load_row4_vec(a.v0 + x0, base);
+        else load_row4_guarded(a.v0, x0, lo, hi, base);
+    }
+}
+
+// The same for an interior tile with one lane group.
+template <int NP, bool RAGGED, bool HAS_BASE>
+__device__ __forceinline__ void pass_load_interior(const CcArgs &a, int n, int sub, int64_t xu,
+                                                   uint32_t &lane_off, float (&val)[NP][4],
+                                                   float (&base)[4])
+{
+    load_tile_interior<NP, RAGGED>(a.g, a.ld, n, xu, lane_off, val);
+    if (HAS_BASE) load_row4_vec(a.v0 + xu + (int64_t)sub * kVec, base);
+}
+
+// One tile of a pass: v^l and the step direction on its 4 coordinates per lane, then the
+// residual norms ||g_i - v^l||^2 (masked coordinates hold zeros in every row).
+template <int NP, int LG, bool HAS_BASE, bool SCALED>
+__device__ __forceinline__ void pass_tile_sums(float (&val)[NP][4], const float (&base)[4],
+                                               const double (&c)[NP], const double (&dl)[NP],
+                                               double cb, double db, const double (&al)[NP], int lg,
+                                               double (&acc)[NP], double &t2)
+{
+    double vv[4], ss[4];
+    combine_rows<NP, LG, HAS_BASE>(val, base, c, dl, cb, db, vv, ss);
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) {
+            forget(val[k][e]);
+            double r;
+            if constexpr (SCALED) r = fma(al[k], (double)val[k][e], -vv[e]);
+            else r = (double)val[k][e] - vv[e];
+            acc[k] = fma(r, r, acc[k]);
+        }
+    }
+    if (lg == 0) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) t2 = fma(ss[e], ss[e], t2);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // one iteration: control step for the previous pass, then norms at v^l
 // ---------------------------------------------------------------------------
 // SCALED: with pre-clipping factors (a variant of its own: the factors cost 32 registers that
 // the plain pass does not pay for).
 template <int NP, int LG, bool RAGGED, bool HAS_BASE, bool SCALED>
-__global__ __launch_bounds__(kBlock, (LG == 1 && !SCALED ? 4 : 2)) void cc_pass_kernel(CcArgs a)
+__global__ __launch_bounds__(kBlock, (LG == 1 && !SCALED && NP <= 8 ? 4 : 2)) void cc_pass_kernel(CcArgs a)
 {
     using G = Geo<NP, LG>;
+    // (one lane group, no factors: the registers allow a second set of tile values)
+    constexpr bool kTwoSets = LG == 1 && !SCALED;
     __shared__ double s_c[kBlock], s_a[kBlock], s_red[kBlock];
     __shared__ int s_flags[2];
     __shared__ double sh[kWaves][G::kPeers + 1];
@@ -315,21 +370,18 @@ __global__ __launch_bounds__(kBlock, (LG == 1 && !SCALED ? 4 : 2)) void cc_pass_
     const int lg = lane / G::kLanes, sub = lane % G::kLanes;
     const TileRange tr = tile_range<G::kW>(lo, hi);
 
+    // (interior tiles, one lane group: scalar row base + the lane's byte offset)
+    uint32_t lane_off = (uint32_t)sub * (uint32_t)(kVec * sizeof(float));
+    const InteriorWalk iw = interior_walk<G::kW>(tr, lo, hi);
+
     // The first tile's loads do not depend on the coefficients: they are issued before the
     // control step and travel while it runs.
-    float val[NP][4];
-    float base[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    bool loaded = false;
-    if (tr.first < tr.units) {
-        const int64_t xu = tr.xa + tr.first * G::kW;
-        const bool interior = (xu >= lo) && (xu + G::kW <= hi);
-        load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
-        if (HAS_BASE) {
-            const int64_t x0 = xu + (int64_t)sub * kVec;
-            if (interior) load_row4_vec(a.v0 + x0, base);
-            else load_row4_guarded(a.v0, x0, lo, hi, base);
-        }
-        loaded = true;
+    float va[NP][4];
+    float base_a[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if constexpr (kTwoSets) {
+        if (iw.begin < iw.end) pass_load_interior<NP, RAGGED, HAS_BASE>(a, n, sub, tr.xa + iw.begin * G::kW, lane_off, va, base_a);
+    } else {
+        if (tr.first < tr.units) pass_load_any<NP, LG, RAGGED, HAS_BASE>(a, n, lg, sub, tr.xa + tr.first * G::kW, lo, hi, va, base_a);
     }
 
     int iters_now;
@@ -348,35 +400,46 @@ __global__ __launch_bounds__(kBlock, (LG == 1 && !SCALED ? 4 : 2)) void cc_pass_
     for (int k = 0; k < NP; ++k) acc[k] = 0.0;
     double t2 = 0.0;
 
-    for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
-        if (!loaded) {
-            const int64_t xu = tr.xa + u * G::kW;
-            const bool interior = (xu >= lo) && (xu + G::kW <= hi);   // wavefront-uniform
-            load_tile<NP, LG, RAGGED>(a.g, a.ld, n, lg, sub, xu, lo, hi, interior, val);
-            if (HAS_BASE) {
-                const int64_t x0 = xu + (int64_t)sub * kVec;
-                if (interior) load_row4_vec(a.v0 + x0, base);
-                else load_row4_guarded(a.v0, x0, lo, hi, base);
+    if constexpr (kTwoSets) {
+        // Interior tiles with two register sets taking turns: the loads of the wavefront's
+        // next tile are issued before the arithmetic of the current one.  On a small slab,
+        // where a wavefront has the compute unit almost to itself, its tiles then cost one
+        // memory latency together instead of one each.
+        if (iw.begin < iw.end) {
+            float vb[NP][4];
+            float base_b[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            int64_t u = iw.begin;
+            bool last_in_b = false;
+            for (;;) {
+                const int64_t u1 = u + tr.stride;
+                if (u1 >= iw.end) break;                 // the last tile is in va
+                pass_load_interior<NP, RAGGED, HAS_BASE>(a, n, sub, tr.xa + u1 * G::kW, lane_off, vb, base_b);
+                pass_tile_sums<NP, LG, HAS_BASE, SCALED>(va, base_a, c, dl, cb, db, al, lg, acc, t2);
+                const int64_t u2 = u1 + tr.stride;
+                if (u2 >= iw.end) {                      // the last tile is in vb
+                    last_in_b = true;
+                    break;
+                }
+                pass_load_interior<NP, RAGGED, HAS_BASE>(a, n, sub, tr.xa + u2 * G::kW, lane_off, va, base_a);
+                pass_tile_sums<NP, LG, HAS_BASE, SCALED>(vb, base_b, c, dl, cb, db, al, lg, acc, t2);
+                u = u2;
             }
+            if (last_in_b) pass_tile_sums<NP, LG, HAS_BASE, SCALED>(vb, base_b, c, dl, cb, db, al, lg, acc, t2);
+            else pass_tile_sums<NP, LG, HAS_BASE, SCALED>(va, base_a, c, dl, cb, db, al, lg, acc, t2);
         }
-        loaded = false;
-        double vv[4], ss[4];
-        combine_rows<NP, LG, HAS_BASE>(val, base, c, dl, cb, db, vv, ss);
-        // residual norms ||g_i - v^l||^2 (masked coordinates hold zeros in every row)
-#pragma unroll
-        for (int k = 0; k < NP; ++k) {
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) {
-                forget(val[k][e]);
-                double r;
-                if constexpr (SCALED) r = fma(al[k], (double)val[k][e], -vv[e]);
-                else r = (double)val[k][e] - vv[e];
-                acc[k] = fma(r, r, acc[k]);
-            }
+        // ... then the partition's first and last tile where they are not interior
+#pragma unroll 1
+        for (int t = 0; t < 2; ++t) {
+            const int64_t u = (t == 0) ? 0 : tr.units - 1;
+            if ((t == 1 && tr.units < 2) || tr.units < 1 || !owns_tile(tr, u)) continue;
+            if (tile_is_interior<G::kW>(tr.xa + u * G::kW, lo, hi)) continue;
+            pass_load_any<NP, LG, RAGGED, HAS_BASE>(a, n, lg, sub, tr.xa + u * G::kW, lo, hi, va, base_a);
+            pass_tile_sums<NP, LG, HAS_BASE, SCALED>(va, base_a, c, dl, cb, db, al, lg, acc, t2);
         }
-        if (lg == 0) {
-#pragma unroll
-            for (int e = 0; e < kVec; ++e) t2 = fma(ss[e], ss[e], t2);
+    } else {
+        for (int64_t u = tr.first; u < tr.units; u += tr.stride) {
+            if (u != tr.first) pass_load_any<NP, LG, RAGGED, HAS_BASE>(a, n, lg, sub, tr.xa + u * G::kW, lo, hi, va, base_a);
+            pass_tile_sums<NP, LG, HAS_BASE, SCALED>(va, base_a, c, dl, cb, db, al, lg, acc, t2);
         }
     }
 
