@@ -62,6 +62,8 @@ def recorded_traffic(kernel: str, cfg: int):
     WRITE_SIZE, scaled by a copy kernel of known size); the summaries of those profiler runs
     are kept under profiles/.  None if no such run is recorded for this configuration: a
     plain bench run cannot read hardware counters itself."""
+    if _OTHER_LENGTH:
+        return None
     tag = re.compile(r"^traffic_bytes_per_launch %s cfg%d:\s*([0-9.eE+]+)" % (re.escape(kernel), cfg))
     for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
         try:
@@ -73,6 +75,9 @@ def recorded_traffic(kernel: str, cfg: int):
         except OSError:
             pass
     return None
+
+
+_OTHER_LENGTH = False      # set by --d: the recorded counter runs are for the full lengths
 
 
 TRAFFIC_NOTE = ("traffic: HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
@@ -91,6 +96,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=0,
                     help="BASELINE configuration 1..5 alone (default: 5 as the headline, and "
                          "configurations 1-4 in short under per_config)")
+    ap.add_argument("--d", type=int, default=0,
+                    help="with --config: the same recipe at another vector length (a sensitivity "
+                         "run, e.g. a length that is not a power of two; not a BASELINE workload)")
     ap.add_argument("--no-per-config", action="store_true",
                     help="with no --config: leave out configurations 1-4")
     ap.add_argument("--mode", choices=("both", "headline", "streaming"), default="both")
@@ -115,6 +123,12 @@ def main() -> int:
                     help="also run plain device copies of known size (1 GiB read + 1 GiB "
                          "written) so that HBM counters of a profiler run can be scaled")
     args = ap.parse_args()
+    if args.d > 0:
+        if not args.config:
+            print("bench.py: --d needs --config", file=sys.stderr)
+            return 2
+        global _OTHER_LENGTH
+        _OTHER_LENGTH = True
 
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one process simulates all n peers); "
@@ -133,7 +147,7 @@ def main() -> int:
         """All figures of one configuration.  brief: the short form used for the per_config
         entries (no comparison variants, no extras).  cpu_baseline: thread counts to time
         the oracle with (0: all the host cores; empty: not at all)."""
-        wl = workloads.make_workload(cfg, device=dev)
+        wl = workloads.make_workload(cfg, device=dev, d=(args.d if args.d > 0 and args.config else None))
         G, off = wl.G, wl.offsets
         n, d, P, M = wl.n, wl.d, wl.parts, wl.max_iters
         sizes = [off[j + 1] - off[j] for j in range(P)]
