@@ -439,8 +439,8 @@ int btard_debug_last_pass(const btard_cc_problem *p, int32_t iterations, float *
  * written) or of the last pass (v != NULL: DEVICE v[0..d) receives the fp32 sum of the
  * rows, added in the order of the peers), launched with `blocks` workgroups of 256 threads
  * on `stream`.  It is the yardstick beside which bench.py reports the kernels of the method:
- * what a straightforward kernel reaches on the same slab.  d and ldg must be multiples of
- * 4 and g, v 16-byte aligned (BTARD_ERR_INVALID_ARG otherwise); 1 <= blocks <= 2^20.
+ * what a straightforward kernel reaches on the same slab.  ldg >= d >= 0, 1 <= n <= 255,
+ * 1 <= blocks <= 2^20 (BTARD_ERR_INVALID_ARG otherwise); rows need only be 4-byte aligned.
  */
 int btard_debug_plain_stream(const float *g, int64_t ldg, int32_t n, int64_t d, float *v,
                              int32_t blocks, void *stream);

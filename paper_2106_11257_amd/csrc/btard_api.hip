@@ -714,19 +714,13 @@ int btard_debug_plain_stream(const float *g, int64_t ldg, int32_t n, int64_t d, 
 {
     if (!g || n < 1 || n > kMaxPeers || d < 0 || ldg < d || blocks < 1 || blocks > (1 << 20))
         return BTARD_ERR_INVALID_ARG;
-    // (whole 16-byte columns only: this is a yardstick, not an entry point of the method)
-    if (d % 4 != 0 || ldg % 4 != 0 || reinterpret_cast<uintptr_t>(g) % 16 != 0 ||
-        reinterpret_cast<uintptr_t>(v) % 16 != 0)
-        return BTARD_ERR_INVALID_ARG;
     if (d == 0) return BTARD_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const f32x4_u *g4 = reinterpret_cast<const f32x4_u *>(g);
     if (v)
-        hipLaunchKernelGGL(plain_rowsum_kernel<true>, dim3(blocks), dim3(kBlock), 0, s, g4, ldg / 4, n,
-                           d / 4, reinterpret_cast<f32x4_u *>(v));
+        hipLaunchKernelGGL(plain_rowsum_kernel<true>, dim3(blocks), dim3(kBlock), 0, s, g, ldg, n, d, v);
     else
-        hipLaunchKernelGGL(plain_rowsum_kernel<false>, dim3(blocks), dim3(kBlock), 0, s, g4, ldg / 4, n,
-                           d / 4, static_cast<f32x4_u *>(nullptr));
+        hipLaunchKernelGGL(plain_rowsum_kernel<false>, dim3(blocks), dim3(kBlock), 0, s, g, ldg, n, d,
+                           static_cast<float *>(nullptr));
     return hipGetLastError() == hipSuccess ? BTARD_OK : BTARD_ERR_DEVICE;
 }
 

@@ -139,8 +139,8 @@ def test_argument_errors_are_caught_on_the_host_before_any_gpu_call():
         return lib.btard_debug_plain_stream(g, ld, n, d, v, blocks, None)
 
     assert plain(g=None) == -1 and plain(n=0) == -1 and plain(blocks=0) == -1
-    assert plain(d=6) == -1 and plain(ld=10, d=8) == -1          # whole 16-byte columns only
-    assert plain(g=ctypes.c_void_p(0x1004)) == -1 and plain(v=ctypes.c_void_p(0x2004)) == -1
+    assert plain(d=-1) == -1 and plain(ld=7, d=8) == -1 and plain(n=256) == -1
+    assert plain(blocks=(1 << 20) + 1) == -1
     assert plain(d=0, ld=0) == 0                                 # nothing to do
 
 

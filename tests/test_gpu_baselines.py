@@ -168,7 +168,8 @@ def test_geometric_median_resnet18_partitions(dev):
 # touch exactly what it says -- every row once, and v only when asked to.
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("n,d,ld,blocks", [(1, 4, 4, 1), (3, 1000, 1004, 2), (16, 70000, 70000, 7),
-                                           (64, 4096, 4100, 300), (255, 516, 516, 3)])
+                                           (64, 4096, 4100, 300), (255, 516, 516, 3),
+                                           (5, 3, 3, 2), (16, 70002, 70003, 5), (2, 1, 9, 1)])
 def test_plain_stream_sums_the_rows(dev, n, d, ld, blocks):
     say(f"[plain stream] n={n} d={d} ld={ld} blocks={blocks}")
     gen = torch.Generator(device="cpu").manual_seed(9000 + n)
