@@ -414,7 +414,8 @@ __global__ __launch_bounds__(kBlock, 2) void gram_pass_band_kernel(GramArgs a)
     const int64_t xa = tile_origin<B::kW>(lo);
     const int64_t units = (hi > lo) ? (hi - xa + B::kW - 1) / B::kW : 0;
     const int64_t stride = gridDim.x;
-    int64_t begin = blockIdx.x, end = units;
+    const int64_t bx = (blockIdx.x + blockIdx.y) % gridDim.x;     // (rotated as in tile_range)
+    int64_t begin = bx, end = units;
     if (units > 0 && !tile_is_interior<B::kW>(xa + (units - 1) * B::kW, lo, hi)) end = units - 1;
     if (begin == 0 && units > 0 && !tile_is_interior<B::kW>(xa, lo, hi)) begin = stride;
     const int64_t count = (begin < end) ? (end - begin + stride - 1) / stride : 0;
@@ -456,7 +457,7 @@ __global__ __launch_bounds__(kBlock, 2) void gram_pass_band_kernel(GramArgs a)
     for (int t = 0; t < 2; ++t) {
         const int64_t u = (t == 0) ? 0 : units - 1;
         if ((t == 1 && units < 2) || u < 0) continue;
-        if (u < blockIdx.x || (u - blockIdx.x) % stride != 0) continue;
+        if (u < bx || (u - bx) % stride != 0) continue;
         if (tile_is_interior<B::kW>(xa + u * B::kW, lo, hi)) continue;
         float ve[B::kRows][4];
 #pragma unroll
