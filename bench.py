@@ -500,6 +500,19 @@ def main() -> int:
                 "rows_read_one_written": {"us": round(best_w[0], 2), "workgroups": best_w[1],
                                           "GBps": round((slab_bytes + 4.0 * d) / (best_w[0] * 1e-6) / 1e9, 1)},
             }
+            # the method's kernels beside it (time of the plain kernel with the same traffic /
+            # time of the kernel: above 1 = faster than the plain kernel), which does not depend
+            # on how fast this particular machine's memory is
+            rel = {}
+            if ("streaming" in out and out["streaming"]["roofline"].get("avg_launch_us")
+                    and out["streaming"]["roofline"]["bytes_per_launch"] >= 0.999 * slab_bytes):
+                rel["cc_pass_kernel"] = round(best_r[0] / out["streaming"]["roofline"]["avg_launch_us"], 3)
+            kk = out.get("kernels", {})
+            if "gram_pass_kernel" in kk:
+                rel["gram_pass_kernel"] = round(best_r[0] / kk["gram_pass_kernel"].get("kernel_us", kk["gram_pass_kernel"]["us"]), 3)
+            if "cc_finish_verify_kernel" in kk:
+                rel["cc_finish_verify_kernel"] = round(best_w[0] / kk["cc_finish_verify_kernel"].get("kernel_us", kk["cc_finish_verify_kernel"]["us"]), 3)
+            out["plain_kernel"]["plain_time_over_kernel_time"] = rel
 
         # ---- the baseline aggregators on the same slab (not part of the headline step)
         if args.baselines and not brief:
