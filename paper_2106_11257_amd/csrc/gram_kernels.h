@@ -550,6 +550,46 @@ __device__ __forceinline__ void wide_multiply(const float (&val)[NB][S][4], cons
     }
 }
 
+// The operands of half a tile: fp64, absent peers (RAGGED) as zeros.
+template <int NB, bool RAGGED>
+__device__ __forceinline__ void wide_convert(float (&val)[NB][2][4], const bool (&have)[NB],
+                                             double (&d)[NB][2][4])
+{
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                d[b][s][e] = (RAGGED && !have[b]) ? 0.0 : (double)val[b][s][e];
+                // (converted before the loads that follow may overwrite the register)
+                asm volatile("" : "+v"(d[b][s][e]));
+            }
+        }
+    }
+}
+
+template <int NB>
+__device__ __forceinline__ void wide_multiply_f64(const double (&d)[NB][2][4],
+                                                  f64x4 (&acc)[NB * (NB + 1) / 2])
+{
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            int t = 0;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                for (int c = b; c < NB; ++c) {
+                    acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(d[b][s][e], d[c][s][e], acc[t], 0, 0, 0);
+                    ++t;
+                }
+            }
+        }
+    }
+}
+
 // RAGGED: n < 16 NB (rows beyond n are read from row n - 1 and replaced by zero).
 template <int NB, bool RAGGED>
 __global__ __launch_bounds__(kBlock, 2) void gram_pass_wide_kernel(GramArgs a)
@@ -578,31 +618,28 @@ __global__ __launch_bounds__(kBlock, 2) void gram_pass_wide_kernel(GramArgs a)
     const TileRange tr = tile_range<kW>(lo, hi);
     const InteriorWalk iw = interior_walk<kW>(tr, lo, hi);
     // Interior tiles, half a tile (32 coordinates, 80 matrix instructions at NB = 4) at a
-    // time: the loads of the next half are issued before the matrix instructions of the
-    // current one and copied over afterwards, so that the matrix unit does not wait for
-    // memory whenever both wavefronts of a SIMD run out of data at about the same time
-    // (4.5 GB slab with 64 peers: 1.33 against 1.41 ms with loads issued only when the
-    // previous tile is done; a whole tile ahead, 242 registers, 1.40 ms).  One loop body
-    // with a copy rather than two bodies taking turns: the compiler then keeps the 80
-    // accumulator registers in place instead of moving them once per round.
+    // time: the half's values are converted to fp64 operands, the loads of the next half are
+    // issued into the registers they leave, and then the matrix instructions run -- so the
+    // matrix unit does not wait for memory whenever both wavefronts of a SIMD run out of
+    // data at about the same time, and nothing is copied.  Vector and fp64 matrix
+    // instructions of a SIMD do not overlap on this chip, so every vector instruction saved
+    // counts: 4.5 GB slab with 64 peers 1.41 ms with loads issued only when the previous
+    // tile is done, 1.33 ms with the next half's loads ahead and a register copy per half,
+    // 1.27 ms in this form (a whole tile ahead, 242 registers: 1.40 ms; two loop bodies
+    // taking turns make the compiler move the 80 accumulator registers once per round).
     if (iw.begin < iw.end) {
-        float cur[NB][2][4], nxt[NB][2][4];
-        wide_fetch<NB, 2>(row, tr.xa + iw.begin * kW + 4 * q, cur);
+        float val[NB][2][4];
+        wide_fetch<NB, 2>(row, tr.xa + iw.begin * kW + 4 * q, val);
         for (int64_t u = iw.begin; u < iw.end; u += tr.stride) {
 #pragma unroll 1
             for (int h = 0; h < 2; ++h) {
-                // the half after this one: the tile's second half, or the next tile's first
+                // this half's values as fp64 operands, then the next half's loads (the tile's
+                // second half, or the next tile's first) into the registers they leave
+                double d[NB][2][4];
+                wide_convert<NB, RAGGED>(val, have, d);
                 const int64_t xn = (h == 0) ? tr.xa + u * kW + 32 : tr.xa + (u + tr.stride) * kW;
-                if (h == 0 || u + tr.stride < iw.end) wide_fetch<NB, 2>(row, xn + 4 * q, nxt);
-                wide_multiply<NB, RAGGED, 2>(cur, have, acc);
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-#pragma unroll
-                    for (int s = 0; s < 2; ++s) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) cur[b][s][e] = nxt[b][s][e];
-                    }
-                }
+                if (h == 0 || u + tr.stride < iw.end) wide_fetch<NB, 2>(row, xn + 4 * q, val);
+                wide_multiply_f64<NB>(d, acc);
             }
         }
     }
