@@ -467,6 +467,47 @@ def main() -> int:
                                     "frac_of_hbm_peak": round(rate / HBM_PEAK_GBPS, 4)})
             out["roofline"]["traffic_note"] = TRAFFIC_NOTE
 
+        # ---- one GPU's share if the partitions were spread over n GPUs: partition 0 alone (all n
+        # peers' rows of its columns), the shape one aggregator of the paper's protocol works on
+        if not brief and n <= 64 and args.mode != "streaming" and P > 1:
+            G1 = G[:, off[0]:off[1]]
+            d1 = off[1] - off[0]
+            off1 = [0, d1]
+            ws1 = btard.alloc_workspace(n, 1, dev)
+            v1 = torch.empty(d1, dtype=torch.float32, device=dev)
+            it1 = torch.empty(1, dtype=torch.int32, device=dev)
+            sn1 = torch.empty(1, dtype=torch.float64, device=dev)
+            out1 = {k: torch.empty((n, 1), dtype=torch.float64, device=dev)
+                    for k in ("norms", "weights", "proj")}
+            out1["colsum"] = torch.empty(1, dtype=torch.float64, device=dev)
+            prob1 = btard.make_problem(G1, off1, wl.tau, wl.eps, M, workspace=ws1,
+                                       flags=headline_flags, preclip=lam)
+
+            def share_step():
+                btard.cc_gram_matrix(prob1)
+                btard.cc_gram_iterate(prob1)
+                passes1 = btard.cc_remaining(prob1)          # (host sync: the share is timed with it)
+                btard.cc_iterate(prob1, 0, passes1)
+                btard.cc_finish_verify(prob1, passes1, wl.seed_z, v1, it1, sn1, out=out1)
+            for _ in range(2):
+                share_step()
+            torch.cuda.synchronize()
+            reps = 5
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                share_step()
+            torch.cuda.synchronize()
+            ms1 = (time.perf_counter() - t0) * 1e3 / reps
+            iters1 = int(it1.cpu()[0])
+            out["one_gpu_share"] = {
+                "what": "partition 0 alone: the n x d/P slab one aggregator holds when the partitions "
+                        "are spread over P GPUs (no communication timed); whole step with one host "
+                        "synchronisation",
+                "d": d1, "iters": iters1, "ms_per_step": round(ms1, 4),
+                "value": round(4.0 * n * d1 * max(iters1, 0) / (ms1 * 1e-3) / 1e9, 1), "unit": "GB/s",
+                "physical_GBps": round((2.0 * 4.0 * n * d1 + 4.0 * d1) / (ms1 * 1e-3) / 1e9, 1)}
+            del G1, v1, ws1
+
         # ---- a plain grid-stride kernel on the same slab: what a straightforward kernel reaches
         # with the traffic of a pass (rows read) and of the last pass (rows read, one row written)
         if not brief:
