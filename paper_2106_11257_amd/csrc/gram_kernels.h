@@ -714,6 +714,10 @@ constexpr double kGramUnit = 1.4210854715202004e-14;
 // The Gram iteration vouches for a squared norm whose error bar is below this fraction of
 // it (1e-8 relative on the norm: four orders inside the tolerance of the projections).
 constexpr double kGramVouch = 2e-8;
+// ... and only if rounding v to fp32 cannot move a norm by 1e-6 of itself (see where they
+// are used): squares of 0.34 and of 6e-5.
+constexpr double kGramRoundSpread = 0.1156;
+constexpr double kGramRoundFloor = 3.6e-9;
 
 // Value of lane `k` (a compile-time constant) for every lane: two v_readlane into scalar
 // registers, no LDS traffic.
@@ -1091,7 +1095,20 @@ __global__ __launch_bounds__(kBlock) void gram_iterate_kernel(GramIterArgs a)
         const double eN2 = kGramUnit * (rt + Sf) * (rt + Sf);
         T2f = fmax(Tf, 0.0);
         const double eT2 = kGramUnit * Sa * Sa;
-        const bool bad = peer && !(eN2 <= kGramVouch * N2f);
+        bool bad = peer && !(eN2 <= kGramVouch * N2f);
+        // These norms are those at the unrounded v = sum_i c_i g_i; what goes out, and what
+        // the verification is of, is v rounded to fp32.  The rounding moves a norm by at
+        // most 2^-24 ||v|| in absolute terms, which no tolerance here notices unless the
+        // norm is tiny beside ||v||: ||g_i - v - er||^2 = ||g_i - v||^2 - 2 <g_i - v, er> +
+        // ||er||^2, where the middle term has a standard deviation of 3.4e-8 ||g_i - v|| ||v||
+        // / sqrt(d_j) if the rounding errors er are taken as independent of each other and of
+        // the residual (uniform within half a unit in the last place), and the last one is
+        // at most 2^-48 ||v||^2.  A partition is vouched for only if ten such deviations and
+        // the last term are each below 1e-6 of every squared norm's root, i.e.
+        // ||g_i - v|| >= 0.34 ||v|| / sqrt(d_j) and >= 6e-5 ||v||; otherwise the last pass
+        // measures its norms against the rounded v.  (qf = ||v||^2.)
+        const double dj = (double)(a.st.off[j + 1] - a.st.off[j]);
+        bad = bad || (peer && !(N2f * dj >= kGramRoundSpread * qf && N2f >= kGramRoundFloor * qf));
         ok = !__any(bad) && (eT2 <= kGramVouch * T2f || Sa == 0.0);
     }
     if (t < n) {                                  // (N = 16: lanes 0..15 hold peers 0..15)
