@@ -1,0 +1,135 @@
+"""GPU parity on seeded random small shapes: peer counts on both sides of every kernel
+variant's limits, partitions from empty to a few hundred thousand coordinates, padded and
+dense rows, every path (per-iteration passes, Gram formulation with and without the host
+synchronisation, caller's start vector, pre-clipping, stand-alone verification with the
+clipped residuals, the baseline aggregators), each compared with the fp64 oracle at the
+tolerances of test_gpu_parity.py.  The shapes are drawn from a fixed seed: the same cases
+every run."""
+import random
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2106_11257_amd as btard
+from paper_2106_11257_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+V_TOL = 1e-5
+PROJ_TOL = 1e-4
+SCALAR_TOL = 1e-6
+PEERS = [1, 2, 3, 4, 5, 7, 8, 9, 12, 15, 16, 17, 24, 31, 32, 33, 48, 63, 64, 65, 100]
+GRAM = btard.BTARD_FLAG_GRAM
+SYNC = btard.BTARD_FLAG_GRAM | btard.BTARD_FLAG_HOST_SYNC
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch.device("cuda:0")
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def rel_l2(a, b):
+    den = np.linalg.norm(b)
+    return np.linalg.norm(a - b) / den if den > 0 else np.linalg.norm(a - b)
+
+
+def draw(rng, case, dev, base_seed):
+    n = rng.choice(PEERS)
+    P = rng.choice([1, 2, 3, 5, 8, 16])
+    d = rng.choice([rng.randint(1, 40), rng.randint(200, 3000), rng.randint(3000, 40000),
+                    rng.randint(40000, 200000)])
+    if n > 64:
+        d = min(d, 20000)
+    ld = d + rng.choice([0, 0, 1, 3, 4, 29])
+    G, off = workloads.generic_case(n, d, P, seed=base_seed + case, device=dev, ld=ld,
+                                    outliers=rng.choice([0, n // 4, n // 3]),
+                                    outlier_scale=rng.choice([3.0, 50.0]))
+    tau = rng.choice([0.05, 0.3, 1.0, 3.0, 30.0])
+    eps = rng.choice([0.0, 1e-6, 1e-3])
+    M = rng.choice([0, 1, 2, 7, 20, 50])
+    flags = rng.choice([0, GRAM, SYNC])
+    return G, off, tau, eps, M, flags
+
+
+def check_verification(out, ref):
+    np.testing.assert_allclose(out["norms"].cpu().numpy(), ref["norms"], rtol=SCALAR_TOL, atol=1e-12)
+    np.testing.assert_allclose(out["weights"].cpu().numpy(), ref["weights"], rtol=SCALAR_TOL)
+    if np.abs(ref["proj"]).max() > 1e-12:
+        assert rel_l2(out["proj"].cpu().numpy(), ref["proj"]) <= PROJ_TOL
+
+
+def test_centered_clip_with_verification_on_random_shapes(dev):
+    rng = random.Random(20240611)
+    for case in range(60):
+        G, off, tau, eps, M, flags = draw(rng, case, dev, 7000)
+        use_v0 = rng.random() < 0.15
+        say(f"[random cc] case {case}: n={G.shape[0]} d={G.shape[1]} ld={G.stride(0)} P={len(off) - 1} "
+            f"tau={tau} eps={eps} M={M} flags={flags} v0={use_v0}")
+        v0 = torch.randn(G.shape[1], device=dev) if use_v0 else None
+        seed = 99 + case
+        v, iters, sn, out = btard.centered_clip_verify(G, off, tau, eps, M, seed, v0=v0, flags=flags)
+        torch.cuda.synchronize()
+        Gh = G.cpu().numpy()
+        v0h = None if v0 is None else v0.cpu().numpy().astype(np.float64)
+        vo, ito, sno, _ = oracle.centered_clip(Gh, off, tau, eps, M, v0=v0h)
+        np.testing.assert_array_equal(iters.cpu().numpy(), ito)
+        assert rel_l2(v.cpu().numpy(), vo) <= V_TOL
+        np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=SCALAR_TOL, atol=1e-11)
+        check_verification(out, oracle.verify(Gh, off, v.cpu().numpy().astype(np.float64), tau, seed))
+
+
+def test_other_entry_points_on_random_shapes(dev):
+    rng = random.Random(20240612)
+    for case in range(60):
+        G, off, tau, eps, M, flags = draw(rng, case, dev, 9000)
+        kind = rng.choice(["preclip", "verify", "median", "weiszfeld"])
+        n, d = G.shape
+        say(f"[random {kind}] case {case}: n={n} d={d} ld={G.stride(0)} P={len(off) - 1} tau={tau} "
+            f"eps={eps} M={M} flags={flags}")
+        Gh = G.cpu().numpy()
+        seed = 555 + case
+        if kind == "preclip":
+            norms0 = np.linalg.norm(Gh.astype(np.float64)[:, off[0]:off[1]], axis=1)
+            lam = float(np.float32(rng.choice([0.3, 1.0, 3.0]) * max(np.median(norms0), 1e-3)))
+            v, iters, sn, out, fac = btard.centered_clip_verify_preclipped(G, off, lam, tau, eps, M, seed,
+                                                                           flags=flags)
+            torch.cuda.synchronize()
+            alpha, _ = oracle.preclip_scales(Gh, off, lam)
+            np.testing.assert_allclose(fac.cpu().numpy(), alpha, rtol=1e-12)
+            vo, ito, sno, _ = oracle.centered_clip(Gh, off, tau, eps, M, scale=alpha)
+            np.testing.assert_array_equal(iters.cpu().numpy(), ito)
+            assert rel_l2(v.cpu().numpy(), vo) <= V_TOL
+            np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=SCALAR_TOL, atol=1e-11)
+            check_verification(out, oracle.verify(Gh, off, v.cpu().numpy().astype(np.float64), tau,
+                                                  seed, scale=alpha))
+        elif kind == "verify":
+            v = torch.randn(d, device=dev) * 0.5 + G[: max(1, n // 2)].mean(dim=0)
+            want_delta = n * d < 3_000_000
+            out = btard.verify_projections(G, off, v, tau, seed, want_delta=want_delta)
+            torch.cuda.synchronize()
+            ref = oracle.verify(Gh, off, v.cpu().numpy().astype(np.float64), tau, seed,
+                                want_delta=want_delta)
+            check_verification(out, ref)
+            if want_delta:
+                assert rel_l2(out["delta"].cpu().numpy(), ref["delta"]) <= SCALAR_TOL
+        elif kind == "median":
+            vm = btard.coordinate_median(G)
+            torch.cuda.synchronize()
+            assert np.array_equal(vm.cpu().numpy(), oracle.coordinate_median(Gh).astype(np.float32))
+        else:
+            nu = rng.choice([1e-6, 1e-3, 1.0])
+            v, iters, sn = btard.geometric_median(G, off, nu, eps, M)
+            torch.cuda.synchronize()
+            vo, ito, _ = oracle.geometric_median(Gh, off, nu, eps, M)[:3]
+            np.testing.assert_array_equal(iters.cpu().numpy(), ito)
+            assert rel_l2(v.cpu().numpy(), vo) <= V_TOL
