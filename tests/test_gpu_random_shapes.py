@@ -133,3 +133,93 @@ def test_other_entry_points_on_random_shapes(dev):
             vo, ito, _ = oracle.geometric_median(Gh, off, nu, eps, M)[:3]
             np.testing.assert_array_equal(iters.cpu().numpy(), ito)
             assert rel_l2(v.cpu().numpy(), vo) <= V_TOL
+
+
+def test_hashes_schedule_noalloc_and_poisoned_rows_on_random_shapes(dev):
+    import math
+    rng = random.Random(20240613)
+    for case in range(60):
+        G, off, tau, eps, M, flags = draw(rng, case, dev, 11000)
+        M = max(M, 1)
+        n, d = G.shape
+        P = len(off) - 1
+        kind = rng.choice(["hash", "schedule", "noalloc", "verify preclipped", "poisoned"])
+        say(f"[random {kind}] case {case}: n={n} d={d} ld={G.stride(0)} P={P} tau={tau} eps={eps} "
+            f"M={M} flags={flags}")
+        Gh = G.cpu().numpy()
+        seed = 777 + case
+        if kind == "hash":
+            if n * d > 2_000_000:
+                continue
+            dig = btard.partition_hashes(G, off)
+            torch.cuda.synchronize()
+            assert np.array_equal(dig.cpu().numpy(), oracle.partition_hashes(Gh, off))
+        elif kind == "schedule":
+            # eq. (5)'s radii through the phased calls, the iterations in two chunks
+            w = math.sqrt(max(d / P, 1.0))
+            sched = btard.tau_schedule(0.1, 0.05 * w / 6.0, 40.0 * w, M)
+            p = btard.make_problem(G, off, tau, eps, M, flags=(flags & GRAM), tau_schedule=sched)
+            btard.cc_begin(p)
+            btard.cc_gram(p)
+            left = btard.cc_remaining(p)
+            btard.cc_iterate(p, 0, left // 2)
+            btard.cc_iterate(p, left // 2, left - left // 2)
+            v, iters, sn, out = btard.cc_finish_verify(p, left, seed)
+            torch.cuda.synchronize()
+            vo, ito, sno, _ = oracle.centered_clip(Gh, off, tau, eps, M, tau_l=sched)
+            np.testing.assert_array_equal(iters.cpu().numpy(), ito)
+            assert rel_l2(v.cpu().numpy(), vo) <= V_TOL
+            np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=SCALAR_TOL, atol=1e-11)
+            check_verification(out, oracle.verify(Gh, off, v.cpu().numpy().astype(np.float64), tau, seed))
+        elif kind == "noalloc":
+            if btard.workspace_bytes(n, P) > (12 << 20):
+                continue
+            fl = flags & GRAM
+            v = torch.empty(d, device=dev)
+            iters = torch.empty(P, dtype=torch.int32, device=dev)
+            sn = torch.empty(P, dtype=torch.float64, device=dev)
+            out = {k: torch.empty((n, P), dtype=torch.float64, device=dev)
+                   for k in ("norms", "weights", "proj")}
+            out["colsum"] = torch.empty(P, dtype=torch.float64, device=dev)
+            btard.centered_clip_verify_noalloc(G, off, tau, eps, M, seed, v, iters, sn, out, flags=fl)
+            v2, it2, sn2, out2 = btard.centered_clip_verify(G, off, tau, eps, M, seed, flags=fl)
+            torch.cuda.synchronize()
+            assert torch.equal(v, v2) and torch.equal(iters, it2) and torch.equal(sn, sn2)
+            for k in ("norms", "weights", "proj", "colsum"):
+                assert torch.equal(out[k], out2[k]), k
+        elif kind == "verify preclipped":
+            norms0 = np.linalg.norm(Gh.astype(np.float64)[:, off[0]:off[1]], axis=1)
+            lam = float(np.float32(rng.choice([0.3, 1.0, 3.0]) * max(np.median(norms0), 1e-3)))
+            alpha, _ = oracle.preclip_scales(Gh, off, lam)
+            v = torch.randn(d, device=dev) * 0.5 + G[: max(1, n // 2)].mean(dim=0)
+            want_delta = n * d < 2_000_000
+            if rng.random() < 0.5:
+                out = btard.verify_projections_preclipped(G, off, v, tau, seed, lam=lam,
+                                                          want_delta=want_delta)
+            else:
+                out = btard.verify_projections_preclipped(
+                    G, off, v, tau, seed, factors=torch.tensor(alpha, dtype=torch.float64, device=dev),
+                    want_delta=want_delta)
+            torch.cuda.synchronize()
+            ref = oracle.verify(Gh, off, v.cpu().numpy().astype(np.float64), tau, seed, scale=alpha,
+                                want_delta=want_delta)
+            check_verification(out, ref)
+            if want_delta:
+                assert rel_l2(out["delta"].cpu().numpy(), ref["delta"]) <= SCALAR_TOL
+        else:
+            # one Inf or NaN: its partition reports -1, every other partition is untouched
+            clean_v, clean_it, _ = btard.centered_clip(G, off, tau, eps, M, flags=flags)
+            i, x = rng.randrange(n), rng.randrange(d)
+            jbad = next(j for j in range(P) if off[j] <= x < off[j + 1])
+            buf = torch.empty((n, G.stride(0)), device=dev)
+            buf[:, :d] = G
+            G2 = buf[:, :d]
+            G2[i, x] = rng.choice([float("inf"), float("-inf"), float("nan")])
+            v, iters, _ = btard.centered_clip(G2, off, tau, eps, M, flags=flags)
+            torch.cuda.synchronize()
+            it, itc = iters.cpu().numpy(), clean_it.cpu().numpy()
+            assert it[jbad] == -1
+            for j in range(P):
+                if j != jbad:
+                    assert it[j] == itc[j]
+                    assert torch.equal(v[off[j]:off[j + 1]], clean_v[off[j]:off[j + 1]])
