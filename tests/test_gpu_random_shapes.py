@@ -223,3 +223,66 @@ def test_hashes_schedule_noalloc_and_poisoned_rows_on_random_shapes(dev):
                 if j != jbad:
                     assert it[j] == itc[j]
                     assert torch.equal(v[off[j]:off[j + 1]], clean_v[off[j]:off[j + 1]])
+
+
+def test_gram_stopping_rule_and_hand_over_on_random_noise_levels(dev):
+    """Rows mu + noise with the noise from 1e-7 to 3 times the common part, the common part
+    from 1e-3 to 1e3, radii from 1e-2 to 1e2 times the spread, tolerances down to 1e-9 of
+    the scale, attackers of four kinds: the cases in which the Gram iteration must decide,
+    within its error bars, to stop where the plain iteration stops or to hand over.  Both
+    paths against the oracle; iteration counts identical."""
+    import math
+    rng = random.Random(20240614)
+    handed = 0
+    for case in range(50):
+        n = rng.choice([2, 3, 5, 8, 9, 13, 16, 17, 30, 48, 64])
+        P = rng.choice([1, 2, 4, 7])
+        d = rng.choice([rng.randint(50, 3000), rng.randint(3000, 60000), rng.randint(60000, 200000)])
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(13000 + case)
+        scale = 10.0 ** rng.uniform(-3, 3)
+        sigma = 10.0 ** rng.uniform(-7, 0.5)
+        mu = scale * torch.randn(d, generator=gen, device=dev)
+        G = mu[None, :] + (sigma * scale) * torch.randn((n, d), generator=gen, device=dev)
+        nbyz = rng.choice([0, 0, n // 4, n // 3])
+        for i in range(n - nbyz, n):
+            kind = rng.choice(["flip", "far", "copy", "zero"])
+            if kind == "flip":
+                G[i] = -rng.choice([1.0, 10.0, 1000.0]) * G[i]
+            elif kind == "far":
+                G[i] = G[i] + scale * rng.choice([1.0, 100.0]) * torch.randn(d, generator=gen, device=dev)
+            elif kind == "copy":
+                G[i] = G[0]
+            else:
+                G[i].zero_()
+        off = btard.split_offsets(d, P)
+        spread = sigma * scale * math.sqrt(d / P)
+        tau = spread * 10.0 ** rng.uniform(-2, 2)
+        eps = rng.choice([0.0, 1e-6, 1e-9 * scale * math.sqrt(d / P), 1e-3 * spread])
+        M = rng.choice([1, 3, 10, 40, 120])
+        flags = rng.choice([GRAM, SYNC])
+        say(f"[random noise] case {case}: n={n} d={d} P={P} scale={scale:.3g} sigma={sigma:.3g} "
+            f"attackers={nbyz} tau={tau:.4g} eps={eps:.4g} M={M} flags={flags}")
+        seed = 31 + case
+        p = btard.make_problem(G, off, tau, eps, M, flags=GRAM)
+        btard.cc_begin(p)
+        btard.cc_gram(p)
+        handed += btard.cc_remaining(p) > 0
+        v, iters, sn, out = btard.centered_clip_verify(G, off, tau, eps, M, seed, flags=flags)
+        vs, its, sns = btard.centered_clip(G, off, tau, eps, M)
+        torch.cuda.synchronize()
+        Gh = G.cpu().numpy()
+        vo, ito, sno, _ = oracle.centered_clip(Gh, off, tau, eps, M)
+        np.testing.assert_array_equal(iters.cpu().numpy(), ito)
+        np.testing.assert_array_equal(its.cpu().numpy(), ito)
+        assert rel_l2(v.cpu().numpy(), vo) <= V_TOL and rel_l2(vs.cpu().numpy(), vo) <= V_TOL
+        atol = 1e-11 * max(scale, 1.0)
+        np.testing.assert_allclose(sn.cpu().numpy(), sno, rtol=SCALAR_TOL, atol=atol)
+        np.testing.assert_allclose(sns.cpu().numpy(), sno, rtol=SCALAR_TOL, atol=atol)
+        ref = oracle.verify(Gh, off, v.cpu().numpy().astype(np.float64), tau, seed)
+        np.testing.assert_allclose(out["norms"].cpu().numpy(), ref["norms"], rtol=SCALAR_TOL,
+                                   atol=1e-9 * scale)
+        np.testing.assert_allclose(out["weights"].cpu().numpy(), ref["weights"], rtol=SCALAR_TOL,
+                                   atol=1e-12)
+        assert rel_l2(out["proj"].cpu().numpy(), ref["proj"]) <= PROJ_TOL
+    assert handed >= 5            # (the sweep does reach the hand-over)
