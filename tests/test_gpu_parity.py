@@ -981,3 +981,52 @@ def test_configs_full_size_partition_against_the_oracle(dev, cfg, j):
                                    err_msg=where)
         scale = np.abs(ref["proj"][:, 0]).sum()
         assert abs(o["colsum"][j] - ref["colsum"][0]) <= PROJ_TOL * scale + 1e-300, where
+
+
+def test_coordinates_beyond_two_to_the_31(dev):
+    """Vector length above 2^31: coordinate indices, tile origins and the counter of the
+    generator behind zhat need their 64 bits.  Three rows of 2^31 + 5000 coordinates in three
+    partitions; the last partition, which ends beyond 2^31, is compared with the oracle on
+    both paths, zhat is compared across the boundary, and so is the coordinate-wise median."""
+    _drop_full_run()
+    n, d, P = 3, (1 << 31) + 5000, 3
+    free, _ = torch.cuda.mem_get_info()
+    need = 4.0 * n * d * 2.2 + 4.0 * d * 3 + (2 << 30)
+    if free < need:
+        pytest.skip(f"needs {need / 2**30:.0f} GiB of device memory")
+    say(f"[large index] n={n} d={d} P={P}")
+    G, off = workloads.generic_case(n, d, P, seed=31, device=dev, spread=0.3, outliers=1,
+                                    outlier_scale=3.0)
+    assert off == btard.split_offsets(d, P) and off[2] < (1 << 31) < off[3]
+    tau, eps, M, seed = 2000.0, 0.0, 3, 0x1F00D
+    j = P - 1
+    lo, hi = off[j], off[j + 1]
+    sub = np.empty((n, hi - lo), dtype=np.float32)
+    for i in range(n):
+        sub[i] = G[i, lo:hi].cpu().numpy()
+    vo, ito, sno, _ = oracle.centered_clip(sub, [0, hi - lo], tau, eps, M)
+    znorm = oracle.z_norm(seed, d)
+    for flags in (0, btard.BTARD_FLAG_GRAM):
+        say(f"    flags={flags}")
+        v, iters, sn, out = btard.centered_clip_verify(G, off, tau, eps, M, seed, flags=flags)
+        torch.cuda.synchronize()
+        vj = v[lo:hi].cpu().numpy()
+        assert int(iters[j]) == ito[0]
+        assert rel_l2(vj, vo) <= V_TOL
+        assert float(sn[j]) == pytest.approx(sno[0], rel=SCALAR_TOL, abs=1e-11)
+        ref = oracle.verify(sub, [0, hi - lo], vj.astype(np.float64), tau, seed, x_base=lo, znorm=znorm)
+        assert rel_l2(out["proj"][:, j].cpu().numpy(), ref["proj"][:, 0]) <= PROJ_TOL
+        np.testing.assert_allclose(out["norms"][:, j].cpu().numpy(), ref["norms"][:, 0], rtol=SCALAR_TOL)
+        np.testing.assert_allclose(out["weights"][:, j].cpu().numpy(), ref["weights"][:, 0], rtol=SCALAR_TOL)
+        del v, out
+    # zhat on both sides of 2^31 (it is a function of the global coordinate)
+    x0 = (1 << 31) - 40
+    z = btard.debug_zhat(seed, x0, 96, dev).cpu().numpy().astype(np.float64)
+    zo = oracle.z_hat(seed, x0, 96)
+    assert np.abs(z - zo).max() <= 2e-6 * max(1.0, np.abs(zo).max())
+    # the median, on a window that ends at d
+    vm = btard.coordinate_median(G)
+    torch.cuda.synchronize()
+    w0 = d - 20000
+    want = oracle.coordinate_median(np.ascontiguousarray(sub[:, w0 - lo:])).astype(np.float32)
+    assert np.array_equal(vm[w0:].cpu().numpy(), want)
