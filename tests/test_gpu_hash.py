@@ -87,6 +87,19 @@ def test_full_size_resnet18_slab(dev):
     check(wl.G, wl.offsets, "cfg2")
 
 
+def test_a_partition_beyond_four_gibibytes(dev):
+    """One row of 2^30 + 2^28 + 333 coordinates as a single partition: byte offsets beyond
+    2^32, 5.2 million chunks, four levels of the tree."""
+    d = (1 << 30) + (1 << 28) + 333
+    free, _ = torch.cuda.mem_get_info()
+    if free < 4.0 * d * 1.5 + (2 << 30):
+        pytest.skip("needs 10 GiB of device memory")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    v = torch.empty(d, device=dev).normal_(generator=gen)
+    check(v, [0, d], "one partition of 5.4 GB")
+
+
 def test_bad_arguments(dev):
     G = torch.zeros((2, 64), device=dev)
     with pytest.raises(btard.BtardError):
