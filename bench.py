@@ -469,7 +469,9 @@ def main() -> int:
 
         # ---- one GPU's share if the partitions were spread over n GPUs: partition 0 alone (all n
         # peers' rows of its columns), the shape one aggregator of the paper's protocol works on
-        if not brief and n <= 64 and args.mode != "streaming" and P > 1:
+        # (in the default run only: with --config the run is what the profiler commands under
+        # profiles/ trace, and these smaller launches of the same kernels would blur their averages)
+        if not brief and not args.config and n <= 64 and args.mode != "streaming" and P > 1:
             G1 = G[:, off[0]:off[1]]
             d1 = off[1] - off[0]
             off1 = [0, d1]
