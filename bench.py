@@ -698,7 +698,11 @@ def main() -> int:
             for c in (1, 2, 3, 4, 5):
                 if c == head or not fits(c):
                     continue
-                r = measured(c, max(4, args.steps // 2), max(2, args.warmup), True,
+                # (the two small slabs take more, shorter steps: their kernels are tens of
+                # microseconds, and a dozen steps end before the clocks have settled)
+                small = c in (1, 2)
+                r = measured(c, 40 if small else max(4, args.steps // 2),
+                             10 if small else max(2, args.warmup), True,
                              [1] if (c == 1 and cpu) else [])
                 e = {"workload": r["config"]["workload"],
                      "iters_min": r["config"].get("iters_min"), "iters_max": r["config"].get("iters_max"),
