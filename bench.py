@@ -99,6 +99,9 @@ def main() -> int:
     ap.add_argument("--d", type=int, default=0,
                     help="with --config: the same recipe at another vector length (a sensitivity "
                          "run, e.g. a length that is not a power of two; not a BASELINE workload)")
+    ap.add_argument("--entry", action="store_true",
+                    help="with --config: print that configuration's entry of the default run's "
+                         "per_config block (the default run starts one such process per configuration)")
     ap.add_argument("--no-per-config", action="store_true",
                     help="with no --config: leave out configurations 1-4")
     ap.add_argument("--mode", choices=("both", "headline", "streaming"), default="both")
@@ -677,43 +680,67 @@ def main() -> int:
         free, _total = torch.cuda.mem_get_info()
         return free >= 4.0 * n_c * d_c * 1.08 + (2 << 30)
 
-    def measured(*a):
+    def measured(*a, release=True):
         r = measure(*a)
         gc.collect()                      # (the slab and the outputs of this configuration)
-        torch.cuda.empty_cache()
+        if release:
+            torch.cuda.empty_cache()
         return r
 
     cpu = [] if args.no_cpu_baseline else [0]
-    if args.config:
+    if args.config and args.entry:
+        # one entry of the default run's per_config block (see below)
+        c = args.config
+        small = c in (1, 2)          # (more, shorter steps: their kernels are tens of microseconds)
+        r = measured(c, 40 if small else max(4, args.steps // 2),
+                     10 if small else max(2, args.warmup), True, [1] if (c == 1 and cpu) else [])
+        keys = ("value", "ms_per_step", "physical", "roofline", "kernels", "segments_ms")
+        out = {"workload": r["config"]["workload"],
+               "iters_min": r["config"].get("iters_min"), "iters_max": r["config"].get("iters_max"),
+               "mode": r["config"].get("mode")}
+        out.update({k: r[k] for k in keys if k in r})
+        if "streaming" in r:
+            out["streaming"] = {k: r["streaming"][k] for k in ("ms_per_step", "roofline")}
+        for k in r:
+            if k.startswith("cpu_baseline"):
+                out[k] = r[k]
+    elif args.config:
         out = measured(args.config, args.steps, args.warmup, False,
                        cpu + ([1] if cpu and args.config == 1 else []))
     else:
-        # the largest configuration that fits this GPU is the headline ...
+        # The largest configuration that fits this GPU is the headline and is measured first,
+        # on the device as it was handed over.  The others are measured in short (same recipe,
+        # fewer steps), each in a process of its own, while this process still holds the
+        # headline's memory (in torch's allocator): a slab that is allocated after others have
+        # been allocated and given back to the driver -- by this process or by an earlier one --
+        # lands where every kernel on it runs 2-7 % slower (64 MiB slab after the 84 GB one:
+        # 17.3 against 16.1 us per pass; the 84 GB slab after the four others, in this or in
+        # other processes: 26.5-27.7 against 25.8-26.3 ms per step).
         head = next((c for c in (5, 4, 3, 2, 1) if fits(c)), 1)
-        out = measured(head, args.steps, args.warmup, False, cpu)
-        # ... and the others follow in short (same recipe, fewer steps)
+        out = measured(head, args.steps, args.warmup, False, cpu, release=False)
+        per = {}
         if not args.no_per_config:
-            keys = ("value", "ms_per_step", "physical", "roofline", "kernels", "segments_ms")
-            per = {}
+            import subprocess
             for c in (1, 2, 3, 4, 5):
                 if c == head or not fits(c):
                     continue
-                # (the two small slabs take more, shorter steps: their kernels are tens of
-                # microseconds, and a dozen steps end before the clocks have settled)
-                small = c in (1, 2)
-                r = measured(c, 40 if small else max(4, args.steps // 2),
-                             10 if small else max(2, args.warmup), True,
-                             [1] if (c == 1 and cpu) else [])
-                e = {"workload": r["config"]["workload"],
-                     "iters_min": r["config"].get("iters_min"), "iters_max": r["config"].get("iters_max"),
-                     "mode": r["config"].get("mode")}
-                e.update({k: r[k] for k in keys if k in r})
-                if "streaming" in r:
-                    e["streaming"] = {k: r["streaming"][k] for k in ("ms_per_step", "roofline")}
-                for k in r:
-                    if k.startswith("cpu_baseline"):
-                        e[k] = r[k]
-                per[f"cfg{c}"] = e
+                cmd = [sys.executable, os.path.abspath(__file__), "--config", str(c), "--entry",
+                       "--steps", str(args.steps), "--warmup", str(args.warmup)]
+                if args.no_cpu_baseline:
+                    cmd.append("--no-cpu-baseline")
+                try:
+                    done = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE,
+                                          timeout=300, check=False)
+                    lines = [l for l in done.stdout.decode(errors="replace").splitlines()
+                             if l.startswith("{")]
+                    if done.returncode == 0 and lines:
+                        per[f"cfg{c}"] = json.loads(lines[-1])
+                    else:
+                        per[f"cfg{c}"] = {"error": f"exit status {done.returncode}",
+                                          "stderr": done.stderr.decode(errors="replace")[-400:]}
+                except subprocess.TimeoutExpired:
+                    per[f"cfg{c}"] = {"error": "no result within 300 s"}
+        if per:
             out["per_config"] = per
     print(json.dumps(out), flush=True)
     return 0
