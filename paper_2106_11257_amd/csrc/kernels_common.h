@@ -462,19 +462,40 @@ __device__ __forceinline__ double sum_across_groups(double a)
 // dealt round-robin to `tpq` threads per quantity (independent loads, a few each), whose
 // sums are then added in order.  Thread q < Q returns the total of quantity q.  The order
 // depends only on (B, Q, NT): results are reproducible.  s_red has NT entries.
+// (In two halves, so that a caller can put other work between the loads and the barriers.)
+constexpr int kPartialsInFlight = 16;
 template <int NT>
-__device__ __forceinline__ double reduce_partials(const double *__restrict__ pj, int B, int stride,
-                                                  int Q, double *s_red)
+__device__ __forceinline__ double reduce_partials_load(const double *__restrict__ pj, int B,
+                                                       int stride, int Q)
 {
     int tpq = NT / Q;
     if (tpq > 32) tpq = 32;
     const int t = threadIdx.x;
     const int s = t / Q, q = t - s * Q;
+    // (kPartialsInFlight loads at a time, added in order: one memory latency per group, not
+    // one per row.  A row beyond B counts as 0.0, which changes no sum.)
     double acc = 0.0;
     if (s < tpq) {
-#pragma unroll 4
-        for (int b = s; b < B; b += tpq) acc += pj[(int64_t)b * stride + q];
+        for (int b0 = s; b0 < B; b0 += kPartialsInFlight * tpq) {
+            double x[kPartialsInFlight];
+#pragma unroll
+            for (int k = 0; k < kPartialsInFlight; ++k) {
+                const int b = b0 + k * tpq;
+                x[k] = (b < B) ? pj[(int64_t)b * stride + q] : 0.0;
+            }
+#pragma unroll
+            for (int k = 0; k < kPartialsInFlight; ++k) acc += x[k];
+        }
     }
+    return acc;
+}
+
+template <int NT>
+__device__ __forceinline__ double reduce_partials_combine(double acc, int Q, double *s_red)
+{
+    int tpq = NT / Q;
+    if (tpq > 32) tpq = 32;
+    const int t = threadIdx.x;
     __syncthreads();
     s_red[t] = acc;
     __syncthreads();
@@ -482,6 +503,13 @@ __device__ __forceinline__ double reduce_partials(const double *__restrict__ pj,
     if (t < Q)
         for (int k = 0; k < tpq; ++k) tot += s_red[k * Q + t];
     return tot;
+}
+
+template <int NT>
+__device__ __forceinline__ double reduce_partials(const double *__restrict__ pj, int B, int stride,
+                                                  int Q, double *s_red)
+{
+    return reduce_partials_combine<NT>(reduce_partials_load<NT>(pj, B, stride, Q), Q, s_red);
 }
 
 }  // namespace btard

@@ -301,6 +301,11 @@ static __global__ __launch_bounds__(kFinishThreads) void verify_finish_kernel(Ve
     const int t = threadIdx.x;
     __shared__ double s_red[kFinishThreads];
     __shared__ double s_proj[256];
+    // quantity q < n: norm^2 of peer q; n <= q < 2n: <zhat, r> of peer q - n
+    // (with report: all S = 2n + 2 quantities, the last being ||last applied update||^2)
+    // (this partition's loads are issued first and travel while |zhat|^2 is summed)
+    const int Q = a.report ? S : 2 * n;
+    const double mine = reduce_partials_load<kFinishThreads>(a.partial + (int64_t)j * B * S, B, S, Q);
     double zz = 0.0;
     for (int64_t e = t; e < (int64_t)P * B; e += kFinishThreads) zz += a.partial[e * S + 2 * n];
     s_red[t] = zz;
@@ -311,11 +316,7 @@ static __global__ __launch_bounds__(kFinishThreads) void verify_finish_kernel(Ve
     }
     const double Z = sqrt(s_red[0]);
 
-    // quantity q < n: norm^2 of peer q; n <= q < 2n: <zhat, r> of peer q - n
-    // (with report: all S = 2n + 2 quantities, the last being ||last applied update||^2)
-    const int Q = a.report ? S : 2 * n;
-    const double tot = reduce_partials<kFinishThreads>(a.partial + (int64_t)j * B * S, B, S, Q,
-                                                       s_red);
+    const double tot = reduce_partials_combine<kFinishThreads>(mine, Q, s_red);
     __syncthreads();
     if (t < Q) s_red[t] = tot;
     __syncthreads();
