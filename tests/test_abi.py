@@ -158,3 +158,33 @@ def test_binding_constants_match_the_header():
     # the flags are distinct bits
     bits = [int(defines[k]) for k in flags if int(defines[k]) != 0]
     assert len(set(bits)) == len(bits) and all(b & (b - 1) == 0 for b in bits)
+
+
+def test_header_is_plain_c_and_a_c_program_calls_the_library(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 and as C++11 without warnings,
+    and a C program linked against the library calls a host entry point."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None or shutil.which("g++") is None:
+        pytest.skip("no host compiler")
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "caller.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "btard.h"\n'
+        "int main(void) {\n"
+        "    int64_t off[4];\n"
+        "    if (btard_split_offsets(10, 3, off) != 0) return 1;\n"
+        '    printf("%lld %lld %lld %lld\\n", (long long)off[0], (long long)off[1],\n'
+        "           (long long)off[2], (long long)off[3]);\n"
+        "    return btard_split_offsets(-1, 3, off) == -1 ? 0 : 2;\n"
+        "}\n")
+    flags = ["-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc]
+    subprocess.run(["gcc", "-std=c99", *flags, "-fsyntax-only", str(src)], check=True)
+    subprocess.run(["g++", "-std=c++11", *flags, "-fsyntax-only", "-x", "c++", str(src)], check=True)
+    btard.load_library()
+    libdir = os.path.dirname(binding._LIB_PATH)
+    exe = tmp_path / "caller"
+    subprocess.run(["gcc", "-std=c99", *flags, str(src), "-o", str(exe), "-L", libdir, "-lbtard",
+                    f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert [int(x) for x in out] == [0, 4, 7, 10]
